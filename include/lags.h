@@ -1,0 +1,115 @@
+/*
+ * lags.h - C ABI of the MI355X (gfx950) per-layer error-compensated top-k
+ * sparsifier of LAGS-SGD ("Layer-wise Adaptive Gradient Sparsification for
+ * Distributed Deep Learning with Convergence Guarantees").
+ *
+ * One worker's step for one layer l (Algorithm 1, lines 6-7; TopK is Eq. 4):
+ *     acc      = residual + lr * grad            (binary32, product rounded, then sum rounded)
+ *     selected = the k entries of largest |acc|  (equal magnitudes: lower index first)
+ *     out      = the (index, acc) pairs of the selected entries, index ascending
+ *     residual = acc with the selected entries set to +0.0f
+ * and the aggregation of P workers (Algorithm 1, lines 8-9; Eq. 5):
+ *     update   = (sum over p = 0..P-1, in that order, of worker p's selected entries) / P
+ *
+ * Conventions for every entry point
+ *   - Returns LAGS_OK (0) or a negative error code; never throws, never exits.
+ *   - Pointers named grad, residual, out_idx, out_val, idx, val, update are DEVICE
+ *     pointers owned by the caller; the library neither frees nor keeps them.
+ *     Everything else (descriptors, handles, out-parameters) is host memory.
+ *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL = the
+ *     default stream) and the call returns without waiting for it.
+ *   - Argument validation happens before anything is enqueued: on an error return
+ *     no output buffer has been touched.
+ *   - A context owns scratch memory only (histograms, counters, candidate lists);
+ *     nothing in it influences results.  One context serves one stream at a time:
+ *     calls on the same context must be ordered on one stream (or externally).
+ *   - Indices are 0-based, local to their layer, int32.
+ */
+#ifndef LAGS_H
+#define LAGS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct lags_ctx lags_ctx;     /* opaque: device id + scratch arena            */
+typedef struct lags_table lags_table; /* opaque: immutable prepared layer table       */
+
+/* One layer (a "segment" of the flat arrays).  Section 3, Eq. 2: the model vector is
+ * the concatenation of L layer vectors; a layer here is one tensor. */
+typedef struct {
+  int64_t offset; /* element offset of the layer in the flat grad/residual/update arrays, >= 0 */
+  int64_t d;      /* elements in the layer, 1 <= d < 2^31                                      */
+  double rho;     /* requested density k/d, 0 < rho <= 1 (the paper's 1/c, Section 4.2)        */
+} lags_layer_desc;
+
+enum {
+  LAGS_OK = 0,
+  LAGS_EINVAL = -1,   /* bad argument (null pointer, size or density out of range, overlap) */
+  LAGS_ENOMEM = -2,   /* host or device allocation failed                                   */
+  LAGS_EHIP = -3,     /* a HIP runtime call failed                                          */
+  LAGS_ECAPACITY = -4 /* a size exceeds what the library supports                           */
+};
+
+/* k = max(1, min(d, ceil(rho * d))) with the product evaluated in double.  The paper
+ * configures k per layer (Algorithm 1, input k^(l)); this is how a density becomes a k.
+ * Returns -1 if d < 1 or rho is not in (0, 1]. */
+int64_t lags_topk_count(int64_t d, double rho);
+
+/* Create / destroy a context on HIP device `device`.  Scratch grows when a table is
+ * created and is released by lags_destroy. */
+int lags_create(lags_ctx **out, int device);
+int lags_destroy(lags_ctx *ctx);
+
+/* Prepare a table of n >= 1 layers: derives k_l and the output position of each layer
+ * (layer l's pairs start at sum_{j<l} k_j), builds the launch plan, uploads it and sizes
+ * the context's scratch.  Layers must not overlap each other; gaps are allowed.
+ * `layers` is read during the call only.  A caller may list P workers x L layers of one
+ * flat buffer in a single table.  Synchronous (allocates and copies). */
+int lags_table_create(lags_ctx *ctx, const lags_layer_desc *layers, int32_t n, lags_table **out);
+int lags_table_destroy(lags_table *t);
+int32_t lags_table_num_layers(const lags_table *t);
+int64_t lags_table_total_k(const lags_table *t);              /* sum_l k_l = length of out_idx/out_val */
+int64_t lags_table_k(const lags_table *t, int32_t l);         /* -1 if l is out of range               */
+int64_t lags_table_out_offset(const lags_table *t, int32_t l);/* -1 if l is out of range               */
+
+/* Algorithm 1 lines 6-7 for ONE layer of d elements with a caller-chosen k (1 <= k <= d).
+ *   grad      device, float[d], read only
+ *   residual  device, float[d], read then overwritten with the new residual
+ *   out_idx   device, int32[k], written: selected indices, ascending
+ *   out_val   device, float[k], written: acc at those indices (bit exact)
+ * Buffers must not overlap.  `lr` must be finite. */
+int lags_sparsify_layer(lags_ctx *ctx, const float *grad, float *residual, int64_t d, float lr,
+                        int64_t k, int32_t *out_idx, float *out_val, void *hip_stream);
+
+/* Algorithm 1 lines 6-7 for every layer of a table in a few launches (the one-GPU
+ * analogue of Section 5's buffering of many small tensors).
+ *   grad_flat, residual_flat   device, float arrays covering every layer's [offset, offset+d)
+ *   out_idx, out_val           device, length lags_table_total_k(t); layer l's k_l pairs
+ *                              are at lags_table_out_offset(t, l)
+ * The table must have been created from the same context. */
+int lags_sparsify_model(lags_ctx *ctx, const lags_table *t, const float *grad_flat,
+                        float *residual_flat, float lr, int32_t *out_idx, float *out_val,
+                        void *hip_stream);
+
+/* Algorithm 1 lines 8-9 / Eq. 5: dense averaged update from P workers' sparse sets.
+ *   idx, val      device; worker p's pairs, laid out as lags_sparsify_model writes them for
+ *                 this table, start at idx + p*stride_k and val + p*stride_k
+ *                 (stride_k >= lags_table_total_k(t)); within a layer each worker's indices
+ *                 must be strictly ascending and in [0, d)
+ *   update_flat   device, float; every element of every layer is overwritten (sum in worker
+ *                 order starting from +0.0f, then one division by (float)P); elements
+ *                 outside all layers are left alone
+ *   1 <= P <= 1024.  The parameter step v -= update is the caller's. */
+int lags_merge_sparse(lags_ctx *ctx, const lags_table *t, const int32_t *idx, const float *val,
+                      int32_t P, int64_t stride_k, float *update_flat, void *hip_stream);
+
+/* Static, human-readable text for an error code. */
+const char *lags_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LAGS_H */

@@ -1,0 +1,136 @@
+"""Thin ctypes binding of liblags.so: same names as include/lags.h, argument
+marshalling only.  Torch tensors are used for device memory and streams; every
+step of the method runs inside the library's HIP kernels.  There is no CPU
+fallback: if the library is missing the import of a symbol fails loudly.
+"""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblags.so")
+
+LAGS_OK, LAGS_EINVAL, LAGS_ENOMEM, LAGS_EHIP, LAGS_ECAPACITY = 0, -1, -2, -3, -4
+
+
+class LayerDesc(ctypes.Structure):
+    _fields_ = [("offset", ctypes.c_int64), ("d", ctypes.c_int64), ("rho", ctypes.c_double)]
+
+
+_lib = None
+
+
+def lib():
+    """Load liblags.so (built beforehand by paper_1911_08727_amd.build); raises if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("liblags.so is not built: run `python -m paper_1911_08727_amd.build` "
+                               "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64, f32, dbl = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float, ctypes.c_double
+        L.lags_topk_count.restype, L.lags_topk_count.argtypes = i64, [i64, dbl]
+        L.lags_create.restype, L.lags_create.argtypes = ctypes.c_int, [ctypes.POINTER(vp), ctypes.c_int]
+        L.lags_destroy.restype, L.lags_destroy.argtypes = ctypes.c_int, [vp]
+        L.lags_table_create.restype = ctypes.c_int
+        L.lags_table_create.argtypes = [vp, ctypes.POINTER(LayerDesc), i32, ctypes.POINTER(vp)]
+        L.lags_table_destroy.restype, L.lags_table_destroy.argtypes = ctypes.c_int, [vp]
+        L.lags_table_num_layers.restype, L.lags_table_num_layers.argtypes = i32, [vp]
+        L.lags_table_total_k.restype, L.lags_table_total_k.argtypes = i64, [vp]
+        L.lags_table_k.restype, L.lags_table_k.argtypes = i64, [vp, i32]
+        L.lags_table_out_offset.restype, L.lags_table_out_offset.argtypes = i64, [vp, i32]
+        L.lags_sparsify_layer.restype = ctypes.c_int
+        L.lags_sparsify_layer.argtypes = [vp, vp, vp, i64, f32, i64, vp, vp, vp]
+        L.lags_sparsify_model.restype = ctypes.c_int
+        L.lags_sparsify_model.argtypes = [vp, vp, vp, vp, f32, vp, vp, vp]
+        L.lags_merge_sparse.restype = ctypes.c_int
+        L.lags_merge_sparse.argtypes = [vp, vp, vp, vp, i32, i64, vp, vp]
+        L.lags_strerror.restype, L.lags_strerror.argtypes = ctypes.c_char_p, [ctypes.c_int]
+        _lib = L
+    return _lib
+
+
+class LagsError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = code
+        super().__init__("%s: %s (%d)" % (where, lib().lags_strerror(code).decode(), code))
+
+
+def _check(code, where):
+    if code != LAGS_OK:
+        raise LagsError(code, where)
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else ctypes.c_void_p(0)
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def lags_topk_count(d, rho):
+    return int(lib().lags_topk_count(int(d), float(rho)))
+
+
+class Table:
+    """Handle of a prepared layer table (lags_table_create / lags_table_destroy)."""
+
+    def __init__(self, ctx, layers):
+        self.ctx = ctx
+        arr = (LayerDesc * len(layers))()
+        for i, (offset, d, rho) in enumerate(layers):
+            arr[i].offset, arr[i].d, arr[i].rho = int(offset), int(d), float(rho)
+        h = ctypes.c_void_p(0)
+        _check(lib().lags_table_create(ctx.handle, arr, len(layers), ctypes.byref(h)), "lags_table_create")
+        self.handle = h
+        self.n = len(layers)
+
+    @property
+    def total_k(self):
+        return int(lib().lags_table_total_k(self.handle))
+
+    def k(self, l):
+        return int(lib().lags_table_k(self.handle, l))
+
+    def out_offset(self, l):
+        return int(lib().lags_table_out_offset(self.handle, l))
+
+    def destroy(self):
+        if self.handle:
+            lib().lags_table_destroy(self.handle)
+            self.handle = None
+
+
+class Context:
+    """Handle of a library context (lags_create / lags_destroy) on one HIP device."""
+
+    def __init__(self, device=0):
+        h = ctypes.c_void_p(0)
+        _check(lib().lags_create(ctypes.byref(h), int(device)), "lags_create")
+        self.handle = h
+        self.device = device
+
+    def table(self, layers):
+        return Table(self, layers)
+
+    def lags_sparsify_layer(self, grad, residual, lr, k, out_idx, out_val, stream=None):
+        _check(lib().lags_sparsify_layer(self.handle, _ptr(grad), _ptr(residual), grad.numel(), float(lr),
+                                         int(k), _ptr(out_idx), _ptr(out_val), _stream(stream)),
+               "lags_sparsify_layer")
+
+    def lags_sparsify_model(self, table, grad_flat, residual_flat, lr, out_idx, out_val, stream=None):
+        _check(lib().lags_sparsify_model(self.handle, table.handle, _ptr(grad_flat), _ptr(residual_flat),
+                                         float(lr), _ptr(out_idx), _ptr(out_val), _stream(stream)),
+               "lags_sparsify_model")
+
+    def lags_merge_sparse(self, table, idx, val, P, stride_k, update_flat, stream=None):
+        _check(lib().lags_merge_sparse(self.handle, table.handle, _ptr(idx), _ptr(val), int(P), int(stride_k),
+                                       _ptr(update_flat), _stream(stream)), "lags_merge_sparse")
+
+    def destroy(self):
+        if self.handle:
+            lib().lags_destroy(self.handle)
+            self.handle = None

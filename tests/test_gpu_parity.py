@@ -1,0 +1,244 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, bit for bit,
+on the same seeded inputs.  Bar: indices, values, residuals and the merged update are
+integer/bit identical (the arithmetic is two binary32 roundings on both sides; where a
+float decides the selection both sides decide on the same binary32 acc bits)."""
+import zlib
+
+import numpy as np
+import pytest
+
+from gpu_util import Gpu, assert_same, bits, note, oracle_model_parallel
+from paper_1911_08727_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    g = Gpu()
+    yield g
+    g.close()
+
+
+def _values(kind, d, rng):
+    if kind == "normal":
+        return rng.standard_normal(d).astype(np.float32)
+    if kind == "ties":
+        return rng.integers(-3, 4, d).astype(np.float32)
+    if kind == "zeros":
+        return np.zeros(d, np.float32)
+    if kind == "equal":
+        return np.full(d, -2.5, np.float32)
+    if kind == "signed_zeros":
+        return np.where(rng.random(d) < 0.5, np.float32(0.0), np.float32(-0.0)).astype(np.float32)
+    if kind == "denormal":
+        return (rng.integers(-50, 51, d).astype(np.float64) * 2.0 ** -149).astype(np.float32)
+    if kind == "mostly_zero":
+        x = rng.standard_normal(d).astype(np.float32)
+        x[rng.random(d) < 0.9] = 0.0
+        return x
+    if kind == "narrow":          # all magnitudes inside one top-level radix bin
+        return (1.0 + rng.random(d) * 0.01).astype(np.float32) * rng.choice([-1, 1], d).astype(np.float32)
+    if kind == "inf":
+        x = rng.standard_normal(d).astype(np.float32)
+        x[rng.integers(0, d, max(1, d // 50))] = np.inf
+        x[rng.integers(0, d, max(1, d // 50))] = -np.inf
+        return x
+    raise KeyError(kind)
+
+
+KINDS = ["normal", "ties", "zeros", "equal", "signed_zeros", "denormal", "mostly_zero", "narrow", "inf"]
+# sizes around every boundary of the launch plan: vector width, wave, small classes, tile
+SIZES = [1, 2, 3, 4, 5, 63, 64, 65, 255, 256, 257, 1023, 1024, 1025, 4100, 8191, 8192, 8193,
+         40959, 40960, 40961, 3 * 8192, 3 * 8192 + 5, 100003]
+
+
+def _ks(d, rng):
+    ks = {1, d, max(1, d // 2), max(1, int(np.ceil(0.001 * d))), max(1, int(np.ceil(0.01 * d)))}
+    if d > 3:
+        ks.add(int(rng.integers(2, d)))
+    return sorted(ks)
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_single_layer_edges(gpu, oracle, kind):
+    """lags_sparsify_layer on crafted layers at every size boundary and several k."""
+    rng = np.random.default_rng(zlib.crc32(kind.encode()))
+    lr = np.float32(0.3)
+    for d in SIZES:
+        g = _values(kind, d, rng)
+        r0 = (_values(kind, d, rng) * np.float32(0.5)).astype(np.float32)
+        if kind == "inf":
+            r0[~np.isfinite(r0)] = 1.0          # keep acc free of inf - inf
+            r0[~np.isfinite(g)] = 0.0
+        for k in _ks(d, rng):
+            note("edges kind=%s d=%d k=%d" % (kind, d, k))
+            want_r = r0.copy()
+            wi, wv = oracle.sparsify_layer(g, want_r, lr, k)
+            gi, gv, gr = gpu.sparsify_layer(g, r0, lr, k)
+            assert_same("idx %s d=%d k=%d" % (kind, d, k), gi, wi)
+            assert_same("val %s d=%d k=%d" % (kind, d, k), gv, wv)
+            assert_same("res %s d=%d k=%d" % (kind, d, k), gr, want_r)
+
+
+def test_fma_would_differ(gpu, oracle):
+    """The accumulate is a rounded product then a rounded sum: inputs where a fused
+    multiply-add gives other bits (and another selection) must match the oracle."""
+    d = 5000
+    rng = np.random.default_rng(3)
+    g = rng.standard_normal(d).astype(np.float32)
+    r0 = (-np.float32(0.1) * g).astype(np.float32)      # acc is exactly the product's rounding error...
+    r0[::7] += np.float32(1e-9)
+    g[0], r0[0] = 3.0, -0.3                              # the hand-worked element: acc == +0.0
+    want_r = r0.copy()
+    wi, wv = oracle.sparsify_layer(g, want_r, np.float32(0.1), 40)
+    gi, gv, gr = gpu.sparsify_layer(g, r0, np.float32(0.1), 40)
+    assert bits(gr)[0] == 0
+    assert_same("idx", gi, wi)
+    assert_same("val", gv, wv)
+    assert_same("res", gr, want_r)
+
+
+def test_unaligned_offsets_and_gaps(gpu, oracle):
+    """Layers at arbitrary element offsets (not multiples of 4), with gaps between them."""
+    rng = np.random.default_rng(8)
+    sizes = [7, 1, 300, 1025, 9000, 41001, 70001, 13]
+    layers, off = [], 3
+    for d in sizes:
+        layers.append((off, d, float(rng.choice([0.001, 0.01, 0.3, 1.0]))))
+        off += d + int(rng.integers(0, 6))
+    total = off + 5
+    g = rng.standard_normal(total).astype(np.float32)
+    r0 = rng.standard_normal(total).astype(np.float32)
+    note("unaligned offsets")
+    want_r = r0.copy()
+    wi, wv = oracle.sparsify_model(layers, g, want_r, 0.05)
+    gi, gv, gr = gpu.sparsify_model(layers, g, r0, 0.05)
+    assert_same("idx", gi, wi)
+    assert_same("val", gv, wv)
+    assert_same("res", gr, want_r)            # includes the untouched gaps
+
+
+def test_nan_inputs_select_same_indices(gpu, oracle):
+    """NaN keys rank above infinity on both sides; NaN payloads are not compared."""
+    d = 3000
+    rng = np.random.default_rng(12)
+    g = rng.standard_normal(d).astype(np.float32)
+    g[[5, 77, 2048]] = np.nan
+    r0 = np.zeros(d, np.float32)
+    want_r = r0.copy()
+    wi, _ = oracle.sparsify_layer(g, want_r, 1.0, 10)
+    gi, gv, gr = gpu.sparsify_layer(g, r0, 1.0, 10)
+    assert_same("idx", gi, wi)
+    assert np.isnan(gv[np.isin(gi, [5, 77, 2048])]).all()
+    assert_same("res", gr, want_r)
+
+
+def _run_config(gpu, oracle, wl, iters, P, check_merge=True):
+    layers = wl.layers()
+    total = wl.total_d
+    table = gpu.ctx.table(layers)
+    K = table.total_k
+    assert K == oracle.total_k(layers)
+    res_gpu = [np.zeros(total, np.float32) for _ in range(P)]
+    res_cpu = [np.zeros(total, np.float32) for _ in range(P)]
+    for it in range(iters):
+        all_i = np.empty(P * K, np.int32)
+        all_v = np.empty(P * K, np.float32)
+        for p in range(P):
+            note("config %s iteration %d worker %d" % (wl.name, it, p))
+            g = workloads.grad_numpy(wl, it, p)
+            gi, gv, gr = gpu.sparsify_model(layers, g, res_gpu[p], wl.lr, table=table)
+            wi, wv = oracle_model_parallel(oracle, layers, g, res_cpu[p], wl.lr)
+            assert_same("idx it=%d p=%d" % (it, p), gi, wi)
+            assert_same("val it=%d p=%d" % (it, p), gv, wv)
+            assert_same("res it=%d p=%d" % (it, p), gr, res_cpu[p])
+            res_gpu[p] = gr
+            all_i[p * K:(p + 1) * K] = gi
+            all_v[p * K:(p + 1) * K] = gv
+        if check_merge:
+            note("config %s iteration %d merge" % (wl.name, it))
+            want_u = np.full(total, 123.0, np.float32)
+            oracle.merge_sparse(layers, all_i, all_v, P, K, want_u)
+            got_u = gpu.merge(layers, all_i, all_v, P, K, total, table=table)
+            assert_same("update it=%d" % it, got_u, want_u)
+    table.destroy()
+
+
+def test_config_single_tensor(gpu, oracle):
+    """Benchmark configuration 1 in full: d = 2^20, k = 1049, P = 4, 10 iterations."""
+    wl = workloads.make("single")
+    _run_config(gpu, oracle, wl, wl.iters, wl.P)
+
+
+def test_config_resnet20(gpu, oracle):
+    """Benchmark configuration 2 in full: 58 tensors, P = 16, 20 iterations."""
+    wl = workloads.make("resnet20")
+    _run_config(gpu, oracle, wl, wl.iters, wl.P)
+
+
+def test_config_resnet50_reduced(gpu, oracle):
+    """Configuration 4's full table; 2 workers x 3 iterations against the full oracle
+    (the full worker and iteration counts run in test_gpu_fullsize.py on sampled layers)."""
+    wl = workloads.make("resnet50")
+    _run_config(gpu, oracle, wl, 3, 2)
+
+
+def test_merge_closed_forms(gpu, oracle):
+    """P = 1 is a scatter; many workers on one index sum in worker order; division is a
+    true division (P = 3, 7); indices spread over several merge tiles; P > 64."""
+    rng = np.random.default_rng(31)
+    layers = [(0, 20000, 0.01), (20004, 9, 0.5), (20013, 70000, 0.002)]
+    total = 20013 + 70000
+    K = oracle.total_k(layers)
+    for P in (1, 3, 7, 16, 70):
+        idx = np.empty(P * K, np.int32)
+        val = (rng.standard_normal(P * K) * 10.0 ** rng.integers(-8, 8, P * K)).astype(np.float32)
+        for p in range(P):
+            pos = 0
+            for (_, d, rho) in layers:
+                k = oracle.topk_count(d, rho)
+                hot = np.arange(k // 2)                       # shared by all workers -> P-term sums
+                rest = rng.choice(np.arange(k // 2, d), k - k // 2, replace=False)
+                idx[p * K + pos:p * K + pos + k] = np.sort(np.concatenate([hot, rest]))
+                pos += k
+        note("merge closed forms P=%d" % P)
+        want = np.full(total, 123.0, np.float32)
+        oracle.merge_sparse(layers, idx, val, P, K, want)
+        got = gpu.merge(layers, idx, val, P, K, total)
+        assert_same("update P=%d" % P, got, want)
+
+
+def test_determinism_and_scratch_independence(gpu, oracle):
+    """Same inputs twice, with another table's work in between, give the same bits."""
+    rng = np.random.default_rng(41)
+    layers = [(0, 300000, 0.003), (300000, 50000, 0.01), (350000, 500, 0.1)]
+    total = 350500
+    g = rng.standard_normal(total).astype(np.float32)
+    r0 = rng.standard_normal(total).astype(np.float32)
+    a = gpu.sparsify_model(layers, g, r0, 0.1)
+    gpu.sparsify_layer(rng.standard_normal(123457).astype(np.float32), np.zeros(123457, np.float32), 1.0, 999)
+    b = gpu.sparsify_model(layers, g, r0, 0.1)
+    for x, y, n in zip(a, b, ("idx", "val", "res")):
+        assert_same(n, x, y)
+
+
+def test_invalid_arguments_leave_outputs_untouched(gpu):
+    import torch
+    from paper_1911_08727_amd import lags
+    t = torch
+    g = t.zeros(100, device=gpu.dev)
+    r = t.ones(100, device=gpu.dev)
+    oi = t.full((5,), -7, dtype=t.int32, device=gpu.dev)
+    ov = t.full((5,), 9.0, device=gpu.dev)
+    for kwargs in (dict(k=0), dict(k=101), dict(lr=float("inf")), dict(lr=float("nan"))):
+        with pytest.raises(lags.LagsError):
+            gpu.ctx.lags_sparsify_layer(g, r, kwargs.get("lr", 0.1), kwargs.get("k", 5), oi, ov)
+    with pytest.raises(lags.LagsError):                       # grad and residual overlap
+        gpu.ctx.lags_sparsify_layer(g, g, 0.1, 5, oi, ov)
+    with pytest.raises(lags.LagsError):                       # overlapping layers
+        gpu.ctx.table([(0, 10, 0.1), (5, 10, 0.1)])
+    with pytest.raises(lags.LagsError):                       # density outside (0, 1]
+        gpu.ctx.table([(0, 10, 0.0)])
+    t.cuda.synchronize()
+    assert (oi == -7).all() and (ov == 9.0).all() and (r == 1.0).all()
