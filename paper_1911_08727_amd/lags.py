@@ -26,6 +26,9 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise RuntimeError("liblags.so is not built: run `python -m paper_1911_08727_amd.build` "
                                "(there is no fallback path)")
+        # torch ships its own HIP runtime; it must be the one already mapped when liblags.so
+        # resolves libamdhip64, or the process ends up with two runtimes and no usable device
+        import torch  # noqa: F401
         L = ctypes.CDLL(LIB_PATH)
         vp, i32, i64, f32, dbl = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float, ctypes.c_double
         L.lags_topk_count.restype, L.lags_topk_count.argtypes = i64, [i64, dbl]
