@@ -1,0 +1,178 @@
+#!/usr/bin/env python3
+"""Benchmark of the LAGS-SGD hot path on one MI355X.
+
+One step = one pass of the whole path over one batch of synthetic gradients that are
+already resident in HBM: the per-layer error-compensated top-k sparsifier for all P
+workers of the workload (one batched lags_sparsify_model call over P x L layers) and
+the merge of the P sparse sets into the dense averaged update (lags_merge_sparse).
+
+Prints ONE JSON line: sparsified elements/s (whole job), the roofline of the dominant
+kernel from HIP-event timings taken inside the timed region, and the CPU oracle timed
+on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
+
+
+def cpu_baseline(wl, grad0_host, threads):
+    """The oracle as it stands on the host cores: worker 0, one iteration, every layer,
+    layers spread over `threads` host threads."""
+    import concurrent.futures as cf
+    import numpy as np
+    import oracle
+    layers = wl.layers()
+    res = np.zeros(wl.total_d, np.float32)
+    ks = [oracle.topk_count(d, rho) for (_, d, rho) in layers]
+
+    def one(l):
+        off, d, _ = layers[l]
+        oracle.sparsify_layer(np.ascontiguousarray(grad0_host[off:off + d]), res[off:off + d], wl.lr, ks[l])
+
+    order = sorted(range(len(layers)), key=lambda l: -layers[l][1])
+    t0 = time.perf_counter()
+    with cf.ThreadPoolExecutor(threads) as ex:
+        list(ex.map(one, order))
+    dt = time.perf_counter() - t0
+    return wl.total_d / dt, dt
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="vgg16", help="single|resnet20|vgg16|resnet50|lstm")
+    ap.add_argument("--rho", default="0.001", help="density for every layer, or 'config' for the workload's own")
+    ap.add_argument("--workers", type=int, default=0, help="simulated workers P (0 = the workload's)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain device copy of 1 GiB (for scaling rocprofv3 byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the path has no inter-GPU step); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_1911_08727_amd import lags, workloads
+
+    dev = torch.device("cuda:0")
+    if args.calibrate_copy:
+        n = 1 << 28
+        a = torch.ones(n, dtype=torch.float32, device=dev)
+        b = torch.empty_like(a)
+        for _ in range(args.steps):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration": "plain copy", "bytes_read": n * 4, "bytes_written": n * 4,
+                          "launches": args.steps}))
+        return
+
+    rho = None if args.rho == "config" else float(args.rho)
+    wl = workloads.make(args.workload, rho_override=rho)
+    P = args.workers or wl.P
+    total = wl.total_d
+    layers = wl.layers()
+    batched = [(p * total + off, d, r) for p in range(P) for (off, d, r) in layers]
+
+    ctx = lags.Context(0)
+    table_b = ctx.table(batched)      # P x L layers: one sparsify call per step
+    table_1 = ctx.table(layers)       # one worker's layout: the merge
+    K = table_1.total_k
+    assert table_b.total_k == P * K
+
+    grad = torch.empty(P * total, dtype=torch.float32, device=dev)
+    for p in range(P):
+        workloads.grad_torch(wl, 0, p, dev, out=grad[p * total:(p + 1) * total])
+    res = torch.zeros(P * total, dtype=torch.float32, device=dev)
+    idx = torch.empty(P * K, dtype=torch.int32, device=dev)
+    val = torch.empty(P * K, dtype=torch.float32, device=dev)
+    upd = torch.empty(total, dtype=torch.float32, device=dev)
+    grad0_host = None if args.no_cpu_baseline else grad[:total].cpu().numpy()
+    stream = torch.cuda.current_stream()
+
+    def step():
+        ctx.lags_sparsify_model(table_b, grad, res, wl.lr, idx, val, stream)
+        ctx.lags_merge_sparse(table_1, idx, val, P, K, upd, stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ctx.lags_profile_reset()
+    ctx.lags_profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ctx.lags_profile_enable(False)
+    prof = ctx.lags_profile_read()
+    ctx.lags_profile_reset()
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    elements = P * total
+    value = elements / (ms_per_step * 1e-3)
+
+    # dominant kernel = largest total time; its algorithmic bytes per launch
+    rho_mean = float(K) / float(total)
+    kel = dict(table_b.kernel_elements())
+    kel.update({k: v for k, v in table_1.kernel_elements().items() if k == "k_merge"})
+    dom = max(prof, key=lambda k: prof[k][0])
+    dom_ms = prof[dom][0] / prof[dom][1]
+    launches_per_step = prof[dom][1] / args.steps
+    if dom == "k_merge":
+        bpe = 4.0 + 8.0 * P * rho_mean
+    else:
+        bpe = 12.0 + 8.0 * rho_mean
+    # a kernel launched several times per step (e.g. k_hist) shares the per-step algorithmic bytes
+    achieved = bpe * kel.get(dom, elements) / (dom_ms * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "avg_kernel_ms": round(dom_ms, 4), "launches_per_step": launches_per_step,
+                "bytes_per_element": round(bpe, 4), "elements_per_launch": kel.get(dom, elements)}
+    kernels = {k: {"ms_per_step": round(v[0] / args.steps, 4), "launches_per_step": v[1] / args.steps}
+               for k, v in sorted(prof.items(), key=lambda kv: -kv[1][0])}
+    sparsify_ms = sum(v[0] for k, v in prof.items() if k != "k_merge") / args.steps
+    merge_ms = prof.get("k_merge", (0.0, 0))[0] / args.steps
+
+    out = {
+        "metric": "sparsified elements/s, per-layer top-k + error feedback (P workers) + merge",
+        "value": value, "unit": "elements/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": wl.name, "layers": len(layers), "elements_per_worker": total, "workers": P,
+                   "sum_k_per_worker": K, "lr": wl.lr, "distribution": wl.dist},
+        "algorithmic_gbs": {"sparsify": round((12.0 + 8.0 * rho_mean) * elements / (sparsify_ms * 1e-3) / 1e9, 1)
+                            if sparsify_ms > 0 else None,
+                            "merge": round((4.0 + 8.0 * P * rho_mean) * total / (merge_ms * 1e-3) / 1e9, 1)
+                            if merge_ms > 0 else None,
+                            "sparsify_frac_of_peak": round((12.0 + 8.0 * rho_mean) * elements /
+                                                           (sparsify_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+                            if sparsify_ms > 0 else None},
+        "kernels": kernels,
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        threads = min(16, os.cpu_count() or 1)
+        v, dt = cpu_baseline(wl, grad0_host, threads)
+        out["cpu_baseline"] = {"value": v, "unit": "elements/s", "cores": threads, "kind": "oracle",
+                               "sample": "worker 0 of %d, one iteration, all %d layers (%d elements), "
+                                         "%.1f s wall" % (P, len(layers), total, dt)}
+    print(json.dumps(out))
+    table_b.destroy()
+    table_1.destroy()
+    ctx.destroy()
+
+
+if __name__ == "__main__":
+    main()

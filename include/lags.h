@@ -106,6 +106,21 @@ int lags_sparsify_model(lags_ctx *ctx, const lags_table *t, const float *grad_fl
 int lags_merge_sparse(lags_ctx *ctx, const lags_table *t, const int32_t *idx, const float *val,
                       int32_t P, int64_t stride_k, float *update_flat, void *hip_stream);
 
+/* Optional per-kernel timing with HIP events recorded on the caller's stream (measurement
+ * aid; off by default; no effect on results).  While enabled every kernel launch of this
+ * context is bracketed by a pair of events.  lags_profile_read waits for all recorded
+ * events, adds the elapsed milliseconds and launch count of kernel `kernel_id`
+ * (0 <= kernel_id < lags_profile_num_kernels()) to *total_ms / *launches, and
+ * lags_profile_reset drops everything recorded so far.  All three are host-synchronous. */
+int lags_profile_enable(lags_ctx *ctx, int on);
+int lags_profile_num_kernels(void);
+const char *lags_profile_kernel_name(int kernel_id); /* NULL if out of range */
+int lags_profile_read(lags_ctx *ctx, int kernel_id, double *total_ms, int64_t *launches);
+int lags_profile_reset(lags_ctx *ctx);
+/* Number of layer elements one launch of kernel `kernel_id` covers for table `t` (0 if that
+ * kernel is not launched for it): the unit count for bytes-per-launch arithmetic. */
+int64_t lags_profile_kernel_elements(const lags_table *t, int kernel_id);
+
 /* Static, human-readable text for an error code. */
 const char *lags_strerror(int code);
 

@@ -20,6 +20,7 @@ struct lags_ctx {
   SegState* state = nullptr;   int64_t state_cap = 0;    // n_large
   uint32_t* tile_gt = nullptr; uint32_t* tile_eq = nullptr; int64_t tile_cap = 0;  // n_tiles
   std::map<std::pair<int64_t, int64_t>, lags_table*> layer_tables;  // (d, k) -> one-layer table
+  Prof prof;
 };
 
 struct lags_table {
@@ -190,11 +191,11 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
 int run_sparsify(lags_ctx* ctx, const lags_table* t, const float* grad, float* res, float lr,
                  int32_t* out_idx, float* out_val, hipStream_t s) {
   for (int c = 0; c < 3; ++c) {
-    if (launch_small(c, t->n_small[c], t->d_segs, t->d_small[c], grad, res, lr, out_idx, out_val, s) != hipSuccess)
+    if (launch_small(c, t->n_small[c], t->d_segs, t->d_small[c], grad, res, lr, out_idx, out_val, s, &ctx->prof) != hipSuccess)
       return LAGS_EHIP;
   }
   if (launch_large(t->n_large, t->n_tiles, t->d_segs, t->d_lsegs, t->d_tiles, grad, res, lr, out_idx,
-                   out_val, ctx->ghist, ctx->state, ctx->tile_gt, ctx->tile_eq, s) != hipSuccess)
+                   out_val, ctx->ghist, ctx->state, ctx->tile_gt, ctx->tile_eq, s, &ctx->prof) != hipSuccess)
     return LAGS_EHIP;
   return LAGS_OK;
 }
@@ -227,6 +228,7 @@ int lags_create(lags_ctx** out, int device) {
 int lags_destroy(lags_ctx* ctx) {
   if (!ctx) return LAGS_EINVAL;
   DeviceGuard g(ctx->device);
+  (void)lags_profile_reset(ctx);
   for (auto& kv : ctx->layer_tables) {
     free_table_device(kv.second);
     delete kv.second;
@@ -339,9 +341,64 @@ int lags_merge_sparse(lags_ctx* ctx, const lags_table* t, const int32_t* idx, co
   DeviceGuard g(ctx->device);
   if (!g.ok) return LAGS_EHIP;
   if (launch_merge(t->n_mtiles, t->d_mtiles, t->d_segs, idx, val, P, stride_k, update_flat,
-                   (hipStream_t)hip_stream) != hipSuccess)
+                   (hipStream_t)hip_stream, &ctx->prof) != hipSuccess)
     return LAGS_EHIP;
   return LAGS_OK;
+}
+
+int lags_profile_enable(lags_ctx* ctx, int on) {
+  if (!ctx) return LAGS_EINVAL;
+  ctx->prof.on = on != 0;
+  return LAGS_OK;
+}
+
+int lags_profile_num_kernels(void) { return K_NUM; }
+
+const char* lags_profile_kernel_name(int kernel_id) { return kernel_name(kernel_id); }
+
+int lags_profile_read(lags_ctx* ctx, int kernel_id, double* total_ms, int64_t* launches) {
+  if (!ctx || !total_ms || !launches || kernel_id < 0 || kernel_id >= K_NUM) return LAGS_EINVAL;
+  DeviceGuard g(ctx->device);
+  for (const Prof::Rec& r : ctx->prof.recs) {
+    if (r.id != kernel_id) continue;
+    float ms = 0.f;
+    if (hipEventSynchronize(r.b) != hipSuccess || hipEventElapsedTime(&ms, r.a, r.b) != hipSuccess) return LAGS_EHIP;
+    *total_ms += (double)ms;
+    *launches += 1;
+  }
+  return LAGS_OK;
+}
+
+int lags_profile_reset(lags_ctx* ctx) {
+  if (!ctx) return LAGS_EINVAL;
+  DeviceGuard g(ctx->device);
+  for (const Prof::Rec& r : ctx->prof.recs) {
+    (void)hipEventSynchronize(r.b);
+    (void)hipEventDestroy(r.a);
+    (void)hipEventDestroy(r.b);
+  }
+  ctx->prof.recs.clear();
+  return LAGS_OK;
+}
+
+int64_t lags_profile_kernel_elements(const lags_table* t, int kernel_id) {
+  if (!t) return -1;
+  int64_t small[3] = {0, 0, 0}, large = 0, all = 0;
+  for (const SegDesc& sd : t->segs) {
+    all += sd.d;
+    if (sd.d <= kSmall0) small[0] += sd.d;
+    else if (sd.d <= kSmall1) small[1] += sd.d;
+    else if (sd.d <= kSmall2) small[2] += sd.d;
+    else large += sd.d;
+  }
+  switch (kernel_id) {
+    case K_SMALL0: return small[0];
+    case K_SMALL1: return small[1];
+    case K_SMALL2: return small[2];
+    case K_ACCUM_HIST: case K_HIST: case K_COUNT: case K_EMIT: return large;
+    case K_MERGE: return all;
+    default: return 0;
+  }
 }
 
 const char* lags_strerror(int code) {

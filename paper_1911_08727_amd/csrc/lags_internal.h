@@ -3,6 +3,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <vector>
 
 namespace lags {
 
@@ -52,15 +53,40 @@ struct SegState {       // radix-select state of one large layer
   uint32_t k_rem;       // entries still to take among keys matching the prefix
 };
 
+// Kernel ids for the optional event timing.
+enum KernelId {
+  K_ZERO = 0, K_SMALL0, K_SMALL1, K_SMALL2, K_ACCUM_HIST, K_CHOOSE, K_HIST, K_COUNT, K_SCAN, K_EMIT,
+  K_MERGE, K_NUM
+};
+const char* kernel_name(int id);
+
+struct Prof {
+  bool on = false;
+  struct Rec { int id; hipEvent_t a, b; };
+  std::vector<Rec> recs;
+};
+
+// Brackets one kernel launch with events when profiling is on.
+struct ProfScope {
+  Prof* p; hipStream_t s; hipEvent_t a = nullptr, b = nullptr; int id;
+  ProfScope(Prof* prof, int kid, hipStream_t st) : p(prof && prof->on ? prof : nullptr), s(st), id(kid) {
+    if (p && hipEventCreate(&a) == hipSuccess && hipEventCreate(&b) == hipSuccess) (void)hipEventRecord(a, s);
+    else p = nullptr;
+  }
+  ~ProfScope() {
+    if (p) { (void)hipEventRecord(b, s); p->recs.push_back(Prof::Rec{id, a, b}); }
+  }
+};
+
 // Launch wrappers (lags_kernels.hip).  All enqueue on `s` and return the launch status.
-hipError_t launch_zero_u32(uint32_t* p, int64_t n, hipStream_t s);
+hipError_t launch_zero_u32(uint32_t* p, int64_t n, hipStream_t s, Prof* prof);
 hipError_t launch_small(int cls, int nseg, const SegDesc* segs, const int32_t* list, const float* grad,
-                        float* res, float lr, int32_t* out_idx, float* out_val, hipStream_t s);
+                        float* res, float lr, int32_t* out_idx, float* out_val, hipStream_t s, Prof* prof);
 hipError_t launch_large(int n_large, int n_tiles, const SegDesc* segs, const LargeSeg* lsegs,
                         const TileDesc* tiles, const float* grad, float* res, float lr,
                         int32_t* out_idx, float* out_val, uint32_t* ghist, SegState* state,
-                        uint32_t* tile_gt, uint32_t* tile_eq, hipStream_t s);
+                        uint32_t* tile_gt, uint32_t* tile_eq, hipStream_t s, Prof* prof);
 hipError_t launch_merge(int n_tiles, const TileDesc* mtiles, const SegDesc* segs, const int32_t* idx,
-                        const float* val, int P, int64_t stride_k, float* update, hipStream_t s);
+                        const float* val, int P, int64_t stride_k, float* update, hipStream_t s, Prof* prof);
 
 }  // namespace lags

@@ -563,17 +563,26 @@ __global__ __launch_bounds__(256) void k_merge(const TileDesc* __restrict__ mtil
 }
 
 // ------------------------------------------------------------------ launch ---
-hipError_t launch_zero_u32(uint32_t* p, int64_t n, hipStream_t s) {
+const char* kernel_name(int id) {
+  static const char* names[K_NUM] = {"k_zero_u32", "k_small<4,1>", "k_small<4,8>", "k_small<16,10>",
+                                     "k_accum_hist", "k_choose", "k_hist", "k_count", "k_scan", "k_emit",
+                                     "k_merge"};
+  return (id >= 0 && id < K_NUM) ? names[id] : nullptr;
+}
+
+hipError_t launch_zero_u32(uint32_t* p, int64_t n, hipStream_t s, Prof* prof) {
   if (n <= 0) return hipSuccess;
   int64_t blocks = (n + 255) / 256;
   if (blocks > 4096) blocks = 4096;
+  ProfScope ps(prof, K_ZERO, s);
   hipLaunchKernelGGL(k_zero_u32, dim3((unsigned)blocks), dim3(256), 0, s, p, n);
   return hipGetLastError();
 }
 
 hipError_t launch_small(int cls, int nseg, const SegDesc* segs, const int32_t* list, const float* grad,
-                        float* res, float lr, int32_t* out_idx, float* out_val, hipStream_t s) {
+                        float* res, float lr, int32_t* out_idx, float* out_val, hipStream_t s, Prof* prof) {
   if (nseg <= 0) return hipSuccess;
+  ProfScope ps(prof, K_SMALL0 + cls, s);
   if (cls == 0)
     hipLaunchKernelGGL((k_small<4, 1>), dim3(nseg), dim3(256), 0, s, segs, list, grad, res, lr, out_idx, out_val);
   else if (cls == 1)
@@ -586,26 +595,45 @@ hipError_t launch_small(int cls, int nseg, const SegDesc* segs, const int32_t* l
 hipError_t launch_large(int n_large, int n_tiles, const SegDesc* segs, const LargeSeg* lsegs,
                         const TileDesc* tiles, const float* grad, float* res, float lr,
                         int32_t* out_idx, float* out_val, uint32_t* ghist, SegState* state,
-                        uint32_t* tile_gt, uint32_t* tile_eq, hipStream_t s) {
+                        uint32_t* tile_gt, uint32_t* tile_eq, hipStream_t s, Prof* prof) {
   if (n_large <= 0) return hipSuccess;
-  hipError_t e = launch_zero_u32(ghist, (int64_t)n_large * kHistStride, s);
+  hipError_t e = launch_zero_u32(ghist, (int64_t)n_large * kHistStride, s, prof);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(k_accum_hist, dim3(n_tiles), dim3(256), 0, s, tiles, grad, res, lr, ghist);
-  hipLaunchKernelGGL(k_choose, dim3(n_large), dim3(256), 0, s, 0, lsegs, segs, ghist, state);
-  hipLaunchKernelGGL(k_hist<1>, dim3(n_tiles), dim3(256), 0, s, tiles, res, state, ghist);
-  hipLaunchKernelGGL(k_choose, dim3(n_large), dim3(256), 0, s, 1, lsegs, segs, ghist, state);
-  hipLaunchKernelGGL(k_hist<2>, dim3(n_tiles), dim3(256), 0, s, tiles, res, state, ghist);
-  hipLaunchKernelGGL(k_choose, dim3(n_large), dim3(256), 0, s, 2, lsegs, segs, ghist, state);
-  hipLaunchKernelGGL(k_count, dim3(n_tiles), dim3(256), 0, s, tiles, res, state, tile_gt, tile_eq);
-  hipLaunchKernelGGL(k_scan, dim3(n_large), dim3(256), 0, s, lsegs, tile_gt, tile_eq);
-  hipLaunchKernelGGL(k_emit, dim3(n_tiles), dim3(256), 0, s, tiles, lsegs, segs, res, state, tile_gt,
-                     tile_eq, out_idx, out_val);
+  {
+    ProfScope ps(prof, K_ACCUM_HIST, s);
+    hipLaunchKernelGGL(k_accum_hist, dim3(n_tiles), dim3(256), 0, s, tiles, grad, res, lr, ghist);
+  }
+  for (int level = 0; level < 3; ++level) {
+    if (level == 1) {
+      ProfScope ps(prof, K_HIST, s);
+      hipLaunchKernelGGL(k_hist<1>, dim3(n_tiles), dim3(256), 0, s, tiles, res, state, ghist);
+    } else if (level == 2) {
+      ProfScope ps(prof, K_HIST, s);
+      hipLaunchKernelGGL(k_hist<2>, dim3(n_tiles), dim3(256), 0, s, tiles, res, state, ghist);
+    }
+    ProfScope ps(prof, K_CHOOSE, s);
+    hipLaunchKernelGGL(k_choose, dim3(n_large), dim3(256), 0, s, level, lsegs, segs, ghist, state);
+  }
+  {
+    ProfScope ps(prof, K_COUNT, s);
+    hipLaunchKernelGGL(k_count, dim3(n_tiles), dim3(256), 0, s, tiles, res, state, tile_gt, tile_eq);
+  }
+  {
+    ProfScope ps(prof, K_SCAN, s);
+    hipLaunchKernelGGL(k_scan, dim3(n_large), dim3(256), 0, s, lsegs, tile_gt, tile_eq);
+  }
+  {
+    ProfScope ps(prof, K_EMIT, s);
+    hipLaunchKernelGGL(k_emit, dim3(n_tiles), dim3(256), 0, s, tiles, lsegs, segs, res, state, tile_gt,
+                       tile_eq, out_idx, out_val);
+  }
   return hipGetLastError();
 }
 
 hipError_t launch_merge(int n_tiles, const TileDesc* mtiles, const SegDesc* segs, const int32_t* idx,
-                        const float* val, int P, int64_t stride_k, float* update, hipStream_t s) {
+                        const float* val, int P, int64_t stride_k, float* update, hipStream_t s, Prof* prof) {
   if (n_tiles <= 0) return hipSuccess;
+  ProfScope ps(prof, K_MERGE, s);
   hipLaunchKernelGGL(k_merge, dim3(n_tiles), dim3(256), 0, s, mtiles, segs, idx, val, P, stride_k, update);
   return hipGetLastError();
 }

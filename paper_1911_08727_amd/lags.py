@@ -48,6 +48,14 @@ def lib():
         L.lags_merge_sparse.restype = ctypes.c_int
         L.lags_merge_sparse.argtypes = [vp, vp, vp, vp, i32, i64, vp, vp]
         L.lags_strerror.restype, L.lags_strerror.argtypes = ctypes.c_char_p, [ctypes.c_int]
+        L.lags_profile_enable.restype, L.lags_profile_enable.argtypes = ctypes.c_int, [vp, ctypes.c_int]
+        L.lags_profile_num_kernels.restype, L.lags_profile_num_kernels.argtypes = ctypes.c_int, []
+        L.lags_profile_kernel_name.restype, L.lags_profile_kernel_name.argtypes = ctypes.c_char_p, [ctypes.c_int]
+        L.lags_profile_read.restype = ctypes.c_int
+        L.lags_profile_read.argtypes = [vp, ctypes.c_int, ctypes.POINTER(dbl), ctypes.POINTER(i64)]
+        L.lags_profile_reset.restype, L.lags_profile_reset.argtypes = ctypes.c_int, [vp]
+        L.lags_profile_kernel_elements.restype = i64
+        L.lags_profile_kernel_elements.argtypes = [vp, ctypes.c_int]
         _lib = L
     return _lib
 
@@ -101,6 +109,15 @@ class Table:
     def out_offset(self, l):
         return int(lib().lags_table_out_offset(self.handle, l))
 
+    def kernel_elements(self):
+        """{kernel name: layer elements one launch covers} for this table."""
+        out = {}
+        for kid in range(lib().lags_profile_num_kernels()):
+            n = int(lib().lags_profile_kernel_elements(self.handle, kid))
+            if n > 0:
+                out[lib().lags_profile_kernel_name(kid).decode()] = n
+        return out
+
     def destroy(self):
         if self.handle:
             lib().lags_table_destroy(self.handle)
@@ -132,6 +149,22 @@ class Context:
     def lags_merge_sparse(self, table, idx, val, P, stride_k, update_flat, stream=None):
         _check(lib().lags_merge_sparse(self.handle, table.handle, _ptr(idx), _ptr(val), int(P), int(stride_k),
                                        _ptr(update_flat), _stream(stream)), "lags_merge_sparse")
+
+    def lags_profile_enable(self, on):
+        _check(lib().lags_profile_enable(self.handle, int(bool(on))), "lags_profile_enable")
+
+    def lags_profile_reset(self):
+        _check(lib().lags_profile_reset(self.handle), "lags_profile_reset")
+
+    def lags_profile_read(self):
+        """{kernel name: (total milliseconds, launches)} of everything recorded since the last reset."""
+        out = {}
+        for kid in range(lib().lags_profile_num_kernels()):
+            ms, n = ctypes.c_double(0.0), ctypes.c_int64(0)
+            _check(lib().lags_profile_read(self.handle, kid, ctypes.byref(ms), ctypes.byref(n)), "lags_profile_read")
+            if n.value:
+                out[lib().lags_profile_kernel_name(kid).decode()] = (ms.value, n.value)
+        return out
 
     def destroy(self):
         if self.handle:
