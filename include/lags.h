@@ -106,6 +106,14 @@ int lags_sparsify_model(lags_ctx *ctx, const lags_table *t, const float *grad_fl
 int lags_merge_sparse(lags_ctx *ctx, const lags_table *t, const int32_t *idx, const float *val,
                       int32_t P, int64_t stride_k, float *update_flat, void *hip_stream);
 
+/* Diagnostic: which route each layer took in the LAST lags_sparsify_model call made with
+ * this table on this context (host-synchronous: waits for the device).  route[l], l in
+ * [0, n): 0 = one-workgroup route (small layer); 1 = sampled threshold accepted, selection
+ * ran on the candidate list; 2 = sampled threshold rejected (too few candidates or a list
+ * overflowed), exact multi-pass fallback; 3 = layer not sampled, exact multi-pass route.
+ * Results never depend on the route. */
+int lags_last_routes(lags_ctx *ctx, const lags_table *t, int32_t *route, int32_t n);
+
 /* Optional per-kernel timing with HIP events recorded on the caller's stream (measurement
  * aid; off by default; no effect on results).  While enabled every kernel launch of this
  * context is bracketed by a pair of events.  lags_profile_read waits for all recorded

@@ -13,14 +13,46 @@
 
 using namespace lags;
 
+// A device buffer that only ever grows.
+struct DevBuf {
+  void* p = nullptr;
+  size_t bytes = 0;
+  int grow(size_t need) {
+    if (need <= bytes) return LAGS_OK;
+    if (p) (void)hipFree(p);
+    p = nullptr;
+    bytes = 0;
+    if (hipMalloc(&p, need) != hipSuccess) { p = nullptr; return LAGS_ENOMEM; }
+    bytes = need;
+    return LAGS_OK;
+  }
+  void release() {
+    if (p) (void)hipFree(p);
+    p = nullptr;
+    bytes = 0;
+  }
+};
+
 struct lags_ctx {
   int device = 0;
   // scratch of the multi-block path, sized for the largest table created so far
-  uint32_t* ghist = nullptr;   int64_t ghist_cap = 0;    // n_large * kHistStride
-  SegState* state = nullptr;   int64_t state_cap = 0;    // n_large
-  uint32_t* tile_gt = nullptr; uint32_t* tile_eq = nullptr; int64_t tile_cap = 0;  // n_tiles
+  DevBuf counters, ghist, lstate, tile_gt, tile_eq, items, chunk_cnt, chunk_off, slots, cand;
   std::map<std::pair<int64_t, int64_t>, lags_table*> layer_tables;  // (d, k) -> one-layer table
   Prof prof;
+  Scratch scratch() const {
+    Scratch sc;
+    sc.counters = static_cast<uint32_t*>(counters.p);
+    sc.ghist = static_cast<uint32_t*>(ghist.p);
+    sc.lstate = static_cast<LState*>(lstate.p);
+    sc.tile_gt = static_cast<uint32_t*>(tile_gt.p);
+    sc.tile_eq = static_cast<uint32_t*>(tile_eq.p);
+    sc.items = static_cast<int32_t*>(items.p);
+    sc.chunk_cnt = static_cast<uint32_t*>(chunk_cnt.p);
+    sc.chunk_off = static_cast<uint32_t*>(chunk_off.p);
+    sc.slots = static_cast<uint2*>(slots.p);
+    sc.cand = static_cast<uint2*>(cand.p);
+    return sc;
+  }
 };
 
 struct lags_table {
@@ -29,13 +61,19 @@ struct lags_table {
   int64_t total_k = 0;
   int64_t span_lo = 0, span_hi = 0;            // [min offset, max offset + d)
   std::vector<SegDesc> segs;                   // host copy
+  std::vector<LargeSeg> lsegs;                 // host copy
   int n_small[3] = {0, 0, 0};
-  int n_large = 0, n_tiles = 0, n_mtiles = 0;
+  int n_mtiles = 0;
+  LargePlan plan;                              // device pointers below, owned by the table
   SegDesc* d_segs = nullptr;
   int32_t* d_small[3] = {nullptr, nullptr, nullptr};
   LargeSeg* d_lsegs = nullptr;
   TileDesc* d_tiles = nullptr;
+  TileDesc* d_ctiles = nullptr;
   TileDesc* d_mtiles = nullptr;
+  int32_t* d_sampled = nullptr;
+  int32_t* d_cand_small[3] = {nullptr, nullptr, nullptr};
+  int32_t* d_chunk_lseg = nullptr;
 };
 
 namespace {
@@ -65,20 +103,6 @@ int upload(T** dst, const std::vector<T>& src) {
   return LAGS_OK;
 }
 
-template <typename T>
-int grow(T** p, int64_t* cap, int64_t need) {
-  if (need <= *cap) return LAGS_OK;
-  if (*p) (void)hipFree(*p);
-  *p = nullptr;
-  *cap = 0;
-  if (hipMalloc(reinterpret_cast<void**>(p), (size_t)need * sizeof(T)) != hipSuccess) {
-    *p = nullptr;
-    return LAGS_ENOMEM;
-  }
-  *cap = need;
-  return LAGS_OK;
-}
-
 bool ranges_overlap(const void* a, int64_t abytes, const void* b, int64_t bbytes) {
   const uintptr_t a0 = reinterpret_cast<uintptr_t>(a), b0 = reinterpret_cast<uintptr_t>(b);
   return a0 < b0 + (uintptr_t)bbytes && b0 < a0 + (uintptr_t)abytes;
@@ -86,11 +110,49 @@ bool ranges_overlap(const void* a, int64_t abytes, const void* b, int64_t bbytes
 
 void free_table_device(lags_table* t) {
   if (t->d_segs) (void)hipFree(t->d_segs);
-  for (int c = 0; c < 3; ++c)
+  for (int c = 0; c < 3; ++c) {
     if (t->d_small[c]) (void)hipFree(t->d_small[c]);
+    if (t->d_cand_small[c]) (void)hipFree(t->d_cand_small[c]);
+  }
   if (t->d_lsegs) (void)hipFree(t->d_lsegs);
   if (t->d_tiles) (void)hipFree(t->d_tiles);
+  if (t->d_ctiles) (void)hipFree(t->d_ctiles);
   if (t->d_mtiles) (void)hipFree(t->d_mtiles);
+  if (t->d_sampled) (void)hipFree(t->d_sampled);
+  if (t->d_chunk_lseg) (void)hipFree(t->d_chunk_lseg);
+}
+
+// Plan of the threshold guess for a large layer of d elements keeping k: how many sample
+// pieces, which rank of the sample becomes the threshold, how long the candidate list may
+// get.  Returns false if the layer is not worth sampling (k too large for the slots).
+bool plan_sample(int64_t d, int64_t k, LargeSeg* ls) {
+  int64_t pieces, stride;
+  if (d >= kSampleMax) {
+    pieces = kSamplePieces;
+    stride = d / kSamplePieces;
+  } else {
+    pieces = (d + kSamplePiece - 1) / kSamplePiece;
+    stride = kSamplePiece;
+  }
+  const double m = (double)std::min<int64_t>(d, pieces * kSamplePiece);
+  const double fk = (double)k * m / (double)d;
+  // the sample's rank-j key admits about j/m of the layer; j is fk plus six standard
+  // deviations of the sampled count plus a constant, so that fewer than k is very unlikely
+  const double jd = std::ceil(fk + 6.0 * std::sqrt(fk) + 20.0);
+  if (jd > m) return false;
+  // expected candidates per chunk of 2048 elements must stay well inside its slots
+  if (jd / m * (double)kWaveChunk > (double)kSlot * 0.5) return false;
+  const double expect = jd / m * (double)d;
+  const int64_t cap = std::min<int64_t>(d, (int64_t)(2.0 * expect) + 8192);
+  ls->sample_rank = (int32_t)jd;
+  ls->sample_pieces = (int32_t)pieces;
+  ls->sample_stride = (int32_t)stride;
+  ls->cap = (int32_t)cap;
+  if (cap <= kSmall0) ls->cand_class = CAND_SMALL0;
+  else if (cap <= kSmall1) ls->cand_class = CAND_SMALL1;
+  else if (cap <= kSmall2) ls->cand_class = CAND_SMALL2;
+  else ls->cand_class = CAND_LARGE;
+  return true;
 }
 
 // Build a table from explicit (offset, d, k) triples.
@@ -101,9 +163,11 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
   if (!t) return LAGS_ENOMEM;
   t->ctx = ctx;
   t->n = n;
-  std::vector<int32_t> small[3];
-  std::vector<LargeSeg> lsegs;
-  std::vector<TileDesc> tiles, mtiles;
+  std::vector<int32_t> small[3], cand_small[3], sampled, chunk_lseg;
+  std::vector<TileDesc> tiles, ctiles, mtiles;
+  int64_t n_ctile_dense = 0;   // dense tiles of sampled layers (they own 4 chunks each)
+  int64_t cand_total = 0;
+  constexpr int64_t kMaxTiles = 1 << 28;
   try {
     t->segs.resize(n);
     int64_t outpos = 0;
@@ -122,33 +186,62 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
       else if (d[l] <= kSmall1) small[1].push_back(l);
       else if (d[l] <= kSmall2) small[2].push_back(l);
       else {
-        LargeSeg ls;
+        LargeSeg ls = {};
+        const int32_t li = (int32_t)t->lsegs.size();
         ls.seg = l;
+        ls.cand_class = CAND_NONE;
+        const bool sampled_layer = plan_sample(d[l], k[l], &ls);
         ls.tile_begin = (int32_t)tiles.size();
         const int64_t nt = (d[l] + kTile - 1) / kTile;
-        if ((int64_t)tiles.size() + nt > 0x3FFFFFFF) { delete t; return LAGS_ECAPACITY; }
+        if ((int64_t)tiles.size() + nt > kMaxTiles) { delete t; return LAGS_ECAPACITY; }
+        if (sampled_layer) {
+          ls.chunk_begin = (int32_t)(n_ctile_dense * kTileWaves);
+          ls.cand_base = cand_total;
+          cand_total += ls.cap;
+          sampled.push_back(li);
+          if (ls.cand_class == CAND_LARGE) {
+            ls.ctile_begin = (int32_t)ctiles.size();
+            const int64_t nct = ((int64_t)ls.cap + kTile - 1) / kTile;
+            for (int64_t i = 0; i < nct; ++i) {
+              TileDesc td;
+              td.start = ls.cand_base + i * kTile;
+              td.n = (int32_t)std::min<int64_t>(kTile, (int64_t)ls.cap - i * kTile);
+              td.seg = li;
+              td.local0 = (int32_t)(i * kTile);
+              td.ctile = -1;
+              ctiles.push_back(td);
+            }
+            ls.ctile_end = (int32_t)ctiles.size();
+          } else {
+            cand_small[ls.cand_class - CAND_SMALL0].push_back(li);
+          }
+        }
         for (int64_t i = 0; i < nt; ++i) {
           TileDesc td;
           td.start = off[l] + i * kTile;
           td.n = (int32_t)std::min<int64_t>(kTile, d[l] - i * kTile);
-          td.seg = (int32_t)lsegs.size();
+          td.seg = li;
           td.local0 = (int32_t)(i * kTile);
-          td.pad = 0;
+          td.ctile = sampled_layer ? (int32_t)n_ctile_dense : -1;
+          if (sampled_layer) {
+            ++n_ctile_dense;
+            for (int w = 0; w < kTileWaves; ++w) chunk_lseg.push_back(li);
+          }
           tiles.push_back(td);
         }
         ls.tile_end = (int32_t)tiles.size();
-        ls.pad = 0;
-        lsegs.push_back(ls);
+        if (sampled_layer) ls.chunk_end = (int32_t)(n_ctile_dense * kTileWaves);
+        t->lsegs.push_back(ls);
       }
       const int64_t nmt = (d[l] + kMergeTile - 1) / kMergeTile;
-      if ((int64_t)mtiles.size() + nmt > 0x3FFFFFFF) { delete t; return LAGS_ECAPACITY; }
+      if ((int64_t)mtiles.size() + nmt > kMaxTiles) { delete t; return LAGS_ECAPACITY; }
       for (int64_t i = 0; i < nmt; ++i) {
         TileDesc td;
         td.start = off[l] + i * kMergeTile;
         td.n = (int32_t)std::min<int64_t>(kMergeTile, d[l] - i * kMergeTile);
         td.seg = l;
         td.local0 = (int32_t)(i * kMergeTile);
-        td.pad = 0;
+        td.ctile = -1;
         mtiles.push_back(td);
       }
     }
@@ -158,26 +251,42 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
     return LAGS_ENOMEM;
   }
   for (int c = 0; c < 3; ++c) t->n_small[c] = (int)small[c].size();
-  t->n_large = (int)lsegs.size();
-  t->n_tiles = (int)tiles.size();
   t->n_mtiles = (int)mtiles.size();
+  LargePlan& pl = t->plan;
+  pl.n_large = (int)t->lsegs.size();
+  pl.n_tiles = (int)tiles.size();
+  pl.n_sampled = (int)sampled.size();
+  pl.n_chunks = (int)chunk_lseg.size();
+  pl.n_ctiles = (int)ctiles.size();
+  for (int c = 0; c < 3; ++c) pl.n_cand_small[c] = (int)cand_small[c].size();
 
   int rc = upload(&t->d_segs, t->segs);
   for (int c = 0; c < 3 && rc == LAGS_OK; ++c) rc = upload(&t->d_small[c], small[c]);
-  if (rc == LAGS_OK) rc = upload(&t->d_lsegs, lsegs);
+  for (int c = 0; c < 3 && rc == LAGS_OK; ++c) rc = upload(&t->d_cand_small[c], cand_small[c]);
+  if (rc == LAGS_OK) rc = upload(&t->d_lsegs, t->lsegs);
   if (rc == LAGS_OK) rc = upload(&t->d_tiles, tiles);
+  if (rc == LAGS_OK) rc = upload(&t->d_ctiles, ctiles);
   if (rc == LAGS_OK) rc = upload(&t->d_mtiles, mtiles);
-  if (rc == LAGS_OK) rc = grow(&ctx->ghist, &ctx->ghist_cap, (int64_t)t->n_large * kHistStride);
-  if (rc == LAGS_OK) rc = grow(&ctx->state, &ctx->state_cap, (int64_t)t->n_large);
-  if (rc == LAGS_OK && t->n_tiles > ctx->tile_cap) {
-    if (ctx->tile_gt) (void)hipFree(ctx->tile_gt);
-    if (ctx->tile_eq) (void)hipFree(ctx->tile_eq);
-    ctx->tile_gt = ctx->tile_eq = nullptr;
-    ctx->tile_cap = 0;
-    int64_t c1 = 0, c2 = 0;
-    rc = grow(&ctx->tile_gt, &c1, t->n_tiles);
-    if (rc == LAGS_OK) rc = grow(&ctx->tile_eq, &c2, t->n_tiles);
-    if (rc == LAGS_OK) ctx->tile_cap = t->n_tiles;
+  if (rc == LAGS_OK) rc = upload(&t->d_sampled, sampled);
+  if (rc == LAGS_OK) rc = upload(&t->d_chunk_lseg, chunk_lseg);
+  pl.lsegs = t->d_lsegs;
+  pl.tiles = t->d_tiles;
+  pl.ctiles = t->d_ctiles;
+  pl.sampled = t->d_sampled;
+  pl.chunk_lseg = t->d_chunk_lseg;
+  for (int c = 0; c < 3; ++c) pl.cand_small[c] = t->d_cand_small[c];
+  if (pl.n_large > 0) {
+    const size_t nt = (size_t)pl.n_tiles + (size_t)pl.n_ctiles;
+    if (rc == LAGS_OK) rc = ctx->counters.grow(16 * sizeof(uint32_t));
+    if (rc == LAGS_OK) rc = ctx->ghist.grow((size_t)pl.n_large * kHistStride * sizeof(uint32_t));
+    if (rc == LAGS_OK) rc = ctx->lstate.grow((size_t)pl.n_large * sizeof(LState));
+    if (rc == LAGS_OK) rc = ctx->tile_gt.grow(nt * sizeof(uint32_t));
+    if (rc == LAGS_OK) rc = ctx->tile_eq.grow(nt * sizeof(uint32_t));
+    if (rc == LAGS_OK) rc = ctx->items.grow((size_t)pl.n_tiles * sizeof(int32_t));
+    if (rc == LAGS_OK) rc = ctx->chunk_cnt.grow((size_t)pl.n_chunks * sizeof(uint32_t));
+    if (rc == LAGS_OK) rc = ctx->chunk_off.grow((size_t)pl.n_chunks * sizeof(uint32_t));
+    if (rc == LAGS_OK) rc = ctx->slots.grow((size_t)pl.n_chunks * kSlot * sizeof(uint2));
+    if (rc == LAGS_OK) rc = ctx->cand.grow((size_t)cand_total * sizeof(uint2));
   }
   if (rc != LAGS_OK) {
     free_table_device(t);
@@ -194,8 +303,7 @@ int run_sparsify(lags_ctx* ctx, const lags_table* t, const float* grad, float* r
     if (launch_small(c, t->n_small[c], t->d_segs, t->d_small[c], grad, res, lr, out_idx, out_val, s, &ctx->prof) != hipSuccess)
       return LAGS_EHIP;
   }
-  if (launch_large(t->n_large, t->n_tiles, t->d_segs, t->d_lsegs, t->d_tiles, grad, res, lr, out_idx,
-                   out_val, ctx->ghist, ctx->state, ctx->tile_gt, ctx->tile_eq, s, &ctx->prof) != hipSuccess)
+  if (launch_large(t->plan, ctx->scratch(), t->d_segs, grad, res, lr, out_idx, out_val, s, &ctx->prof) != hipSuccess)
     return LAGS_EHIP;
   return LAGS_OK;
 }
@@ -233,10 +341,9 @@ int lags_destroy(lags_ctx* ctx) {
     free_table_device(kv.second);
     delete kv.second;
   }
-  if (ctx->ghist) (void)hipFree(ctx->ghist);
-  if (ctx->state) (void)hipFree(ctx->state);
-  if (ctx->tile_gt) (void)hipFree(ctx->tile_gt);
-  if (ctx->tile_eq) (void)hipFree(ctx->tile_eq);
+  DevBuf* bufs[] = {&ctx->counters, &ctx->ghist, &ctx->lstate, &ctx->tile_gt, &ctx->tile_eq, &ctx->items,
+                    &ctx->chunk_cnt, &ctx->chunk_off, &ctx->slots, &ctx->cand};
+  for (DevBuf* b : bufs) b->release();
   delete ctx;
   return LAGS_OK;
 }
@@ -346,6 +453,29 @@ int lags_merge_sparse(lags_ctx* ctx, const lags_table* t, const int32_t* idx, co
   return LAGS_OK;
 }
 
+int lags_last_routes(lags_ctx* ctx, const lags_table* t, int32_t* route, int32_t n) {
+  if (!ctx || !t || t->ctx != ctx || !route || n != t->n) return LAGS_EINVAL;
+  DeviceGuard g(ctx->device);
+  if (!g.ok) return LAGS_EHIP;
+  for (int32_t l = 0; l < n; ++l) route[l] = 0;
+  const int nl = t->plan.n_large;
+  if (nl == 0) return LAGS_OK;
+  std::vector<LState> st;
+  try {
+    st.resize(nl);
+  } catch (const std::bad_alloc&) {
+    return LAGS_ENOMEM;
+  }
+  if (hipDeviceSynchronize() != hipSuccess) return LAGS_EHIP;
+  if (hipMemcpy(st.data(), ctx->lstate.p, (size_t)nl * sizeof(LState), hipMemcpyDeviceToHost) != hipSuccess)
+    return LAGS_EHIP;
+  for (int i = 0; i < nl; ++i) {
+    const LargeSeg& ls = t->lsegs[i];
+    route[ls.seg] = ls.cand_class == CAND_NONE ? 3 : (st[i].mode == MODE_SPARSE ? 1 : 2);
+  }
+  return LAGS_OK;
+}
+
 int lags_profile_enable(lags_ctx* ctx, int on) {
   if (!ctx) return LAGS_EINVAL;
   ctx->prof.on = on != 0;
@@ -395,7 +525,7 @@ int64_t lags_profile_kernel_elements(const lags_table* t, int kernel_id) {
     case K_SMALL0: return small[0];
     case K_SMALL1: return small[1];
     case K_SMALL2: return small[2];
-    case K_ACCUM_HIST: case K_HIST: case K_COUNT: case K_EMIT: return large;
+    case K_STREAM: return large;
     case K_MERGE: return all;
     default: return 0;
   }

@@ -8,8 +8,8 @@
 namespace lags {
 
 // Geometry of the multi-block ("large") path: one workgroup of 4 waves per tile,
-// each wave owns a contiguous quarter of the tile and walks it in rounds of
-// 64 lanes x 4 consecutive elements.
+// each wave owns a contiguous quarter of the tile (a "chunk") and walks it in rounds
+// of 64 lanes x 4 consecutive elements.
 constexpr int kTileWaves = 4;
 constexpr int kTileV = 8;                               // rounds per wave
 constexpr int kWaveChunk = kTileV * 256;                // 2048 elements per wave
@@ -23,6 +23,13 @@ constexpr int kSmall0 = 4 * 1 * 256;     // <= 1024  : 4 waves, 1 round
 constexpr int kSmall1 = 4 * 8 * 256;     // <= 8192  : 4 waves, 8 rounds
 constexpr int kSmall2 = 16 * 10 * 256;   // <= 40960 : 16 waves, 10 rounds
 
+// Threshold guess from a sample (large layers): 1024 pieces of 64 consecutive elements.
+constexpr int kSamplePiece = 64;
+constexpr int kSamplePieces = 1024;
+constexpr int kSampleMax = kSamplePiece * kSamplePieces;   // 65536 sampled elements
+constexpr int kSlot = 128;               // candidate slots per chunk of 2048 elements
+constexpr int kDenseGrid = 2048;         // workgroups of the fallback kernels (grid-stride)
+
 constexpr int kMergeTile = 8192;
 constexpr int kMaxWorkers = 1024;
 
@@ -33,30 +40,72 @@ struct SegDesc {        // one layer
   int32_t k;
 };
 
-struct TileDesc {       // one tile of a layer
-  int64_t start;        // absolute element offset of the tile's first element
-  int32_t n;            // valid elements in the tile (<= tile size)
+struct TileDesc {       // one tile of a layer (dense tiles, candidate tiles, merge tiles)
+  int64_t start;        // dense/merge: absolute element offset; candidate tile: offset in the candidate array
+  int32_t n;            // elements in the tile (<= tile size); candidate tiles: capacity
   int32_t seg;          // large path: index among the large layers; merge: layer index
-  int32_t local0;       // layer-local index of the tile's first element
-  int32_t pad;
+  int32_t local0;       // layer-local index (candidate tiles: list position) of the first element
+  int32_t ctile;        // dense tiles of sampled layers: index among those tiles; else -1
 };
 
-struct LargeSeg {
+enum : int32_t { CAND_NONE = 0, CAND_SMALL0 = 1, CAND_SMALL1 = 2, CAND_SMALL2 = 3, CAND_LARGE = 4 };
+
+struct LargeSeg {       // static plan of one large layer
+  int64_t cand_base;    // start of the layer's candidate list in the candidate array
   int32_t seg;          // layer index
-  int32_t tile_begin;   // first tile of the layer in the tile list
+  int32_t tile_begin;   // dense tiles [tile_begin, tile_end)
   int32_t tile_end;
-  int32_t pad;
+  int32_t chunk_begin;  // chunks of the sampled tiles [chunk_begin, chunk_end), or 0,0
+  int32_t chunk_end;
+  int32_t cand_class;   // CAND_NONE: not sampled
+  int32_t cap;          // capacity of the candidate list
+  int32_t ctile_begin;  // candidate tiles (CAND_LARGE) [ctile_begin, ctile_end)
+  int32_t ctile_end;
+  int32_t sample_rank;  // rank (1-based, from the top) of the sample key used as threshold
+  int32_t sample_pieces;
+  int32_t sample_stride;
 };
 
-struct SegState {       // radix-select state of one large layer
-  uint32_t prefix;      // key bits decided so far
+enum : uint32_t { MODE_DENSE = 0, MODE_SPARSE = 1 };
+
+struct LState {         // per call, per large layer
+  uint32_t tau;         // candidates are the entries with key >= tau
+  uint32_t ncand;       // number of candidates found
+  uint32_t mode;        // MODE_SPARSE: the candidate list holds the top k; MODE_DENSE: fall back
+  uint32_t prefix;      // radix select: key bits decided so far
   uint32_t k_rem;       // entries still to take among keys matching the prefix
+  uint32_t pad[3];
+};
+
+struct LargePlan {      // everything launch_large needs (device pointers + counts)
+  int n_large = 0, n_tiles = 0, n_sampled = 0, n_chunks = 0, n_ctiles = 0;
+  int n_cand_small[3] = {0, 0, 0};
+  const LargeSeg* lsegs = nullptr;
+  const TileDesc* tiles = nullptr;      // dense tiles
+  const TileDesc* ctiles = nullptr;     // candidate tiles of CAND_LARGE layers
+  const int32_t* sampled = nullptr;     // large-layer indices that are sampled
+  const int32_t* cand_small[3] = {nullptr, nullptr, nullptr};  // large-layer indices per class
+  const int32_t* chunk_lseg = nullptr;  // chunk -> large-layer index
+};
+
+struct Scratch {        // context-owned device memory, contents meaningless between calls
+  uint32_t* counters = nullptr;   // [0] = number of dense work items; zeroed each call
+  uint32_t* ghist = nullptr;      // n_large * kHistStride
+  LState* lstate = nullptr;       // n_large
+  uint32_t* tile_gt = nullptr;    // n_tiles + n_ctiles
+  uint32_t* tile_eq = nullptr;
+  int32_t* items = nullptr;       // n_tiles: dense tiles to process in fallback mode
+  uint32_t* chunk_cnt = nullptr;  // n_chunks
+  uint32_t* chunk_off = nullptr;  // n_chunks
+  uint2* slots = nullptr;         // n_chunks * kSlot
+  uint2* cand = nullptr;          // sum of cap over sampled layers
 };
 
 // Kernel ids for the optional event timing.
 enum KernelId {
-  K_ZERO = 0, K_SMALL0, K_SMALL1, K_SMALL2, K_ACCUM_HIST, K_CHOOSE, K_HIST, K_COUNT, K_SCAN, K_EMIT,
-  K_MERGE, K_NUM
+  K_ZERO = 0, K_SMALL0, K_SMALL1, K_SMALL2, K_SAMPLE, K_STREAM, K_CSCAN, K_CGATHER,
+  K_CSMALL0, K_CSMALL1, K_CSMALL2, K_HIST_CAND, K_HIST_DENSE, K_CHOOSE, K_COUNT_CAND, K_COUNT_DENSE,
+  K_SCAN, K_EMIT_CAND, K_EMIT_DENSE, K_MERGE, K_NUM
 };
 const char* kernel_name(int id);
 
@@ -82,10 +131,8 @@ struct ProfScope {
 hipError_t launch_zero_u32(uint32_t* p, int64_t n, hipStream_t s, Prof* prof);
 hipError_t launch_small(int cls, int nseg, const SegDesc* segs, const int32_t* list, const float* grad,
                         float* res, float lr, int32_t* out_idx, float* out_val, hipStream_t s, Prof* prof);
-hipError_t launch_large(int n_large, int n_tiles, const SegDesc* segs, const LargeSeg* lsegs,
-                        const TileDesc* tiles, const float* grad, float* res, float lr,
-                        int32_t* out_idx, float* out_val, uint32_t* ghist, SegState* state,
-                        uint32_t* tile_gt, uint32_t* tile_eq, hipStream_t s, Prof* prof);
+hipError_t launch_large(const LargePlan& pl, const Scratch& sc, const SegDesc* segs, const float* grad,
+                        float* res, float lr, int32_t* out_idx, float* out_val, hipStream_t s, Prof* prof);
 hipError_t launch_merge(int n_tiles, const TileDesc* mtiles, const SegDesc* segs, const int32_t* idx,
                         const float* val, int P, int64_t stride_k, float* update, hipStream_t s, Prof* prof);
 

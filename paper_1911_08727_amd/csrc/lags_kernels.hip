@@ -15,6 +15,17 @@
 // so loads/stores are 16-byte vectors, coalesced over the wave, and index order is
 // (round, lane, component).  Ordered compaction uses per-wave counts, a scan over waves
 // (and over tiles for multi-block layers) and a wave prefix scan per round.
+//
+// Three routes, chosen per layer by size:
+//   small  (d <= 40960): one workgroup, acc stays in registers between the single read of
+//          grad/residual and the single write of the residual.
+//   large, sampled: a sample of up to 65536 elements gives a threshold tau that, with high
+//          probability, admits slightly more than k entries.  One streaming pass writes acc
+//          into the residual buffer and collects every entry with key >= tau (in index
+//          order).  If at least k were collected (and the lists did not overflow) the exact
+//          top k are among them and the selection runs on the short candidate list only.
+//          The guess never changes the result: it is verified by the count.
+//   large, fallback: radix select over the acc values in the residual buffer, multi-block.
 #include "lags_internal.h"
 
 namespace lags {
@@ -22,6 +33,11 @@ namespace lags {
 // ------------------------------------------------------------------ helpers --
 __device__ __forceinline__ int lane_id() {
   return (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+}
+
+// number of set bits of `m` below the calling lane
+__device__ __forceinline__ uint32_t mbcnt64(uint64_t m) {
+  return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
 }
 
 // Algorithm 1 line 6 for one element: product rounded to binary32, then the sum
@@ -72,7 +88,8 @@ __device__ __forceinline__ uint32_t block_incl_scan(uint32_t v, uint32_t* s_wt, 
 // Given a histogram of `nb` bins (nb a multiple of NT) whose total is >= k_rem >= 1,
 // find the bin b holding the k_rem-th entry counted from the top bin downwards and
 // the rank of that entry inside the bin.  Result in s_sel[0] = b, s_sel[1] = new k_rem
-// (valid for every thread after the call).  `hist` may be LDS or global memory.
+// (valid for every thread after the call; untouched if the total is below k_rem).
+// `hist` may be LDS or global memory.
 template <int NT>
 __device__ __forceinline__ void block_find_bucket(const uint32_t* hist, int nb, uint32_t k_rem,
                                                   uint32_t* s_wt, uint32_t* s_sel) {
@@ -96,6 +113,41 @@ __device__ __forceinline__ void block_find_bucket(const uint32_t* hist, int nb, 
     }
   }
   __syncthreads();
+}
+
+// Exact radix select over keys held in registers by a whole workgroup: finds the k-th
+// largest key T and the number of entries equal to T that belong to the top k.
+// s_hist: kBins0 words, s_wt: NT/64 words, s_sel: 2 words.
+template <int NT, int V>
+__device__ __forceinline__ void block_radix_select(const uint32_t (&a)[V][4], int n_w, int lane, uint32_t k,
+                                                   uint32_t* s_hist, uint32_t* s_wt, uint32_t* s_sel,
+                                                   uint32_t& T, uint32_t& rtake) {
+  const int tid = threadIdx.x;
+  uint32_t prefix = 0, mask = 0, k_rem = k;
+#pragma unroll
+  for (int level = 0; level < 3; ++level) {
+    const int shift = level == 0 ? 20 : (level == 1 ? 10 : 0);
+    const int nb = level == 0 ? kBins0 : kBins12;
+    for (int i = tid; i < nb; i += NT) s_hist[i] = 0u;
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < V; ++j) {
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const int e = j * 256 + lane * 4 + c;
+        const uint32_t key = a[j][c] & 0x7FFFFFFFu;
+        if (e < n_w && (key & mask) == prefix) atomicAdd(&s_hist[(key >> shift) & (uint32_t)(nb - 1)], 1u);
+      }
+    }
+    __syncthreads();
+    block_find_bucket<NT>(s_hist, nb, k_rem, s_wt, s_sel);
+    prefix |= s_sel[0] << shift;
+    mask |= (uint32_t)(nb - 1) << shift;
+    k_rem = s_sel[1];
+    __syncthreads();
+  }
+  T = prefix;
+  rtake = k_rem;
 }
 
 // Load a wave's chunk of grad and residual and form acc (bits).  `n_w` = number of valid
@@ -145,6 +197,18 @@ __device__ __forceinline__ void load_bits(const float* __restrict__ r, int n_w, 
   }
 }
 
+// Load the value bits of a wave's chunk of a candidate list ((index, bits) pairs).
+template <int V>
+__device__ __forceinline__ void load_cand_bits(const uint2* __restrict__ cw, int n_w, int lane,
+                                               uint32_t (&a)[V][4]) {
+#pragma unroll
+  for (int j = 0; j < V; ++j) {
+    const int e = j * 256 + lane * 4;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) a[j][c] = (e + c < n_w) ? cw[e + c].y : 0u;
+  }
+}
+
 template <int V>
 __device__ __forceinline__ void store_bits(float* __restrict__ r, int n_w, bool vec, int lane,
                                            const uint32_t (&a)[V][4]) {
@@ -177,17 +241,24 @@ __device__ __forceinline__ void lane_count(const uint32_t (&a)[V][4], int n_w, i
   }
 }
 
+enum { EMIT_FULL = 0, EMIT_ZERO = 1, EMIT_CAND = 2 };
+
 // Ordered emission of a wave's chunk.  gt_before / eq_before: numbers of keys > T and
 // == T that precede the chunk in the layer.  An element is kept if key > T, or key == T
 // and fewer than `rtake` equal keys precede it; its output slot is the number of kept
 // elements before it = gt_before + min(eq_before, rtake).
-// FULL: the residual chunk is written completely (acc, kept entries zeroed).
-// !FULL: the residual already holds acc; only the kept entries are zeroed.
-template <int V, bool FULL>
+// EMIT_FULL: the chunk is residual data; it is written back completely (acc, kept entries
+//            zeroed).  r = the chunk's residual.
+// EMIT_ZERO: the residual already holds acc; only the kept entries are zeroed.  r = the
+//            chunk's residual.
+// EMIT_CAND: the chunk is part of a candidate list cw ((index, bits) pairs); the kept
+//            entries' residual slots r[index] are zeroed.  r = the layer's residual.
+template <int V, int MODE>
 __device__ __forceinline__ void wave_emit(uint32_t (&a)[V][4], int n_w, int lane, uint32_t T,
                                           uint32_t rtake, uint32_t gt_before, uint32_t eq_before,
                                           uint32_t k, int32_t idx_base, int32_t* __restrict__ oi,
-                                          float* __restrict__ ov, float* __restrict__ r, bool vec) {
+                                          float* __restrict__ ov, float* __restrict__ r, bool vec,
+                                          const uint2* __restrict__ cw) {
 #pragma unroll
   for (int j = 0; j < V; ++j) {
     if (j * 256 >= n_w) break;  // wave-uniform
@@ -214,9 +285,15 @@ __device__ __forceinline__ void wave_emit(uint32_t (&a)[V][4], int n_w, int lane
       const bool sel = fg[c] || (fe[c] && eb < rtake);
       const uint32_t pos = gb + (eb < rtake ? eb : rtake);
       if (sel && pos < k) {  // pos < k always holds; the check keeps a wrong T from writing out of bounds
-        oi[pos] = idx_base + e + c;
         ov[pos] = __uint_as_float(a[j][c]);
-        if (FULL) a[j][c] = 0u; else r[e + c] = 0.0f;
+        if (MODE == EMIT_CAND) {
+          const int32_t index = (int32_t)cw[e + c].x;
+          oi[pos] = index;
+          r[index] = 0.0f;
+        } else {
+          oi[pos] = idx_base + e + c;
+          if (MODE == EMIT_FULL) a[j][c] = 0u; else r[e + c] = 0.0f;
+        }
       }
       gb += fg[c];
       eb += fe[c];
@@ -224,11 +301,26 @@ __device__ __forceinline__ void wave_emit(uint32_t (&a)[V][4], int n_w, int lane
     gt_before += tot & 0xFFFFu;
     eq_before += tot >> 16;
   }
-  if (FULL) store_bits<V>(r, n_w, vec, lane, a);
+  if (MODE == EMIT_FULL) store_bits<V>(r, n_w, vec, lane, a);
 }
 
 __device__ __forceinline__ bool aligned16(const void* a, const void* b) {
   return ((reinterpret_cast<uintptr_t>(a) | reinterpret_cast<uintptr_t>(b)) & 15u) == 0;
+}
+
+// Histogram update where many lanes may hit the same bin: lanes that share lane 0's bin
+// are counted with one ballot and a single LDS add; the others add individually.
+// b = 0xFFFFFFFF: the lane has nothing to add.  Must be called by all 64 lanes.
+__device__ __forceinline__ void hist_add_peeled(uint32_t* s_hist, uint32_t b, int lane) {
+  const uint32_t f = (uint32_t)__builtin_amdgcn_readfirstlane((int)b);
+  const uint64_t same = __ballot(b == f);
+  if (lane == 0 && f != 0xFFFFFFFFu) atomicAdd(&s_hist[f], (uint32_t)__popcll(same));
+  if (b != f && b != 0xFFFFFFFFu) atomicAdd(&s_hist[b], 1u);
+}
+
+__device__ __forceinline__ uint32_t mix32(uint32_t x) {
+  x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
+  return x;
 }
 
 // ------------------------------------------------------------------ zero -----
@@ -239,11 +331,14 @@ __global__ void k_zero_u32(uint32_t* __restrict__ p, int64_t n) {
 }
 
 // ------------------------------------------------------------------ small ----
-// One workgroup per layer; the layer's acc values live in registers from the single
-// read of grad/residual to the single write of the residual.
-template <int NW, int V>
+// One workgroup per layer (CAND = false) or per candidate list of a large layer
+// (CAND = true); the values live in registers between the single read and the write.
+template <int NW, int V, bool CAND>
 __global__ __launch_bounds__(NW * 64) void k_small(const SegDesc* __restrict__ segs,
                                                    const int32_t* __restrict__ list,
+                                                   const LargeSeg* __restrict__ lsegs,
+                                                   const LState* __restrict__ lstate,
+                                                   const uint2* __restrict__ cand,
                                                    const float* __restrict__ grad,
                                                    float* __restrict__ res, float lr,
                                                    int32_t* __restrict__ out_idx,
@@ -255,40 +350,37 @@ __global__ __launch_bounds__(NW * 64) void k_small(const SegDesc* __restrict__ s
   __shared__ uint32_t s_sel[2];
   __shared__ uint32_t s_wg[NW], s_we[NW];
 
-  const SegDesc sd = segs[list[blockIdx.x]];
   const int tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
-  const float* g = grad + sd.offset + (int64_t)w * CH;
+  SegDesc sd;
+  int n;
+  const uint2* cw = nullptr;
+  if (CAND) {
+    const int li = list[blockIdx.x];
+    const LargeSeg ls = lsegs[li];
+    const LState st = lstate[li];
+    if (st.mode != MODE_SPARSE) return;  // uniform over the workgroup
+    sd = segs[ls.seg];
+    n = (int)st.ncand;
+    cw = cand + ls.cand_base + (int64_t)w * CH;
+  } else {
+    sd = segs[list[blockIdx.x]];
+    n = sd.d;
+  }
+  const int n_w = n - w * CH;
   float* r = res + sd.offset + (int64_t)w * CH;
-  const int n_w = sd.d - w * CH;
-  const bool vec = aligned16(g, r);
+  bool vec = false;
 
   uint32_t a[V][4];
-  load_acc<V>(g, r, n_w, lr, vec, lane, a);
-
-  uint32_t prefix = 0, mask = 0, k_rem = (uint32_t)sd.k;
-#pragma unroll
-  for (int level = 0; level < 3; ++level) {
-    const int shift = level == 0 ? 20 : (level == 1 ? 10 : 0);
-    const int nb = level == 0 ? kBins0 : kBins12;
-    for (int i = tid; i < nb; i += NT) s_hist[i] = 0u;
-    __syncthreads();
-#pragma unroll
-    for (int j = 0; j < V; ++j) {
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const int e = j * 256 + lane * 4 + c;
-        const uint32_t key = a[j][c] & 0x7FFFFFFFu;
-        if (e < n_w && (key & mask) == prefix) atomicAdd(&s_hist[(key >> shift) & (uint32_t)(nb - 1)], 1u);
-      }
-    }
-    __syncthreads();
-    block_find_bucket<NT>(s_hist, nb, k_rem, s_wt, s_sel);
-    prefix |= s_sel[0] << shift;
-    mask |= (uint32_t)(nb - 1) << shift;
-    k_rem = s_sel[1];
-    __syncthreads();
+  if (CAND) {
+    load_cand_bits<V>(cw, n_w, lane, a);
+  } else {
+    const float* g = grad + sd.offset + (int64_t)w * CH;
+    vec = aligned16(g, r);
+    load_acc<V>(g, r, n_w, lr, vec, lane, a);
   }
-  const uint32_t T = prefix, rtake = k_rem;
+
+  uint32_t T, rtake;
+  block_radix_select<NT, V>(a, n_w, lane, (uint32_t)sd.k, s_hist, s_wt, s_sel, T, rtake);
 
   uint32_t cg, ce;
   lane_count<V>(a, n_w, lane, T, cg, ce);
@@ -298,21 +390,89 @@ __global__ __launch_bounds__(NW * 64) void k_small(const SegDesc* __restrict__ s
   __syncthreads();
   uint32_t gb = 0, eb = 0;
   for (int i = 0; i < w; ++i) { gb += s_wg[i]; eb += s_we[i]; }
-  wave_emit<V, true>(a, n_w, lane, T, rtake, gb, eb, (uint32_t)sd.k, w * CH, out_idx + sd.out_offset,
-                     out_val + sd.out_offset, r, vec);
+  if (CAND)
+    wave_emit<V, EMIT_CAND>(a, n_w, lane, T, rtake, gb, eb, (uint32_t)sd.k, 0, out_idx + sd.out_offset,
+                            out_val + sd.out_offset, res + sd.offset, false, cw);
+  else
+    wave_emit<V, EMIT_FULL>(a, n_w, lane, T, rtake, gb, eb, (uint32_t)sd.k, w * CH, out_idx + sd.out_offset,
+                            out_val + sd.out_offset, r, vec, nullptr);
 }
 
-// ------------------------------------------------------------------ large ----
-// Pass 1: acc = residual + lr*grad written into the residual buffer (it is the final
-// residual everywhere but at the k kept entries), plus the histogram of key bits 30..20.
-__global__ __launch_bounds__(256) void k_accum_hist(const TileDesc* __restrict__ tiles,
-                                                    const float* __restrict__ grad,
-                                                    float* __restrict__ res, float lr,
-                                                    uint32_t* __restrict__ ghist) {
+// ------------------------------------------------------------------ sample ---
+// Threshold guess for one large layer: form acc on up to 1024 pieces of 64 consecutive
+// elements spread over the layer (with a hashed offset inside each stride), and take the
+// sample's `sample_rank`-th largest key as tau.  Missing sample slots count as key 0.
+__global__ __launch_bounds__(1024) void k_sample(const SegDesc* __restrict__ segs,
+                                                 const int32_t* __restrict__ sampled,
+                                                 const LargeSeg* __restrict__ lsegs,
+                                                 const float* __restrict__ grad,
+                                                 const float* __restrict__ res, float lr,
+                                                 LState* __restrict__ lstate) {
+  constexpr int NW = 16, V = 16, NT = 1024;
+  __shared__ uint32_t s_hist[kBins0];
+  __shared__ uint32_t s_wt[NW];
+  __shared__ uint32_t s_sel[2];
+  const int li = sampled[blockIdx.x];
+  const LargeSeg ls = lsegs[li];
+  const SegDesc sd = segs[ls.seg];
+  const int tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
+  const float* g = grad + sd.offset;
+  const float* r = res + sd.offset;
+  const bool vec = aligned16(g, r);
+  uint32_t a[V][4];
+#pragma unroll
+  for (int j = 0; j < V; ++j) {
+    const int piece = w * 64 + j * 4 + (lane >> 4);
+    a[j][0] = a[j][1] = a[j][2] = a[j][3] = 0u;
+    if (piece < ls.sample_pieces) {
+      int start = piece * ls.sample_stride;
+      if (ls.sample_stride > kSamplePiece)
+        start += (int)(mix32((uint32_t)piece * 0x9E3779B9u + (uint32_t)li) %
+                       (uint32_t)(ls.sample_stride - kSamplePiece + 1));
+      start &= ~3;
+      const int e = start + (lane & 15) * 4;
+      if (vec && e + 3 < sd.d) {
+        const float4 gv = *reinterpret_cast<const float4*>(g + e);
+        const float4 rv = *reinterpret_cast<const float4*>(r + e);
+        a[j][0] = acc_bits(gv.x, rv.x, lr);
+        a[j][1] = acc_bits(gv.y, rv.y, lr);
+        a[j][2] = acc_bits(gv.z, rv.z, lr);
+        a[j][3] = acc_bits(gv.w, rv.w, lr);
+      } else {
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+          if (e + c < sd.d) a[j][c] = acc_bits(g[e + c], r[e + c], lr);
+      }
+    }
+  }
+  uint32_t T, rtake;
+  block_radix_select<NT, V>(a, V * 256, lane, (uint32_t)ls.sample_rank, s_hist, s_wt, s_sel, T, rtake);
+  if (tid == 0) lstate[li].tau = T;
+}
+
+// ------------------------------------------------------------------ stream ---
+// The one pass over grad and residual of every large layer: acc = residual + lr*grad is
+// written into the residual buffer (it is the final residual everywhere but at the k kept
+// entries).  Tiles of sampled layers also collect, per chunk and in index order, the
+// entries with key >= tau into the chunk's slots; tiles of the other layers add to the
+// layer's histogram of key bits 30..20.
+__global__ __launch_bounds__(256) void k_stream(const TileDesc* __restrict__ tiles,
+                                                const float* __restrict__ grad,
+                                                float* __restrict__ res, float lr,
+                                                const LState* __restrict__ lstate,
+                                                uint32_t* __restrict__ chunk_cnt,
+                                                uint2* __restrict__ slots,
+                                                uint32_t* __restrict__ ghist) {
   __shared__ uint32_t s_hist[kBins0];
   const TileDesc td = tiles[blockIdx.x];
   const int tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
-  for (int i = tid; i < kBins0; i += 256) s_hist[i] = 0u;
+  const bool collect = td.ctile >= 0;  // uniform over the workgroup
+  uint32_t tau = 0;
+  if (collect) {
+    tau = lstate[td.seg].tau;
+  } else {
+    for (int i = tid; i < kBins0; i += 256) s_hist[i] = 0u;
+  }
   const float* g = grad + td.start + w * kWaveChunk;
   float* r = res + td.start + w * kWaveChunk;
   const int n_w = td.n - w * kWaveChunk;
@@ -320,35 +480,236 @@ __global__ __launch_bounds__(256) void k_accum_hist(const TileDesc* __restrict__
   uint32_t a[kTileV][4];
   load_acc<kTileV>(g, r, n_w, lr, vec, lane, a);
   store_bits<kTileV>(r, n_w, vec, lane, a);
-  __syncthreads();
+  if (collect) {
+    const int chunk = td.ctile * kTileWaves + w;
+    uint2* slot = slots + (int64_t)chunk * kSlot;
+    const int32_t idx0 = td.local0 + w * kWaveChunk;
+    uint32_t base = 0;
 #pragma unroll
-  for (int j = 0; j < kTileV; ++j) {
+    for (int j = 0; j < kTileV; ++j) {
+      const int e = j * 256 + lane * 4;
+      bool f[4];
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      const int e = j * 256 + lane * 4 + c;
-      // Gradient magnitudes crowd into few bins: lanes that share lane 0's bin are
-      // counted with one ballot and a single LDS add; the others add individually.
-      const uint32_t b = e < n_w ? (a[j][c] & 0x7FFFFFFFu) >> 20 : 0xFFFFFFFFu;
-      const uint32_t f = (uint32_t)__builtin_amdgcn_readfirstlane((int)b);
-      const uint64_t same = __ballot(b == f);
-      if (lane == 0 && f != 0xFFFFFFFFu) atomicAdd(&s_hist[f], (uint32_t)__popcll(same));
-      if (b != f && b != 0xFFFFFFFFu) atomicAdd(&s_hist[b], 1u);
+      for (int c = 0; c < 4; ++c) f[c] = (e + c < n_w) && ((a[j][c] & 0x7FFFFFFFu) >= tau);
+      const uint64_t b0 = __ballot(f[0]), b1 = __ballot(f[1]), b2 = __ballot(f[2]), b3 = __ballot(f[3]);
+      const uint32_t tot = (uint32_t)(__popcll(b0) + __popcll(b1) + __popcll(b2) + __popcll(b3));
+      if (tot) {  // wave-uniform
+        uint32_t pos = base + mbcnt64(b0) + mbcnt64(b1) + mbcnt64(b2) + mbcnt64(b3);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          if (f[c]) {
+            if (pos < (uint32_t)kSlot) slot[pos] = make_uint2((uint32_t)(idx0 + e + c), a[j][c]);
+            ++pos;
+          }
+        }
+        base += tot;
+      }
+    }
+    if (lane == 0) chunk_cnt[chunk] = base;  // a count above kSlot marks the chunk as overflowed
+  } else {
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < kTileV; ++j) {
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const int e = j * 256 + lane * 4 + c;
+        hist_add_peeled(s_hist, e < n_w ? (a[j][c] & 0x7FFFFFFFu) >> 20 : 0xFFFFFFFFu, lane);
+      }
+    }
+    __syncthreads();
+    uint32_t* gh = ghist + (int64_t)td.seg * kHistStride;
+    for (int i = tid; i < kBins0; i += 256) {
+      const uint32_t h = s_hist[i];
+      if (h) atomicAdd(&gh[i], h);
     }
   }
-  __syncthreads();
-  uint32_t* gh = ghist + (int64_t)td.seg * kHistStride;
-  for (int i = tid; i < kBins0; i += 256) {
-    const uint32_t h = s_hist[i];
-    if (h) atomicAdd(&gh[i], h);
+}
+
+// Per large layer: exclusive scan of the chunks' candidate counts, the verdict on the
+// guess (MODE_SPARSE iff no chunk overflowed, at least k candidates, list fits), and, for
+// layers in MODE_DENSE, their tiles appended to the work list of the fallback kernels.
+__global__ __launch_bounds__(1024) void k_cscan(const SegDesc* __restrict__ segs,
+                                                const LargeSeg* __restrict__ lsegs,
+                                                LState* __restrict__ lstate,
+                                                const uint32_t* __restrict__ chunk_cnt,
+                                                uint32_t* __restrict__ chunk_off,
+                                                uint32_t* __restrict__ counters,
+                                                int32_t* __restrict__ items) {
+  __shared__ uint32_t s_wt[16];
+  __shared__ uint32_t s_base;
+  const int li = blockIdx.x;
+  const LargeSeg ls = lsegs[li];
+  const int tid = threadIdx.x;
+  uint32_t mode = MODE_DENSE;
+  if (ls.cand_class != CAND_NONE) {  // uniform over the workgroup
+    uint32_t carry = 0;
+    int over = 0;
+    for (int base = ls.chunk_begin; base < ls.chunk_end; base += 8192) {
+      const int i0 = base + tid * 8;
+      uint32_t v[8], s = 0;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        v[e] = (i0 + e < ls.chunk_end) ? chunk_cnt[i0 + e] : 0u;
+        over |= v[e] > (uint32_t)kSlot;
+        s += v[e];
+      }
+      uint32_t tot;
+      const uint32_t incl = block_incl_scan<1024>(s, s_wt, tot);
+      uint32_t run = carry + incl - s;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        if (i0 + e < ls.chunk_end) chunk_off[i0 + e] = run;
+        run += v[e];
+      }
+      carry += tot;
+    }
+    over = __syncthreads_or(over);
+    const uint32_t k = (uint32_t)segs[ls.seg].k;
+    if (!over && carry >= k && carry <= (uint32_t)ls.cap) mode = MODE_SPARSE;
+    if (tid == 0) lstate[li].ncand = carry;
+  }
+  if (tid == 0) lstate[li].mode = mode;
+  if (mode == MODE_DENSE) {
+    const int nt = ls.tile_end - ls.tile_begin;
+    if (tid == 0) s_base = atomicAdd(&counters[0], (uint32_t)nt);
+    __syncthreads();
+    const uint32_t b = s_base;
+    for (int j = tid; j < nt; j += 1024) items[b + j] = ls.tile_begin + j;
+  }
+}
+
+// Copy the chunks' slots into the layer's contiguous candidate list (index order is kept
+// because chunks are laid out in index order).  One lane per chunk.
+__global__ __launch_bounds__(256) void k_cgather(int n_chunks, const int32_t* __restrict__ chunk_lseg,
+                                                 const LargeSeg* __restrict__ lsegs,
+                                                 const LState* __restrict__ lstate,
+                                                 const uint32_t* __restrict__ chunk_cnt,
+                                                 const uint32_t* __restrict__ chunk_off,
+                                                 const uint2* __restrict__ slots,
+                                                 uint2* __restrict__ cand) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= n_chunks) return;
+  const int li = chunk_lseg[c];
+  if (lstate[li].mode != MODE_SPARSE) return;
+  const uint32_t cnt = chunk_cnt[c];
+  uint2* dst = cand + lsegs[li].cand_base + chunk_off[c];
+  const uint2* src = slots + (int64_t)c * kSlot;
+  for (uint32_t q = 0; q < cnt; ++q) dst[q] = src[q];
+}
+
+// ------------------------------------------------------------------ multi-block select
+// The same radix-select passes serve two sources: CAND = false walks the acc values in
+// the residual buffer (fallback; tiles come from the device-built work list `items`),
+// CAND = true walks a layer's candidate list (tiles of 8192 list entries).
+struct TileWork {
+  float* res;          // dense: the tile's residual data
+  const uint2* cand;   // candidate source: the tile's list entries
+  int n;               // valid entries
+  int lseg;
+  int local0;          // dense: layer-local index of the first element
+  int slot;            // index into tile_gt / tile_eq
+  bool active;         // candidate source: the layer is in MODE_SPARSE
+  bool skip_level0;    // dense: level-0 histogram already made by the streaming pass
+};
+
+// Returns true if the tile has entries to process.
+template <bool CAND>
+__device__ __forceinline__ bool get_tile(int item, const TileDesc* __restrict__ tiles,
+                                         const int32_t* __restrict__ items, float* res,
+                                         const uint2* cand, const LState* __restrict__ lstate, int n_tiles,
+                                         TileWork& tw) {
+  if (CAND) {
+    const TileDesc td = tiles[item];
+    const LState st = lstate[td.seg];
+    tw.lseg = td.seg;
+    tw.slot = n_tiles + item;
+    tw.local0 = td.local0;
+    tw.res = nullptr;
+    tw.cand = cand + td.start;
+    tw.skip_level0 = false;
+    tw.active = st.mode == MODE_SPARSE;
+    const int left = (int)st.ncand - td.local0;
+    tw.n = left < td.n ? left : td.n;
+    return tw.active && tw.n > 0;
+  } else {
+    const int t = items[item];
+    const TileDesc td = tiles[t];
+    tw.lseg = td.seg;
+    tw.slot = t;
+    tw.local0 = td.local0;
+    tw.res = res + td.start;
+    tw.cand = nullptr;
+    tw.n = td.n;
+    tw.active = true;
+    tw.skip_level0 = td.ctile < 0;
+    return true;
+  }
+}
+
+template <bool CAND>
+__device__ __forceinline__ void load_tile(const TileWork& tw, int w, int lane, uint32_t (&a)[kTileV][4]) {
+  const int n_w = tw.n - w * kWaveChunk;
+  if (CAND) {
+    load_cand_bits<kTileV>(tw.cand + w * kWaveChunk, n_w, lane, a);
+  } else {
+    const float* r = tw.res + w * kWaveChunk;
+    load_bits<kTileV>(r, n_w, aligned16(r, r), lane, a);
+  }
+}
+
+// Histogram of one radix digit over the entries whose higher key bits equal the prefix.
+template <int LEVEL, bool CAND>
+__global__ __launch_bounds__(256) void k_hist(const TileDesc* __restrict__ tiles,
+                                              const int32_t* __restrict__ items,
+                                              const uint32_t* __restrict__ counters, int n_tiles,
+                                              float* __restrict__ res,
+                                              const uint2* __restrict__ cand,
+                                              const LState* __restrict__ lstate,
+                                              uint32_t* __restrict__ ghist) {
+  constexpr int shift = LEVEL == 0 ? 20 : (LEVEL == 1 ? 10 : 0);
+  constexpr uint32_t mask = LEVEL == 0 ? 0u : (LEVEL == 1 ? 0x7FF00000u : 0x7FFFFC00u);
+  constexpr int nb = LEVEL == 0 ? kBins0 : kBins12;
+  __shared__ uint32_t s_hist[nb];
+  const int tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
+  const int n_items = CAND ? (int)gridDim.x : (int)counters[0];
+  for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
+    TileWork tw;
+    if (!get_tile<CAND>(item, tiles, items, res, cand, lstate, n_tiles, tw)) continue;
+    if (LEVEL == 0 && tw.skip_level0) continue;
+    __syncthreads();
+    for (int i = tid; i < nb; i += 256) s_hist[i] = 0u;
+    const uint32_t prefix = LEVEL == 0 ? 0u : lstate[tw.lseg].prefix;
+    uint32_t a[kTileV][4];
+    load_tile<CAND>(tw, w, lane, a);
+    const int n_w = tw.n - w * kWaveChunk;
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < kTileV; ++j) {
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const int e = j * 256 + lane * 4 + c;
+        const uint32_t key = a[j][c] & 0x7FFFFFFFu;
+        const bool in = e < n_w && (key & mask) == prefix;
+        if (LEVEL == 0) hist_add_peeled(s_hist, in ? key >> shift : 0xFFFFFFFFu, lane);
+        else if (in) atomicAdd(&s_hist[(key >> shift) & (uint32_t)(nb - 1)], 1u);
+      }
+    }
+    __syncthreads();
+    uint32_t* gh = ghist + (int64_t)tw.lseg * kHistStride;
+    for (int i = tid; i < nb; i += 256) {
+      const uint32_t h = s_hist[i];
+      if (h) atomicAdd(&gh[i], h);
+    }
   }
 }
 
 // Decide one digit of T for every large layer from its histogram, then clear the
-// histogram for the next pass.  One workgroup of 256 threads per layer.
+// histogram for the next pass.  One workgroup of 256 threads per layer.  Layers whose
+// histogram is empty (their selection runs elsewhere) are left alone.
 __global__ __launch_bounds__(256) void k_choose(int level, const LargeSeg* __restrict__ lsegs,
                                                 const SegDesc* __restrict__ segs,
                                                 uint32_t* __restrict__ ghist,
-                                                SegState* __restrict__ state) {
+                                                LState* __restrict__ lstate) {
   __shared__ uint32_t s_wt[4];
   __shared__ uint32_t s_sel[2];
   const int ls = blockIdx.x;
@@ -359,104 +720,80 @@ __global__ __launch_bounds__(256) void k_choose(int level, const LargeSeg* __res
   if (level == 0) {
     k_rem = (uint32_t)segs[lsegs[ls].seg].k;
   } else {
-    const SegState st = state[ls];
-    prefix = st.prefix;
-    k_rem = st.k_rem;
+    prefix = lstate[ls].prefix;
+    k_rem = lstate[ls].k_rem;
   }
+  if (threadIdx.x == 0) { s_sel[0] = 0u; s_sel[1] = 0u; }
+  __syncthreads();
   block_find_bucket<256>(gh, nb, k_rem, s_wt, s_sel);
   const uint32_t b = s_sel[0], kr = s_sel[1];
   __syncthreads();
   for (int i = threadIdx.x; i < nb; i += 256) gh[i] = 0u;
-  if (threadIdx.x == 0) {
-    SegState st;
-    st.prefix = prefix | (b << shift);
-    st.k_rem = kr;
-    state[ls] = st;
-  }
-}
-
-// Passes 2 and 3: histogram of the next 10 key bits over the entries whose higher
-// bits equal the prefix decided so far.
-template <int LEVEL>
-__global__ __launch_bounds__(256) void k_hist(const TileDesc* __restrict__ tiles,
-                                              const float* __restrict__ res,
-                                              const SegState* __restrict__ state,
-                                              uint32_t* __restrict__ ghist) {
-  constexpr int shift = LEVEL == 1 ? 10 : 0;
-  constexpr uint32_t mask = LEVEL == 1 ? 0x7FF00000u : 0x7FFFFC00u;
-  __shared__ uint32_t s_hist[kBins12];
-  const TileDesc td = tiles[blockIdx.x];
-  const int tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
-  for (int i = tid; i < kBins12; i += 256) s_hist[i] = 0u;
-  const uint32_t prefix = state[td.seg].prefix;
-  const float* r = res + td.start + w * kWaveChunk;
-  const int n_w = td.n - w * kWaveChunk;
-  const bool vec = aligned16(r, r);
-  uint32_t a[kTileV][4];
-  load_bits<kTileV>(r, n_w, vec, lane, a);
-  __syncthreads();
-  uint32_t any = 0;
-#pragma unroll
-  for (int j = 0; j < kTileV; ++j) {
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      const int e = j * 256 + lane * 4 + c;
-      const uint32_t key = a[j][c] & 0x7FFFFFFFu;
-      if (e < n_w && (key & mask) == prefix) {
-        atomicAdd(&s_hist[(key >> shift) & (kBins12 - 1)], 1u);
-        any = 1;
-      }
-    }
-  }
-  if (!__syncthreads_or((int)any)) return;
-  uint32_t* gh = ghist + (int64_t)td.seg * kHistStride;
-  for (int i = tid; i < kBins12; i += 256) {
-    const uint32_t h = s_hist[i];
-    if (h) atomicAdd(&gh[i], h);
+  if (threadIdx.x == 0 && kr != 0u) {
+    lstate[ls].prefix = prefix | (b << shift);
+    lstate[ls].k_rem = kr;
   }
 }
 
 // With T known: per tile, how many keys are above T and how many equal T.
+template <bool CAND>
 __global__ __launch_bounds__(256) void k_count(const TileDesc* __restrict__ tiles,
-                                               const float* __restrict__ res,
-                                               const SegState* __restrict__ state,
+                                               const int32_t* __restrict__ items,
+                                               const uint32_t* __restrict__ counters, int n_tiles,
+                                               float* __restrict__ res,
+                                               const uint2* __restrict__ cand,
+                                               const LState* __restrict__ lstate,
                                                uint32_t* __restrict__ tile_gt,
                                                uint32_t* __restrict__ tile_eq) {
   __shared__ uint32_t s_g[4], s_e[4];
-  const TileDesc td = tiles[blockIdx.x];
   const int tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
-  const uint32_t T = state[td.seg].prefix;
-  const float* r = res + td.start + w * kWaveChunk;
-  const int n_w = td.n - w * kWaveChunk;
-  uint32_t a[kTileV][4];
-  load_bits<kTileV>(r, n_w, aligned16(r, r), lane, a);
-  uint32_t cg, ce;
-  lane_count<kTileV>(a, n_w, lane, T, cg, ce);
-  cg = wave_sum(cg);
-  ce = wave_sum(ce);
-  if (lane == 0) { s_g[w] = cg; s_e[w] = ce; }
-  __syncthreads();
-  if (tid == 0) {
-    tile_gt[blockIdx.x] = s_g[0] + s_g[1] + s_g[2] + s_g[3];
-    tile_eq[blockIdx.x] = s_e[0] + s_e[1] + s_e[2] + s_e[3];
+  const int n_items = CAND ? (int)gridDim.x : (int)counters[0];
+  for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
+    TileWork tw;
+    if (!get_tile<CAND>(item, tiles, items, res, cand, lstate, n_tiles, tw)) {
+      // an empty candidate tile of a layer in candidate mode still takes part in the scan
+      if (CAND && tw.active && tid == 0) { tile_gt[tw.slot] = 0u; tile_eq[tw.slot] = 0u; }
+      continue;
+    }
+    const uint32_t T = lstate[tw.lseg].prefix;
+    uint32_t a[kTileV][4];
+    load_tile<CAND>(tw, w, lane, a);
+    uint32_t cg, ce;
+    lane_count<kTileV>(a, tw.n - w * kWaveChunk, lane, T, cg, ce);
+    cg = wave_sum(cg);
+    ce = wave_sum(ce);
+    __syncthreads();
+    if (lane == 0) { s_g[w] = cg; s_e[w] = ce; }
+    __syncthreads();
+    if (tid == 0) {
+      tile_gt[tw.slot] = s_g[0] + s_g[1] + s_g[2] + s_g[3];
+      tile_eq[tw.slot] = s_e[0] + s_e[1] + s_e[2] + s_e[3];
+    }
   }
 }
 
-// Exclusive scan of the per-tile counts inside each large layer (in place).
-__global__ __launch_bounds__(256) void k_scan(const LargeSeg* __restrict__ lsegs,
-                                              uint32_t* __restrict__ tile_gt,
-                                              uint32_t* __restrict__ tile_eq) {
-  __shared__ uint32_t s_wt[4];
+// Exclusive scan of the per-tile counts inside each large layer (in place): over the
+// layer's dense tiles in MODE_DENSE, over its candidate tiles in MODE_SPARSE.
+__global__ __launch_bounds__(1024) void k_scan(const LargeSeg* __restrict__ lsegs,
+                                               const LState* __restrict__ lstate, int n_tiles,
+                                               uint32_t* __restrict__ tile_gt,
+                                               uint32_t* __restrict__ tile_eq) {
+  __shared__ uint32_t s_wt[16];
   const LargeSeg ls = lsegs[blockIdx.x];
+  const uint32_t mode = lstate[blockIdx.x].mode;
+  int begin, end;
+  if (mode == MODE_DENSE) { begin = ls.tile_begin; end = ls.tile_end; }
+  else if (ls.cand_class == CAND_LARGE) { begin = n_tiles + ls.ctile_begin; end = n_tiles + ls.ctile_end; }
+  else return;
   uint32_t carry_g = 0, carry_e = 0;
-  for (int base = ls.tile_begin; base < ls.tile_end; base += 256) {
+  for (int base = begin; base < end; base += 1024) {
     const int i = base + threadIdx.x;
-    const uint32_t vg = i < ls.tile_end ? tile_gt[i] : 0u;
-    const uint32_t ve = i < ls.tile_end ? tile_eq[i] : 0u;
+    const uint32_t vg = i < end ? tile_gt[i] : 0u;
+    const uint32_t ve = i < end ? tile_eq[i] : 0u;
     uint32_t tg, te;
-    const uint32_t ig = block_incl_scan<256>(vg, s_wt, tg);
-    const uint32_t ie = block_incl_scan<256>(ve, s_wt, te);
-    if (i < ls.tile_end) {
+    const uint32_t ig = block_incl_scan<1024>(vg, s_wt, tg);
+    const uint32_t ie = block_incl_scan<1024>(ve, s_wt, te);
+    if (i < end) {
       tile_gt[i] = carry_g + ig - vg;
       tile_eq[i] = carry_e + ie - ve;
     }
@@ -466,40 +803,52 @@ __global__ __launch_bounds__(256) void k_scan(const LargeSeg* __restrict__ lsegs
 }
 
 // Final pass: ordered emission of the kept pairs and zeroing of their residual slots.
+template <bool CAND>
 __global__ __launch_bounds__(256) void k_emit(const TileDesc* __restrict__ tiles,
+                                              const int32_t* __restrict__ items,
+                                              const uint32_t* __restrict__ counters, int n_tiles,
                                               const LargeSeg* __restrict__ lsegs,
                                               const SegDesc* __restrict__ segs,
                                               float* __restrict__ res,
-                                              const SegState* __restrict__ state,
+                                              const uint2* __restrict__ cand,
+                                              const LState* __restrict__ lstate,
                                               const uint32_t* __restrict__ tile_gt,
                                               const uint32_t* __restrict__ tile_eq,
                                               int32_t* __restrict__ out_idx,
                                               float* __restrict__ out_val) {
   __shared__ uint32_t s_g[4], s_e[4];
-  const TileDesc td = tiles[blockIdx.x];
   const int tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
-  const SegState st = state[td.seg];
-  const uint32_t T = st.prefix, rtake = st.k_rem;
-  const uint32_t tg = tile_gt[blockIdx.x], te = tile_eq[blockIdx.x];
-  const SegDesc sd = segs[lsegs[td.seg].seg];
-  const int64_t out_off = sd.out_offset;
-  float* r = res + td.start + w * kWaveChunk;
-  const int n_w = td.n - w * kWaveChunk;
-  const bool vec = aligned16(r, r);
-  uint32_t a[kTileV][4];
-  load_bits<kTileV>(r, n_w, vec, lane, a);
-  uint32_t cg, ce;
-  lane_count<kTileV>(a, n_w, lane, T, cg, ce);
-  cg = wave_sum(cg);
-  ce = wave_sum(ce);
-  if (lane == 0) { s_g[w] = cg; s_e[w] = ce; }
-  __syncthreads();
-  uint32_t gb = tg, eb = te;
-  for (int i = 0; i < w; ++i) { gb += s_g[i]; eb += s_e[i]; }
-  // nothing to emit in this wave if it holds no key above T and its ties come too late
-  if (cg == 0 && (ce == 0 || eb >= rtake)) return;
-  wave_emit<kTileV, false>(a, n_w, lane, T, rtake, gb, eb, (uint32_t)sd.k, td.local0 + w * kWaveChunk,
-                           out_idx + out_off, out_val + out_off, r, vec);
+  const int n_items = CAND ? (int)gridDim.x : (int)counters[0];
+  for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
+    TileWork tw;
+    if (!get_tile<CAND>(item, tiles, items, res, cand, lstate, n_tiles, tw)) continue;
+    const LState st = lstate[tw.lseg];
+    const uint32_t T = st.prefix, rtake = st.k_rem;
+    const uint32_t tg = tile_gt[tw.slot], te = tile_eq[tw.slot];
+    const SegDesc sd = segs[lsegs[tw.lseg].seg];
+    const int n_w = tw.n - w * kWaveChunk;
+    uint32_t a[kTileV][4];
+    load_tile<CAND>(tw, w, lane, a);
+    uint32_t cg, ce;
+    lane_count<kTileV>(a, n_w, lane, T, cg, ce);
+    cg = wave_sum(cg);
+    ce = wave_sum(ce);
+    __syncthreads();
+    if (lane == 0) { s_g[w] = cg; s_e[w] = ce; }
+    __syncthreads();
+    uint32_t gb = tg, eb = te;
+    for (int i = 0; i < w; ++i) { gb += s_g[i]; eb += s_e[i]; }
+    // nothing to emit in this wave if it holds no key above T and its ties come too late
+    if (cg == 0 && (ce == 0 || eb >= rtake)) continue;
+    if (CAND) {
+      wave_emit<kTileV, EMIT_CAND>(a, n_w, lane, T, rtake, gb, eb, (uint32_t)sd.k, 0, out_idx + sd.out_offset,
+                                   out_val + sd.out_offset, res + sd.offset, false, tw.cand + w * kWaveChunk);
+    } else {
+      float* r = tw.res + w * kWaveChunk;
+      wave_emit<kTileV, EMIT_ZERO>(a, n_w, lane, T, rtake, gb, eb, (uint32_t)sd.k, tw.local0 + w * kWaveChunk,
+                                   out_idx + sd.out_offset, out_val + sd.out_offset, r, aligned16(r, r), nullptr);
+    }
+  }
 }
 
 // ------------------------------------------------------------------ merge ----
@@ -564,9 +913,11 @@ __global__ __launch_bounds__(256) void k_merge(const TileDesc* __restrict__ mtil
 
 // ------------------------------------------------------------------ launch ---
 const char* kernel_name(int id) {
-  static const char* names[K_NUM] = {"k_zero_u32", "k_small<4,1>", "k_small<4,8>", "k_small<16,10>",
-                                     "k_accum_hist", "k_choose", "k_hist", "k_count", "k_scan", "k_emit",
-                                     "k_merge"};
+  static const char* names[K_NUM] = {
+      "k_zero_u32", "k_small<4,1>", "k_small<4,8>", "k_small<16,10>", "k_sample", "k_stream", "k_cscan",
+      "k_cgather", "k_small<4,1,cand>", "k_small<4,8,cand>", "k_small<16,10,cand>", "k_hist<cand>",
+      "k_hist<dense>", "k_choose", "k_count<cand>", "k_count<dense>", "k_scan", "k_emit<cand>",
+      "k_emit<dense>", "k_merge"};
   return (id >= 0 && id < K_NUM) ? names[id] : nullptr;
 }
 
@@ -583,49 +934,117 @@ hipError_t launch_small(int cls, int nseg, const SegDesc* segs, const int32_t* l
                         float* res, float lr, int32_t* out_idx, float* out_val, hipStream_t s, Prof* prof) {
   if (nseg <= 0) return hipSuccess;
   ProfScope ps(prof, K_SMALL0 + cls, s);
+  const LargeSeg* nl = nullptr;
+  const LState* ns = nullptr;
+  const uint2* nc = nullptr;
   if (cls == 0)
-    hipLaunchKernelGGL((k_small<4, 1>), dim3(nseg), dim3(256), 0, s, segs, list, grad, res, lr, out_idx, out_val);
+    hipLaunchKernelGGL((k_small<4, 1, false>), dim3(nseg), dim3(256), 0, s, segs, list, nl, ns, nc, grad, res, lr,
+                       out_idx, out_val);
   else if (cls == 1)
-    hipLaunchKernelGGL((k_small<4, 8>), dim3(nseg), dim3(256), 0, s, segs, list, grad, res, lr, out_idx, out_val);
+    hipLaunchKernelGGL((k_small<4, 8, false>), dim3(nseg), dim3(256), 0, s, segs, list, nl, ns, nc, grad, res, lr,
+                       out_idx, out_val);
   else
-    hipLaunchKernelGGL((k_small<16, 10>), dim3(nseg), dim3(1024), 0, s, segs, list, grad, res, lr, out_idx, out_val);
+    hipLaunchKernelGGL((k_small<16, 10, false>), dim3(nseg), dim3(1024), 0, s, segs, list, nl, ns, nc, grad, res,
+                       lr, out_idx, out_val);
   return hipGetLastError();
 }
 
-hipError_t launch_large(int n_large, int n_tiles, const SegDesc* segs, const LargeSeg* lsegs,
-                        const TileDesc* tiles, const float* grad, float* res, float lr,
-                        int32_t* out_idx, float* out_val, uint32_t* ghist, SegState* state,
-                        uint32_t* tile_gt, uint32_t* tile_eq, hipStream_t s, Prof* prof) {
-  if (n_large <= 0) return hipSuccess;
-  hipError_t e = launch_zero_u32(ghist, (int64_t)n_large * kHistStride, s, prof);
+hipError_t launch_large(const LargePlan& pl, const Scratch& sc, const SegDesc* segs, const float* grad,
+                        float* res, float lr, int32_t* out_idx, float* out_val, hipStream_t s, Prof* prof) {
+  if (pl.n_large <= 0) return hipSuccess;
+  hipError_t e = launch_zero_u32(sc.counters, 16, s, prof);
   if (e != hipSuccess) return e;
-  {
-    ProfScope ps(prof, K_ACCUM_HIST, s);
-    hipLaunchKernelGGL(k_accum_hist, dim3(n_tiles), dim3(256), 0, s, tiles, grad, res, lr, ghist);
+  e = launch_zero_u32(sc.ghist, (int64_t)pl.n_large * kHistStride, s, prof);
+  if (e != hipSuccess) return e;
+  if (pl.n_sampled > 0) {
+    ProfScope ps(prof, K_SAMPLE, s);
+    hipLaunchKernelGGL(k_sample, dim3(pl.n_sampled), dim3(1024), 0, s, segs, pl.sampled, pl.lsegs, grad, res, lr,
+                       sc.lstate);
   }
+  {
+    ProfScope ps(prof, K_STREAM, s);
+    hipLaunchKernelGGL(k_stream, dim3(pl.n_tiles), dim3(256), 0, s, pl.tiles, grad, res, lr, sc.lstate,
+                       sc.chunk_cnt, sc.slots, sc.ghist);
+  }
+  {
+    ProfScope ps(prof, K_CSCAN, s);
+    hipLaunchKernelGGL(k_cscan, dim3(pl.n_large), dim3(1024), 0, s, segs, pl.lsegs, sc.lstate, sc.chunk_cnt,
+                       sc.chunk_off, sc.counters, sc.items);
+  }
+  if (pl.n_chunks > 0) {
+    ProfScope ps(prof, K_CGATHER, s);
+    hipLaunchKernelGGL(k_cgather, dim3((pl.n_chunks + 255) / 256), dim3(256), 0, s, pl.n_chunks, pl.chunk_lseg,
+                       pl.lsegs, sc.lstate, sc.chunk_cnt, sc.chunk_off, sc.slots, sc.cand);
+  }
+  const float* ng = nullptr;
+  if (pl.n_cand_small[0] > 0) {
+    ProfScope ps(prof, K_CSMALL0, s);
+    hipLaunchKernelGGL((k_small<4, 1, true>), dim3(pl.n_cand_small[0]), dim3(256), 0, s, segs, pl.cand_small[0],
+                       pl.lsegs, sc.lstate, sc.cand, ng, res, lr, out_idx, out_val);
+  }
+  if (pl.n_cand_small[1] > 0) {
+    ProfScope ps(prof, K_CSMALL1, s);
+    hipLaunchKernelGGL((k_small<4, 8, true>), dim3(pl.n_cand_small[1]), dim3(256), 0, s, segs, pl.cand_small[1],
+                       pl.lsegs, sc.lstate, sc.cand, ng, res, lr, out_idx, out_val);
+  }
+  if (pl.n_cand_small[2] > 0) {
+    ProfScope ps(prof, K_CSMALL2, s);
+    hipLaunchKernelGGL((k_small<16, 10, true>), dim3(pl.n_cand_small[2]), dim3(1024), 0, s, segs,
+                       pl.cand_small[2], pl.lsegs, sc.lstate, sc.cand, ng, res, lr, out_idx, out_val);
+  }
+  const dim3 gc(pl.n_ctiles > 0 ? pl.n_ctiles : 1), gd(kDenseGrid), b(256);
   for (int level = 0; level < 3; ++level) {
-    if (level == 1) {
-      ProfScope ps(prof, K_HIST, s);
-      hipLaunchKernelGGL(k_hist<1>, dim3(n_tiles), dim3(256), 0, s, tiles, res, state, ghist);
-    } else if (level == 2) {
-      ProfScope ps(prof, K_HIST, s);
-      hipLaunchKernelGGL(k_hist<2>, dim3(n_tiles), dim3(256), 0, s, tiles, res, state, ghist);
+    if (pl.n_ctiles > 0) {
+      ProfScope ps(prof, K_HIST_CAND, s);
+      if (level == 0)
+        hipLaunchKernelGGL((k_hist<0, true>), gc, b, 0, s, pl.ctiles, sc.items, sc.counters, pl.n_tiles, res,
+                           sc.cand, sc.lstate, sc.ghist);
+      else if (level == 1)
+        hipLaunchKernelGGL((k_hist<1, true>), gc, b, 0, s, pl.ctiles, sc.items, sc.counters, pl.n_tiles, res,
+                           sc.cand, sc.lstate, sc.ghist);
+      else
+        hipLaunchKernelGGL((k_hist<2, true>), gc, b, 0, s, pl.ctiles, sc.items, sc.counters, pl.n_tiles, res,
+                           sc.cand, sc.lstate, sc.ghist);
+    }
+    {
+      ProfScope ps(prof, K_HIST_DENSE, s);
+      if (level == 0)
+        hipLaunchKernelGGL((k_hist<0, false>), gd, b, 0, s, pl.tiles, sc.items, sc.counters, pl.n_tiles, res,
+                           sc.cand, sc.lstate, sc.ghist);
+      else if (level == 1)
+        hipLaunchKernelGGL((k_hist<1, false>), gd, b, 0, s, pl.tiles, sc.items, sc.counters, pl.n_tiles, res,
+                           sc.cand, sc.lstate, sc.ghist);
+      else
+        hipLaunchKernelGGL((k_hist<2, false>), gd, b, 0, s, pl.tiles, sc.items, sc.counters, pl.n_tiles, res,
+                           sc.cand, sc.lstate, sc.ghist);
     }
     ProfScope ps(prof, K_CHOOSE, s);
-    hipLaunchKernelGGL(k_choose, dim3(n_large), dim3(256), 0, s, level, lsegs, segs, ghist, state);
+    hipLaunchKernelGGL(k_choose, dim3(pl.n_large), b, 0, s, level, pl.lsegs, segs, sc.ghist, sc.lstate);
+  }
+  if (pl.n_ctiles > 0) {
+    ProfScope ps(prof, K_COUNT_CAND, s);
+    hipLaunchKernelGGL((k_count<true>), gc, b, 0, s, pl.ctiles, sc.items, sc.counters, pl.n_tiles, res, sc.cand,
+                       sc.lstate, sc.tile_gt, sc.tile_eq);
   }
   {
-    ProfScope ps(prof, K_COUNT, s);
-    hipLaunchKernelGGL(k_count, dim3(n_tiles), dim3(256), 0, s, tiles, res, state, tile_gt, tile_eq);
+    ProfScope ps(prof, K_COUNT_DENSE, s);
+    hipLaunchKernelGGL((k_count<false>), gd, b, 0, s, pl.tiles, sc.items, sc.counters, pl.n_tiles, res, sc.cand,
+                       sc.lstate, sc.tile_gt, sc.tile_eq);
   }
   {
     ProfScope ps(prof, K_SCAN, s);
-    hipLaunchKernelGGL(k_scan, dim3(n_large), dim3(256), 0, s, lsegs, tile_gt, tile_eq);
+    hipLaunchKernelGGL(k_scan, dim3(pl.n_large), dim3(1024), 0, s, pl.lsegs, sc.lstate, pl.n_tiles, sc.tile_gt,
+                       sc.tile_eq);
+  }
+  if (pl.n_ctiles > 0) {
+    ProfScope ps(prof, K_EMIT_CAND, s);
+    hipLaunchKernelGGL((k_emit<true>), gc, b, 0, s, pl.ctiles, sc.items, sc.counters, pl.n_tiles, pl.lsegs, segs,
+                       res, sc.cand, sc.lstate, sc.tile_gt, sc.tile_eq, out_idx, out_val);
   }
   {
-    ProfScope ps(prof, K_EMIT, s);
-    hipLaunchKernelGGL(k_emit, dim3(n_tiles), dim3(256), 0, s, tiles, lsegs, segs, res, state, tile_gt,
-                       tile_eq, out_idx, out_val);
+    ProfScope ps(prof, K_EMIT_DENSE, s);
+    hipLaunchKernelGGL((k_emit<false>), gd, b, 0, s, pl.tiles, sc.items, sc.counters, pl.n_tiles, pl.lsegs, segs,
+                       res, sc.cand, sc.lstate, sc.tile_gt, sc.tile_eq, out_idx, out_val);
   }
   return hipGetLastError();
 }

@@ -48,6 +48,8 @@ def lib():
         L.lags_merge_sparse.restype = ctypes.c_int
         L.lags_merge_sparse.argtypes = [vp, vp, vp, vp, i32, i64, vp, vp]
         L.lags_strerror.restype, L.lags_strerror.argtypes = ctypes.c_char_p, [ctypes.c_int]
+        L.lags_last_routes.restype = ctypes.c_int
+        L.lags_last_routes.argtypes = [vp, vp, ctypes.POINTER(i32), i32]
         L.lags_profile_enable.restype, L.lags_profile_enable.argtypes = ctypes.c_int, [vp, ctypes.c_int]
         L.lags_profile_num_kernels.restype, L.lags_profile_num_kernels.argtypes = ctypes.c_int, []
         L.lags_profile_kernel_name.restype, L.lags_profile_kernel_name.argtypes = ctypes.c_char_p, [ctypes.c_int]
@@ -149,6 +151,12 @@ class Context:
     def lags_merge_sparse(self, table, idx, val, P, stride_k, update_flat, stream=None):
         _check(lib().lags_merge_sparse(self.handle, table.handle, _ptr(idx), _ptr(val), int(P), int(stride_k),
                                        _ptr(update_flat), _stream(stream)), "lags_merge_sparse")
+
+    def lags_last_routes(self, table):
+        """Route code per layer of the last lags_sparsify_model call with `table` (diagnostic)."""
+        arr = (ctypes.c_int32 * table.n)()
+        _check(lib().lags_last_routes(self.handle, table.handle, arr, table.n), "lags_last_routes")
+        return list(arr)
 
     def lags_profile_enable(self, on):
         _check(lib().lags_profile_enable(self.handle, int(bool(on))), "lags_profile_enable")

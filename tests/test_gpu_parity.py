@@ -184,6 +184,94 @@ def test_config_resnet50_reduced(gpu, oracle):
     _run_config(gpu, oracle, wl, 3, 2)
 
 
+def _check_table(gpu, oracle, layers, g, r0, lr, want_routes=None):
+    table = gpu.ctx.table(layers)
+    want_r = r0.copy()
+    wi, wv = oracle_model_parallel(oracle, layers, g, want_r, lr)
+    gi, gv, gr = gpu.sparsify_model(layers, g, r0, lr, table=table)
+    routes = gpu.ctx.lags_last_routes(table)
+    table.destroy()
+    assert_same("idx", gi, wi)
+    assert_same("val", gv, wv)
+    assert_same("res", gr, want_r)
+    if want_routes is not None:
+        assert routes == want_routes, routes
+    return routes
+
+
+def test_sampled_route_is_taken_and_exact(gpu, oracle):
+    """Large layers with smooth value distributions go through the sampled threshold
+    (route 1) with short and with multi-tile candidate lists; results equal the oracle."""
+    rng = np.random.default_rng(51)
+    sizes = [(1 << 20, 0.001), (3_000_017, 0.01), (70_001, 0.001), (500_000, 0.02), (41_000, 0.005),
+             (2_500_000, 0.0004)]
+    layers, off = [], 0
+    for d, rho in sizes:
+        layers.append((off, d, rho))
+        off += d
+    g = rng.standard_normal(off).astype(np.float32)
+    g[: 1 << 20] = rng.laplace(size=1 << 20).astype(np.float32)
+    r0 = (0.5 * rng.standard_normal(off)).astype(np.float32)
+    note("sampled route, smooth data")
+    routes = _check_table(gpu, oracle, layers, g, r0, 0.1)
+    assert routes == [1] * len(sizes), routes
+
+
+def test_sampled_route_rejections_fall_back(gpu, oracle):
+    """Inputs on which the guessed threshold cannot work (all equal, all zero, few non-zeros,
+    heavy ties, a k that is most of the layer) take the exact fallback and match the oracle;
+    a layer with clustered large values may overflow single chunks and fall back too."""
+    rng = np.random.default_rng(52)
+    d = 300_000
+    cases = {
+        "zeros": np.zeros(d, np.float32),
+        "equal": np.full(d, 3.25, np.float32),
+        "few_nonzero": np.where(rng.random(d) < 0.0005, rng.standard_normal(d), 0.0).astype(np.float32),
+        "narrow": (1.0 + 1e-4 * rng.random(d)).astype(np.float32),
+        "ties": rng.integers(-2, 3, d).astype(np.float32),
+        "clustered": np.where(np.arange(d) // 3000 % 10 == 0, 50.0, 1.0).astype(np.float32)
+                     * rng.standard_normal(d).astype(np.float32),
+    }
+    for name, g in cases.items():
+        for rho in (0.001, 0.01):
+            note("rejection case %s rho=%g" % (name, rho))
+            routes = _check_table(gpu, oracle, [(0, d, rho)], g, np.zeros(d, np.float32), 1.0)
+            assert routes[0] in (1, 2)
+            if name in ("zeros", "equal"):
+                assert routes == [2], (name, routes)
+            if name == "narrow":          # the threshold is a full 31-bit key, so one radix bin is no obstacle
+                assert routes == [1], (name, routes)
+    note("rejection case large k")
+    g = rng.standard_normal(d).astype(np.float32)
+    assert _check_table(gpu, oracle, [(0, d, 0.5)], g, np.zeros(d, np.float32), 1.0) == [3]
+
+
+def test_mixed_routes_in_one_table(gpu, oracle):
+    """One table whose layers take all four routes at once, over several iterations."""
+    rng = np.random.default_rng(53)
+    sizes = [(100, 0.01), (200_000, 0.002), (60_000, 0.6), (150_000, 0.001), (9000, 0.001), (1_200_000, 0.003)]
+    layers, off = [], 0
+    for d, rho in sizes:
+        layers.append((off, d, rho))
+        off += d + 3
+    table = gpu.ctx.table(layers)
+    res_g = np.zeros(off, np.float32)
+    res_c = np.zeros(off, np.float32)
+    for it in range(4):
+        g = rng.standard_normal(off).astype(np.float32)
+        g[layers[3][0]:layers[3][0] + layers[3][1]] = 0.0 if it < 2 else 1.0     # zero layer -> fallback
+        note("mixed routes iteration %d" % it)
+        wi, wv = oracle_model_parallel(oracle, layers, g, res_c, 0.1)
+        gi, gv, res_g = gpu.sparsify_model(layers, g, res_g, 0.1, table=table)
+        routes = gpu.ctx.lags_last_routes(table)
+        assert_same("idx", gi, wi)
+        assert_same("val", gv, wv)
+        assert_same("res", res_g, res_c)
+        assert routes[0] == 0 and routes[4] == 0 and routes[1] == 1 and routes[5] == 1 and routes[2] == 3
+        assert routes[3] == 2
+    table.destroy()
+
+
 def test_merge_closed_forms(gpu, oracle):
     """P = 1 is a scatter; many workers on one index sum in worker order; division is a
     true division (P = 3, 7); indices spread over several merge tiles; P > 64."""
