@@ -140,8 +140,8 @@ bool plan_sample(int64_t d, int64_t k, LargeSeg* ls) {
   // deviations of the sampled count plus a constant, so that fewer than k is very unlikely
   const double jd = std::ceil(fk + 6.0 * std::sqrt(fk) + 20.0);
   if (jd > m) return false;
-  // expected candidates per chunk of 2048 elements must stay well inside its slots
-  if (jd / m * (double)kWaveChunk > (double)kSlot * 0.5) return false;
+  // expected candidates per tile must stay well inside the tile's slots
+  if (jd / m * (double)kTile > (double)kSlot * 0.5) return false;
   const double expect = jd / m * (double)d;
   const int64_t cap = std::min<int64_t>(d, (int64_t)(2.0 * expect) + 8192);
   ls->sample_rank = (int32_t)jd;
@@ -165,7 +165,7 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
   t->n = n;
   std::vector<int32_t> small[3], cand_small[3], sampled, chunk_lseg;
   std::vector<TileDesc> tiles, ctiles, mtiles;
-  int64_t n_ctile_dense = 0;   // dense tiles of sampled layers (they own 4 chunks each)
+  int64_t n_ctile_dense = 0;   // tiles of sampled layers: each owns kSlot candidate slots
   int64_t cand_total = 0;
   constexpr int64_t kMaxTiles = 1 << 28;
   try {
@@ -195,7 +195,7 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
         const int64_t nt = (d[l] + kTile - 1) / kTile;
         if ((int64_t)tiles.size() + nt > kMaxTiles) { delete t; return LAGS_ECAPACITY; }
         if (sampled_layer) {
-          ls.chunk_begin = (int32_t)(n_ctile_dense * kTileWaves);
+          ls.chunk_begin = (int32_t)n_ctile_dense;
           ls.cand_base = cand_total;
           cand_total += ls.cap;
           sampled.push_back(li);
@@ -225,12 +225,12 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
           td.ctile = sampled_layer ? (int32_t)n_ctile_dense : -1;
           if (sampled_layer) {
             ++n_ctile_dense;
-            for (int w = 0; w < kTileWaves; ++w) chunk_lseg.push_back(li);
+            chunk_lseg.push_back(li);
           }
           tiles.push_back(td);
         }
         ls.tile_end = (int32_t)tiles.size();
-        if (sampled_layer) ls.chunk_end = (int32_t)(n_ctile_dense * kTileWaves);
+        if (sampled_layer) ls.chunk_end = (int32_t)n_ctile_dense;
         t->lsegs.push_back(ls);
       }
       const int64_t nmt = (d[l] + kMergeTile - 1) / kMergeTile;

@@ -8,12 +8,13 @@
 namespace lags {
 
 // Geometry of the multi-block ("large") path: one workgroup of 4 waves per tile,
-// each wave owns a contiguous quarter of the tile (a "chunk") and walks it in rounds
-// of 64 lanes x 4 consecutive elements.
+// each wave owns a contiguous quarter of the tile and walks it in rounds of 64 lanes x 4
+// consecutive elements.  A tile of a sampled layer is also the unit ("chunk") that owns
+// kSlot candidate slots.
 constexpr int kTileWaves = 4;
-constexpr int kTileV = 8;                               // rounds per wave
-constexpr int kWaveChunk = kTileV * 256;                // 2048 elements per wave
-constexpr int kTile = kTileWaves * kWaveChunk;          // 8192 elements per tile
+constexpr int kTileV = 4;                               // rounds per wave
+constexpr int kWaveChunk = kTileV * 256;                // 1024 elements per wave
+constexpr int kTile = kTileWaves * kWaveChunk;          // 4096 elements per tile
 constexpr int kBins0 = 2048;                            // key bits 30..20
 constexpr int kBins12 = 1024;                           // key bits 19..10, 9..0
 constexpr int kHistStride = 2048;
@@ -27,7 +28,7 @@ constexpr int kSmall2 = 16 * 10 * 256;   // <= 40960 : 16 waves, 10 rounds
 constexpr int kSamplePiece = 64;
 constexpr int kSamplePieces = 1024;
 constexpr int kSampleMax = kSamplePiece * kSamplePieces;   // 65536 sampled elements
-constexpr int kSlot = 128;               // candidate slots per chunk of 2048 elements
+constexpr int kSlot = 256;               // candidate slots per tile of a sampled layer
 constexpr int kDenseGrid = 2048;         // workgroups of the fallback kernels (grid-stride)
 
 constexpr int kMergeTile = 8192;
@@ -45,7 +46,7 @@ struct TileDesc {       // one tile of a layer (dense tiles, candidate tiles, me
   int32_t n;            // elements in the tile (<= tile size); candidate tiles: capacity
   int32_t seg;          // large path: index among the large layers; merge: layer index
   int32_t local0;       // layer-local index (candidate tiles: list position) of the first element
-  int32_t ctile;        // dense tiles of sampled layers: index among those tiles; else -1
+  int32_t ctile;        // dense tiles of sampled layers: index among those tiles ("chunk"); else -1
 };
 
 enum : int32_t { CAND_NONE = 0, CAND_SMALL0 = 1, CAND_SMALL1 = 2, CAND_SMALL2 = 3, CAND_LARGE = 4 };
@@ -55,7 +56,7 @@ struct LargeSeg {       // static plan of one large layer
   int32_t seg;          // layer index
   int32_t tile_begin;   // dense tiles [tile_begin, tile_end)
   int32_t tile_end;
-  int32_t chunk_begin;  // chunks of the sampled tiles [chunk_begin, chunk_end), or 0,0
+  int32_t chunk_begin;  // sampled layers: their tiles' ctile numbers [chunk_begin, chunk_end), else 0,0
   int32_t chunk_end;
   int32_t cand_class;   // CAND_NONE: not sampled
   int32_t cap;          // capacity of the candidate list
@@ -85,7 +86,7 @@ struct LargePlan {      // everything launch_large needs (device pointers + coun
   const TileDesc* ctiles = nullptr;     // candidate tiles of CAND_LARGE layers
   const int32_t* sampled = nullptr;     // large-layer indices that are sampled
   const int32_t* cand_small[3] = {nullptr, nullptr, nullptr};  // large-layer indices per class
-  const int32_t* chunk_lseg = nullptr;  // chunk -> large-layer index
+  const int32_t* chunk_lseg = nullptr;  // chunk (sampled tile) -> large-layer index
 };
 
 struct Scratch {        // context-owned device memory, contents meaningless between calls

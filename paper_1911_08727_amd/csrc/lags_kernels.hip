@@ -451,11 +451,15 @@ __global__ __launch_bounds__(1024) void k_sample(const SegDesc* __restrict__ seg
 }
 
 // ------------------------------------------------------------------ stream ---
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
 // The one pass over grad and residual of every large layer: acc = residual + lr*grad is
 // written into the residual buffer (it is the final residual everywhere but at the k kept
-// entries).  Tiles of sampled layers also collect, per chunk and in index order, the
-// entries with key >= tau into the chunk's slots; tiles of the other layers add to the
-// layer's histogram of key bits 30..20.
+// entries).  Tiles of sampled layers also collect, in index order, the entries with
+// key >= tau into the tile's slots; tiles of the other layers add to the layer's histogram
+// of key bits 30..20.  Both arrays are touched exactly once, so full aligned tiles use
+// non-temporal 16-byte loads and stores.
 __global__ __launch_bounds__(256) void k_stream(const TileDesc* __restrict__ tiles,
                                                 const float* __restrict__ grad,
                                                 float* __restrict__ res, float lr,
@@ -464,6 +468,7 @@ __global__ __launch_bounds__(256) void k_stream(const TileDesc* __restrict__ til
                                                 uint2* __restrict__ slots,
                                                 uint32_t* __restrict__ ghist) {
   __shared__ uint32_t s_hist[kBins0];
+  __shared__ uint32_t s_cnt[kTileWaves];
   const TileDesc td = tiles[blockIdx.x];
   const int tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
   const bool collect = td.ctile >= 0;  // uniform over the workgroup
@@ -478,34 +483,74 @@ __global__ __launch_bounds__(256) void k_stream(const TileDesc* __restrict__ til
   const int n_w = td.n - w * kWaveChunk;
   const bool vec = aligned16(g, r);
   uint32_t a[kTileV][4];
-  load_acc<kTileV>(g, r, n_w, lr, vec, lane, a);
-  store_bits<kTileV>(r, n_w, vec, lane, a);
-  if (collect) {
-    const int chunk = td.ctile * kTileWaves + w;
-    uint2* slot = slots + (int64_t)chunk * kSlot;
-    const int32_t idx0 = td.local0 + w * kWaveChunk;
-    uint32_t base = 0;
+  if (vec && td.n == kTile) {  // uniform over the workgroup
+    f32x4 gv[kTileV], rv[kTileV];
 #pragma unroll
     for (int j = 0; j < kTileV; ++j) {
       const int e = j * 256 + lane * 4;
-      bool f[4];
+      gv[j] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(g + e));
+      rv[j] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(r + e));
+    }
 #pragma unroll
-      for (int c = 0; c < 4; ++c) f[c] = (e + c < n_w) && ((a[j][c] & 0x7FFFFFFFu) >= tau);
-      const uint64_t b0 = __ballot(f[0]), b1 = __ballot(f[1]), b2 = __ballot(f[2]), b3 = __ballot(f[3]);
-      const uint32_t tot = (uint32_t)(__popcll(b0) + __popcll(b1) + __popcll(b2) + __popcll(b3));
-      if (tot) {  // wave-uniform
-        uint32_t pos = base + mbcnt64(b0) + mbcnt64(b1) + mbcnt64(b2) + mbcnt64(b3);
+    for (int j = 0; j < kTileV; ++j) {
+      const int e = j * 256 + lane * 4;
+      a[j][0] = acc_bits(gv[j].x, rv[j].x, lr);
+      a[j][1] = acc_bits(gv[j].y, rv[j].y, lr);
+      a[j][2] = acc_bits(gv[j].z, rv[j].z, lr);
+      a[j][3] = acc_bits(gv[j].w, rv[j].w, lr);
+      u32x4 o;
+      o.x = a[j][0]; o.y = a[j][1]; o.z = a[j][2]; o.w = a[j][3];
+      __builtin_nontemporal_store(o, reinterpret_cast<u32x4*>(r + e));
+    }
+  } else {
+    load_acc<kTileV>(g, r, n_w, lr, vec, lane, a);
+    store_bits<kTileV>(r, n_w, vec, lane, a);
+  }
+  if (collect) {
+    // candidates of the wave, then its position among the tile's waves
+    uint32_t wtot = 0;
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          if (f[c]) {
-            if (pos < (uint32_t)kSlot) slot[pos] = make_uint2((uint32_t)(idx0 + e + c), a[j][c]);
-            ++pos;
-          }
-        }
-        base += tot;
+    for (int j = 0; j < kTileV; ++j) {
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const int e = j * 256 + lane * 4 + c;
+        wtot += (uint32_t)__popcll(__ballot(e < n_w && (a[j][c] & 0x7FFFFFFFu) >= tau));
       }
     }
-    if (lane == 0) chunk_cnt[chunk] = base;  // a count above kSlot marks the chunk as overflowed
+    if (lane == 0) s_cnt[w] = wtot;
+    __syncthreads();
+    uint32_t base = 0, total = 0;
+#pragma unroll
+    for (int i = 0; i < kTileWaves; ++i) {
+      const uint32_t t = s_cnt[i];
+      if (i < w) base += t;
+      total += t;
+    }
+    if (tid == 0) chunk_cnt[td.ctile] = total;  // a count above kSlot marks the tile as overflowed
+    if (wtot) {  // wave-uniform
+      uint2* slot = slots + (int64_t)td.ctile * kSlot;
+      const int32_t idx0 = td.local0 + w * kWaveChunk;
+#pragma unroll
+      for (int j = 0; j < kTileV; ++j) {
+        const int e = j * 256 + lane * 4;
+        bool f[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) f[c] = (e + c < n_w) && ((a[j][c] & 0x7FFFFFFFu) >= tau);
+        const uint64_t b0 = __ballot(f[0]), b1 = __ballot(f[1]), b2 = __ballot(f[2]), b3 = __ballot(f[3]);
+        const uint32_t tot = (uint32_t)(__popcll(b0) + __popcll(b1) + __popcll(b2) + __popcll(b3));
+        if (tot) {  // wave-uniform
+          uint32_t pos = base + mbcnt64(b0) + mbcnt64(b1) + mbcnt64(b2) + mbcnt64(b3);
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            if (f[c]) {
+              if (pos < (uint32_t)kSlot) slot[pos] = make_uint2((uint32_t)(idx0 + e + c), a[j][c]);
+              ++pos;
+            }
+          }
+          base += tot;
+        }
+      }
+    }
   } else {
     __syncthreads();
 #pragma unroll
@@ -578,8 +623,8 @@ __global__ __launch_bounds__(1024) void k_cscan(const SegDesc* __restrict__ segs
   }
 }
 
-// Copy the chunks' slots into the layer's contiguous candidate list (index order is kept
-// because chunks are laid out in index order).  One lane per chunk.
+// Copy the tiles' slots into the layer's contiguous candidate list (index order is kept
+// because tiles are laid out in index order).  One lane per tile.
 __global__ __launch_bounds__(256) void k_cgather(int n_chunks, const int32_t* __restrict__ chunk_lseg,
                                                  const LargeSeg* __restrict__ lsegs,
                                                  const LState* __restrict__ lstate,
@@ -600,7 +645,7 @@ __global__ __launch_bounds__(256) void k_cgather(int n_chunks, const int32_t* __
 // ------------------------------------------------------------------ multi-block select
 // The same radix-select passes serve two sources: CAND = false walks the acc values in
 // the residual buffer (fallback; tiles come from the device-built work list `items`),
-// CAND = true walks a layer's candidate list (tiles of 8192 list entries).
+// CAND = true walks a layer's candidate list (tiles of kTile list entries).
 struct TileWork {
   float* res;          // dense: the tile's residual data
   const uint2* cand;   // candidate source: the tile's list entries

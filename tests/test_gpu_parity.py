@@ -50,7 +50,7 @@ def _values(kind, d, rng):
 KINDS = ["normal", "ties", "zeros", "equal", "signed_zeros", "denormal", "mostly_zero", "narrow", "inf"]
 # sizes around every boundary of the launch plan: vector width, wave, small classes, tile
 SIZES = [1, 2, 3, 4, 5, 63, 64, 65, 255, 256, 257, 1023, 1024, 1025, 4100, 8191, 8192, 8193,
-         40959, 40960, 40961, 3 * 8192, 3 * 8192 + 5, 100003]
+         40959, 40960, 40961, 45055, 45056, 45057, 3 * 8192, 3 * 8192 + 5, 100003]
 
 
 def _ks(d, rng):
