@@ -23,6 +23,19 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 
 
+def measured_traffic(kernel, workload, workers):
+    """HBM bytes per launch of `kernel` for this workload from the committed rocprofv3 counter
+    summary (profiles/*.txt, line 'TRAFFIC_BYTES_PER_LAUNCH <kernel> <workload> P=<workers>: <bytes>'),
+    or None if no summary covers it."""
+    import glob
+    key = "TRAFFIC_BYTES_PER_LAUNCH %s %s P=%d:" % (kernel, workload, workers)
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*.txt"))):
+        for line in open(path):
+            if line.startswith(key):
+                return float(line.split(":")[1])
+    return None
+
+
 def cpu_baseline(wl, grad0_host, threads):
     """The oracle as it stands on the host cores: worker 0, one iteration, every layer,
     layers spread over `threads` host threads."""
@@ -137,7 +150,7 @@ def main():
     # a kernel launched several times per step (e.g. k_hist) shares the per-step algorithmic bytes
     achieved = bpe * kel.get(dom, elements) / (dom_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(dom, wl.name, P),
                 "avg_kernel_ms": round(dom_ms, 4), "launches_per_step": launches_per_step,
                 "bytes_per_element": round(bpe, 4), "elements_per_launch": kel.get(dom, elements)}
     kernels = {k: {"ms_per_step": round(v[0] / args.steps, 4), "launches_per_step": v[1] / args.steps}
