@@ -37,6 +37,7 @@ struct lags_ctx {
   int device = 0;
   // scratch of the multi-block path, sized for the largest table created so far
   DevBuf counters, ghist, lstate, tile_gt, tile_eq, items, chunk_cnt, chunk_off, slots, cand;
+  DevBuf bounds;   // merge: P rows of tile start positions, sized at the first merge call that needs it
   std::map<std::pair<int64_t, int64_t>, lags_table*> layer_tables;  // (d, k) -> one-layer table
   Prof prof;
   Scratch scratch() const {
@@ -63,7 +64,7 @@ struct lags_table {
   std::vector<SegDesc> segs;                   // host copy
   std::vector<LargeSeg> lsegs;                 // host copy
   int n_small[3] = {0, 0, 0};
-  int n_mtiles = 0;
+  int n_mtiles = 0, n_bchunks = 0;
   LargePlan plan;                              // device pointers below, owned by the table
   SegDesc* d_segs = nullptr;
   int32_t* d_small[3] = {nullptr, nullptr, nullptr};
@@ -71,6 +72,7 @@ struct lags_table {
   TileDesc* d_tiles = nullptr;
   TileDesc* d_ctiles = nullptr;
   TileDesc* d_mtiles = nullptr;
+  BChunk* d_bchunks = nullptr;
   int32_t* d_sampled = nullptr;
   int32_t* d_cand_small[3] = {nullptr, nullptr, nullptr};
   int32_t* d_chunk_lseg = nullptr;
@@ -118,6 +120,7 @@ void free_table_device(lags_table* t) {
   if (t->d_tiles) (void)hipFree(t->d_tiles);
   if (t->d_ctiles) (void)hipFree(t->d_ctiles);
   if (t->d_mtiles) (void)hipFree(t->d_mtiles);
+  if (t->d_bchunks) (void)hipFree(t->d_bchunks);
   if (t->d_sampled) (void)hipFree(t->d_sampled);
   if (t->d_chunk_lseg) (void)hipFree(t->d_chunk_lseg);
 }
@@ -165,6 +168,7 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
   t->n = n;
   std::vector<int32_t> small[3], cand_small[3], sampled, chunk_lseg;
   std::vector<TileDesc> tiles, ctiles, mtiles;
+  std::vector<BChunk> bchunks;
   int64_t n_ctile_dense = 0;   // tiles of sampled layers: each owns kSlot candidate slots
   int64_t cand_total = 0;
   constexpr int64_t kMaxTiles = 1 << 28;
@@ -235,6 +239,14 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
       }
       const int64_t nmt = (d[l] + kMergeTile - 1) / kMergeTile;
       if ((int64_t)mtiles.size() + nmt > kMaxTiles) { delete t; return LAGS_ECAPACITY; }
+      for (int64_t j0 = 0; j0 < k[l]; j0 += kBoundChunk) {
+        BChunk bc;
+        bc.seg = l;
+        bc.j0 = (int32_t)j0;
+        bc.slot0 = (int32_t)mtiles.size() + l;   // every earlier layer owns one extra (end) slot
+        bc.ntiles = (int32_t)nmt;
+        bchunks.push_back(bc);
+      }
       for (int64_t i = 0; i < nmt; ++i) {
         TileDesc td;
         td.start = off[l] + i * kMergeTile;
@@ -252,6 +264,7 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
   }
   for (int c = 0; c < 3; ++c) t->n_small[c] = (int)small[c].size();
   t->n_mtiles = (int)mtiles.size();
+  t->n_bchunks = (int)bchunks.size();
   LargePlan& pl = t->plan;
   pl.n_large = (int)t->lsegs.size();
   pl.n_tiles = (int)tiles.size();
@@ -267,6 +280,7 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
   if (rc == LAGS_OK) rc = upload(&t->d_tiles, tiles);
   if (rc == LAGS_OK) rc = upload(&t->d_ctiles, ctiles);
   if (rc == LAGS_OK) rc = upload(&t->d_mtiles, mtiles);
+  if (rc == LAGS_OK) rc = upload(&t->d_bchunks, bchunks);
   if (rc == LAGS_OK) rc = upload(&t->d_sampled, sampled);
   if (rc == LAGS_OK) rc = upload(&t->d_chunk_lseg, chunk_lseg);
   pl.lsegs = t->d_lsegs;
@@ -342,7 +356,7 @@ int lags_destroy(lags_ctx* ctx) {
     delete kv.second;
   }
   DevBuf* bufs[] = {&ctx->counters, &ctx->ghist, &ctx->lstate, &ctx->tile_gt, &ctx->tile_eq, &ctx->items,
-                    &ctx->chunk_cnt, &ctx->chunk_off, &ctx->slots, &ctx->cand};
+                    &ctx->chunk_cnt, &ctx->chunk_off, &ctx->slots, &ctx->cand, &ctx->bounds};
   for (DevBuf* b : bufs) b->release();
   delete ctx;
   return LAGS_OK;
@@ -447,8 +461,11 @@ int lags_merge_sparse(lags_ctx* ctx, const lags_table* t, const int32_t* idx, co
   if (ranges_overlap(up, ub, idx, pb) || ranges_overlap(up, ub, val, pb)) return LAGS_EINVAL;
   DeviceGuard g(ctx->device);
   if (!g.ok) return LAGS_EHIP;
-  if (launch_merge(t->n_mtiles, t->d_mtiles, t->d_segs, idx, val, P, stride_k, update_flat,
-                   (hipStream_t)hip_stream, &ctx->prof) != hipSuccess)
+  const int nb = t->n_mtiles + t->n;
+  // P rows of tile bounds; grows (a synchronous allocation) the first time a larger P or table is merged
+  if (ctx->bounds.grow((size_t)P * (size_t)nb * sizeof(int32_t)) != LAGS_OK) return LAGS_ENOMEM;
+  if (launch_merge(t->n_mtiles, t->d_mtiles, t->n_bchunks, t->d_bchunks, nb, static_cast<int32_t*>(ctx->bounds.p),
+                   t->d_segs, idx, val, P, stride_k, update_flat, (hipStream_t)hip_stream, &ctx->prof) != hipSuccess)
     return LAGS_EHIP;
   return LAGS_OK;
 }

@@ -33,6 +33,14 @@ constexpr int kDenseGrid = 2048;         // workgroups of the fallback kernels (
 
 constexpr int kMergeTile = 8192;
 constexpr int kMaxWorkers = 1024;
+constexpr int kBoundChunk = 16384;       // index-list entries per workgroup of k_merge_bounds
+
+struct BChunk {         // a run of one layer's index list, for k_merge_bounds
+  int32_t seg;          // layer
+  int32_t j0;           // first list position of the run
+  int32_t slot0;        // the layer's first slot in a worker's bounds row
+  int32_t ntiles;       // merge tiles of the layer
+};
 
 struct SegDesc {        // one layer
   int64_t offset;       // element offset in the flat arrays
@@ -106,7 +114,7 @@ struct Scratch {        // context-owned device memory, contents meaningless bet
 enum KernelId {
   K_ZERO = 0, K_SMALL0, K_SMALL1, K_SMALL2, K_SAMPLE, K_STREAM, K_CSCAN, K_CGATHER,
   K_CSMALL0, K_CSMALL1, K_CSMALL2, K_HIST_CAND, K_HIST_DENSE, K_CHOOSE, K_COUNT_CAND, K_COUNT_DENSE,
-  K_SCAN, K_EMIT_CAND, K_EMIT_DENSE, K_MERGE, K_NUM
+  K_SCAN, K_EMIT_CAND, K_EMIT_DENSE, K_MERGE_BOUNDS, K_MERGE, K_NUM
 };
 const char* kernel_name(int id);
 
@@ -134,7 +142,8 @@ hipError_t launch_small(int cls, int nseg, const SegDesc* segs, const int32_t* l
                         float* res, float lr, int32_t* out_idx, float* out_val, hipStream_t s, Prof* prof);
 hipError_t launch_large(const LargePlan& pl, const Scratch& sc, const SegDesc* segs, const float* grad,
                         float* res, float lr, int32_t* out_idx, float* out_val, hipStream_t s, Prof* prof);
-hipError_t launch_merge(int n_tiles, const TileDesc* mtiles, const SegDesc* segs, const int32_t* idx,
-                        const float* val, int P, int64_t stride_k, float* update, hipStream_t s, Prof* prof);
+hipError_t launch_merge(int n_tiles, const TileDesc* mtiles, int n_bchunks, const BChunk* bchunks, int nb,
+                        int32_t* bounds, const SegDesc* segs, const int32_t* idx, const float* val, int P,
+                        int64_t stride_k, float* update, hipStream_t s, Prof* prof);
 
 }  // namespace lags

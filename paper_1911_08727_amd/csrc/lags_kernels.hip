@@ -897,46 +897,119 @@ __global__ __launch_bounds__(256) void k_emit(const TileDesc* __restrict__ tiles
 }
 
 // ------------------------------------------------------------------ merge ----
-// Algorithm 1 lines 8-9.  One workgroup owns one tile of the dense update: it
-// accumulates the tile in LDS, adding the workers' entries in worker order (a barrier
-// between workers; inside one worker the indices are distinct), then writes the tile
-// once, divided by P.  No atomics, fixed summation order.
+// Algorithm 1 lines 8-9.  Two kernels.
+//
+// k_merge_bounds: for every worker and layer, where each 8192-element tile of the dense
+// update starts in the worker's sorted index list: bounds[p][slot0 + t] = first list position
+// whose index lies in tile t or later; bounds[p][slot0 + ntiles] = k.  One pass over the lists.
+__global__ __launch_bounds__(256) void k_merge_bounds(const BChunk* __restrict__ chunks,
+                                                      const SegDesc* __restrict__ segs,
+                                                      const int32_t* __restrict__ idx, int64_t stride_k,
+                                                      int nb, int32_t* __restrict__ bounds) {
+  const BChunk bc = chunks[blockIdx.x];
+  const int p = blockIdx.y;
+  const SegDesc sd = segs[bc.seg];
+  const int32_t* li = idx + (int64_t)p * stride_k + sd.out_offset;
+  int32_t* b = bounds + (int64_t)p * nb + bc.slot0;
+  const int jend = sd.k < bc.j0 + kBoundChunk ? sd.k : bc.j0 + kBoundChunk;
+  for (int j = bc.j0 + (int)threadIdx.x; j < jend; j += 256) {
+    // indices are clamped into the layer so that bad input cannot write outside the row
+    int i1 = li[j];
+    i1 = i1 < 0 ? 0 : (i1 >= sd.d ? sd.d - 1 : i1);
+    const int t = i1 / kMergeTile;
+    int tp = -1;
+    if (j > 0) {
+      int i0 = li[j - 1];
+      i0 = i0 < 0 ? 0 : (i0 >= sd.d ? sd.d - 1 : i0);
+      tp = i0 / kMergeTile;
+    }
+    for (int q = tp + 1; q <= t; ++q) b[q] = j;
+    if (j == sd.k - 1)
+      for (int q = t + 1; q <= bc.ntiles; ++q) b[q] = sd.k;
+  }
+}
+
+// k_merge: one workgroup owns one tile of the dense update.  It loads the entries of all
+// workers that fall into the tile (found through the bounds, no searching), accumulates
+// them in LDS in worker order (one barrier per worker; inside one worker the indices are
+// distinct), and writes the tile once, divided by P.  No atomics, fixed summation order.
 __global__ __launch_bounds__(256) void k_merge(const TileDesc* __restrict__ mtiles,
                                                const SegDesc* __restrict__ segs,
                                                const int32_t* __restrict__ idx,
                                                const float* __restrict__ val, int P,
-                                               int64_t stride_k, float* __restrict__ update) {
+                                               int64_t stride_k, int nb,
+                                               const int32_t* __restrict__ bounds,
+                                               float* __restrict__ update) {
   __shared__ float s_acc[kMergeTile];
-  __shared__ int32_t s_lo[64], s_hi[64];
+  __shared__ uint32_t s_start[257];
+  __shared__ int32_t s_lo[256];
+  __shared__ uint32_t s_wt[4];
   const TileDesc td = mtiles[blockIdx.x];
   const SegDesc sd = segs[td.seg];
   const int tid = threadIdx.x;
-  for (int i = tid; i < kMergeTile; i += 256) s_acc[i] = 0.0f;
-  for (int p0 = 0; p0 < P; p0 += 64) {
-    const int np = P - p0 < 64 ? P - p0 : 64;
+  const int slot = (int)blockIdx.x + td.seg;  // every earlier layer owns one extra (end) slot
+  for (int i = tid * 4; i < kMergeTile; i += 1024)
+    *reinterpret_cast<float4*>(&s_acc[i]) = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int p0 = 0; p0 < P; p0 += 256) {
+    const int np = P - p0 < 256 ? P - p0 : 256;
+    int lo = 0;
+    uint32_t cnt = 0;
+    if (tid < np) {
+      const int32_t* b = bounds + (int64_t)(p0 + tid) * nb + slot;
+      int hi = b[1];
+      lo = b[0];
+      lo = lo < 0 ? 0 : (lo > sd.k ? sd.k : lo);
+      hi = hi < 0 ? 0 : (hi > sd.k ? sd.k : hi);
+      cnt = hi > lo ? (uint32_t)(hi - lo) : 0u;
+    }
+    uint32_t total;
+    const uint32_t incl = block_incl_scan<256>(cnt, s_wt, total);
+    s_start[tid] = incl - cnt;
+    s_lo[tid] = lo;
+    if (tid == 0) s_start[256] = total;
     __syncthreads();
-    if (tid < 2 * np) {
-      // first position in worker p's index list of this layer that is >= target
-      const int p = p0 + (tid >> 1);
-      const int32_t target = td.local0 + ((tid & 1) ? td.n : 0);
-      const int32_t* li = idx + (int64_t)p * stride_k + sd.out_offset;
-      int lo = 0, hi = sd.k;
-      while (lo < hi) {
-        const int mid = (lo + hi) >> 1;
-        if (li[mid] < target) lo = mid + 1; else hi = mid;
+    for (uint32_t base = 0; base < total; base += 1024) {
+      int pe[4];
+      uint32_t off[4];
+      float v[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const uint32_t e = base + (uint32_t)(r * 256 + tid);
+        pe[r] = -1;
+        off[r] = 0xFFFFFFFFu;
+        v[r] = 0.f;
+        if (e < total) {
+          int a = 0, z = np;  // last worker q with s_start[q] <= e (skips workers without entries here)
+          while (a < z) {
+            const int mid = (a + z) >> 1;
+            if (s_start[mid] <= e) a = mid + 1; else z = mid;
+          }
+          const int q = a - 1;
+          const int64_t gi = (int64_t)(p0 + q) * stride_k + sd.out_offset + s_lo[q] + (int)(e - s_start[q]);
+          off[r] = (uint32_t)(idx[gi] - td.local0);
+          v[r] = val[gi];
+          pe[r] = q;
+        }
       }
-      if (tid & 1) s_hi[tid >> 1] = lo; else s_lo[tid >> 1] = lo;
+      // workers present in this pass (uniform over the workgroup)
+      int qf, ql;
+      {
+        const uint32_t e0 = base, e1 = (base + 1024 < total ? base + 1024 : total) - 1;
+        int a = 0, z = np;
+        while (a < z) { const int mid = (a + z) >> 1; if (s_start[mid] <= e0) a = mid + 1; else z = mid; }
+        qf = a - 1;
+        a = 0; z = np;
+        while (a < z) { const int mid = (a + z) >> 1; if (s_start[mid] <= e1) a = mid + 1; else z = mid; }
+        ql = a - 1;
+      }
+      for (int q = qf; q <= ql; ++q) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          if (pe[r] == q && off[r] < (uint32_t)td.n) s_acc[off[r]] = __fadd_rn(s_acc[off[r]], v[r]);
+        __syncthreads();
+      }
     }
     __syncthreads();
-    for (int q = 0; q < np; ++q) {
-      const int64_t base = (int64_t)(p0 + q) * stride_k + sd.out_offset;
-      const int hi = s_hi[q];
-      for (int j = s_lo[q] + tid; j < hi; j += 256) {
-        const uint32_t off = (uint32_t)(idx[base + j] - td.local0);
-        if (off < (uint32_t)td.n) s_acc[off] = __fadd_rn(s_acc[off], val[base + j]);
-      }
-      __syncthreads();
-    }
   }
   const float fp = (float)P;
   float* u = update + td.start;
@@ -962,7 +1035,7 @@ const char* kernel_name(int id) {
       "k_zero_u32", "k_small<4,1>", "k_small<4,8>", "k_small<16,10>", "k_sample", "k_stream", "k_cscan",
       "k_cgather", "k_small<4,1,cand>", "k_small<4,8,cand>", "k_small<16,10,cand>", "k_hist<cand>",
       "k_hist<dense>", "k_choose", "k_count<cand>", "k_count<dense>", "k_scan", "k_emit<cand>",
-      "k_emit<dense>", "k_merge"};
+      "k_emit<dense>", "k_merge_bounds", "k_merge"};
   return (id >= 0 && id < K_NUM) ? names[id] : nullptr;
 }
 
@@ -1094,11 +1167,17 @@ hipError_t launch_large(const LargePlan& pl, const Scratch& sc, const SegDesc* s
   return hipGetLastError();
 }
 
-hipError_t launch_merge(int n_tiles, const TileDesc* mtiles, const SegDesc* segs, const int32_t* idx,
-                        const float* val, int P, int64_t stride_k, float* update, hipStream_t s, Prof* prof) {
+hipError_t launch_merge(int n_tiles, const TileDesc* mtiles, int n_bchunks, const BChunk* bchunks, int nb,
+                        int32_t* bounds, const SegDesc* segs, const int32_t* idx, const float* val, int P,
+                        int64_t stride_k, float* update, hipStream_t s, Prof* prof) {
   if (n_tiles <= 0) return hipSuccess;
+  {
+    ProfScope ps(prof, K_MERGE_BOUNDS, s);
+    hipLaunchKernelGGL(k_merge_bounds, dim3(n_bchunks, P), dim3(256), 0, s, bchunks, segs, idx, stride_k, nb, bounds);
+  }
   ProfScope ps(prof, K_MERGE, s);
-  hipLaunchKernelGGL(k_merge, dim3(n_tiles), dim3(256), 0, s, mtiles, segs, idx, val, P, stride_k, update);
+  hipLaunchKernelGGL(k_merge, dim3(n_tiles), dim3(256), 0, s, mtiles, segs, idx, val, P, stride_k, nb, bounds,
+                     update);
   return hipGetLastError();
 }
 

@@ -274,12 +274,12 @@ def test_mixed_routes_in_one_table(gpu, oracle):
 
 def test_merge_closed_forms(gpu, oracle):
     """P = 1 is a scatter; many workers on one index sum in worker order; division is a
-    true division (P = 3, 7); indices spread over several merge tiles; P > 64."""
+    true division (P = 3, 7); indices spread over several merge tiles; P beyond one batch of 256."""
     rng = np.random.default_rng(31)
     layers = [(0, 20000, 0.01), (20004, 9, 0.5), (20013, 70000, 0.002)]
     total = 20013 + 70000
     K = oracle.total_k(layers)
-    for P in (1, 3, 7, 16, 70):
+    for P in (1, 3, 7, 16, 70, 300):
         idx = np.empty(P * K, np.int32)
         val = (rng.standard_normal(P * K) * 10.0 ** rng.integers(-8, 8, P * K)).astype(np.float32)
         for p in range(P):
