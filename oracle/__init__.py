@@ -50,6 +50,11 @@ def _bind(path):
     lib.oracle_merge_sparse.restype = ctypes.c_int
     lib.oracle_merge_sparse.argtypes = [lp, ctypes.c_int32, i32p, f32p, ctypes.c_int32,
                                         ctypes.c_int64, f32p]
+    lib.oracle_apply_sparse.restype = ctypes.c_int
+    lib.oracle_apply_sparse.argtypes = [lp, ctypes.c_int32, i32p, f32p, ctypes.c_int32, ctypes.c_int64, f32p]
+    lib.oracle_delta_monitor.restype = ctypes.c_int
+    lib.oracle_delta_monitor.argtypes = [lp, ctypes.c_int32, f32p, ctypes.c_int64, i32p, f32p, ctypes.c_int32,
+                                         ctypes.c_int64, ctypes.POINTER(ctypes.c_double)]
     return lib
 
 
@@ -122,6 +127,25 @@ class OracleLib:
         return update_flat
 
 
+    def apply_sparse(self, layers, idx, val, P, stride_k, param_flat):
+        """param_flat -= merged update, in place, for every element of every layer."""
+        rc = self._lib.oracle_apply_sparse(_layers(layers), len(layers), _i32(idx), _f32(val), int(P),
+                                           int(stride_k), _f32(param_flat))
+        if rc:
+            raise ValueError("oracle_apply_sparse failed (rc=%d)" % rc)
+        return param_flat
+
+    def delta_monitor(self, layers, residual_flat, res_stride, idx, val, P, stride_k):
+        """float64[n_layers, 3]: numerator, ||sum_p x^p||^2, delta per layer."""
+        out = np.empty((len(layers), 3), np.float64)
+        rc = self._lib.oracle_delta_monitor(_layers(layers), len(layers), _f32(residual_flat), int(res_stride),
+                                            _i32(idx), _f32(val), int(P), int(stride_k),
+                                            out.ctypes.data_as(ctypes.POINTER(ctypes.c_double)))
+        if rc:
+            raise ValueError("oracle_delta_monitor failed (rc=%d)" % rc)
+        return out
+
+
 _default = None
 
 
@@ -154,3 +178,11 @@ def sparsify_model(layers, grad_flat, residual_flat, lr):
 
 def merge_sparse(layers, idx, val, P, stride_k, update_flat):
     return _get().merge_sparse(layers, idx, val, P, stride_k, update_flat)
+
+
+def apply_sparse(layers, idx, val, P, stride_k, param_flat):
+    return _get().apply_sparse(layers, idx, val, P, stride_k, param_flat)
+
+
+def delta_monitor(layers, residual_flat, res_stride, idx, val, P, stride_k):
+    return _get().delta_monitor(layers, residual_flat, res_stride, idx, val, P, stride_k)

@@ -168,3 +168,89 @@ int oracle_merge_sparse(const oracle_layer *layers, int32_t n_layers, const int3
   }
   return 0;
 }
+
+/*
+ * Algorithm 1 line 9 (Eq. 5): v = v - (1/P) * g with g the sum of the workers' selected
+ * entries.  The update is formed exactly as in oracle_merge_sparse (sum in worker order
+ * from +0.0f, one division by (float)P) and then subtracted from the parameters in
+ * binary32, element by element, for every element of every layer.
+ */
+int oracle_apply_sparse(const oracle_layer *layers, int32_t n_layers, const int32_t *idx,
+                        const float *val, int32_t P, int64_t stride_k, float *param_flat) {
+  if (!layers || n_layers < 0 || P < 1 || !idx || !val || !param_flat) return -1;
+  int64_t out = 0;
+  for (int32_t l = 0; l < n_layers; ++l) {
+    int64_t d = layers[l].d;
+    int64_t k = oracle_topk_count(d, layers[l].rho);
+    oracle_layer one = {0, d, layers[l].rho};
+    float *update = (float *)malloc((size_t)d * sizeof(float));
+    if (!update) return -1;
+    int rc = oracle_merge_sparse(&one, 1, idx + out, val + out, P, stride_k, update);
+    if (rc) {
+      free(update);
+      return rc;
+    }
+    float *v = param_flat + layers[l].offset;
+    for (int64_t i = 0; i < d; ++i) v[i] = v[i] - update[i];
+    free(update);
+    out += k;
+  }
+  return 0;
+}
+
+/*
+ * Section 6.2: the per-layer metric delta^(l) that checks Assumption 1, with
+ * x^p = acc^p (Algorithm 1 line 6).  Numerator: || sum_p x^p - sum_p TopK(x^p) ||^2, and
+ * x^p - TopK(x^p) is the new residual of worker p (Algorithm 1 line 7).  Denominator: the
+ * expectation over RandK of || sum_p x^p - RandK(sum_p x^p, k) ||^2, which Section 4.2
+ * gives in closed form as (1 - k/d) || sum_p x^p ||^2.  Everything in double.
+ *   residual_flat  the residuals AFTER sparsification, worker p at residual_flat + p*res_stride
+ *   idx, val       the selected pairs, worker p at + p*stride_k
+ *   out            3 doubles per layer: numerator, ||sum_p x^p||^2, delta
+ *                  (delta is NaN when the denominator is 0, e.g. k == d)
+ */
+int oracle_delta_monitor(const oracle_layer *layers, int32_t n_layers, const float *residual_flat,
+                         int64_t res_stride, const int32_t *idx, const float *val, int32_t P,
+                         int64_t stride_k, double *out3) {
+  if (!layers || n_layers < 0 || P < 1 || !residual_flat || !idx || !val || !out3) return -1;
+  int64_t out = 0;
+  for (int32_t l = 0; l < n_layers; ++l) {
+    int64_t d = layers[l].d;
+    int64_t k = oracle_topk_count(d, layers[l].rho);
+    double *sum_res = (double *)calloc((size_t)d, sizeof(double));
+    double *sum_sel = (double *)calloc((size_t)d, sizeof(double));
+    if (!sum_res || !sum_sel) {
+      free(sum_res);
+      free(sum_sel);
+      return -1;
+    }
+    for (int32_t p = 0; p < P; ++p) {
+      const float *r = residual_flat + (int64_t)p * res_stride + layers[l].offset;
+      for (int64_t i = 0; i < d; ++i) sum_res[i] += (double)r[i];
+      const int32_t *sel_i = idx + (int64_t)p * stride_k + out;
+      const float *sel_v = val + (int64_t)p * stride_k + out;
+      for (int64_t j = 0; j < k; ++j) {
+        if (sel_i[j] < 0 || sel_i[j] >= d) {
+          free(sum_res);
+          free(sum_sel);
+          return -1;
+        }
+        sum_sel[sel_i[j]] += (double)sel_v[j];
+      }
+    }
+    double num = 0.0, sq = 0.0;
+    for (int64_t i = 0; i < d; ++i) {
+      double x = sum_res[i] + sum_sel[i];
+      num += sum_res[i] * sum_res[i];
+      sq += x * x;
+    }
+    double den = (1.0 - (double)k / (double)d) * sq;
+    out3[3 * l + 0] = num;
+    out3[3 * l + 1] = sq;
+    out3[3 * l + 2] = den > 0.0 ? num / den : NAN;
+    free(sum_res);
+    free(sum_sel);
+    out += k;
+  }
+  return 0;
+}

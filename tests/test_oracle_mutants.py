@@ -37,6 +37,22 @@ MUTANTS = {
     "merge_ignores_stride": ("const int32_t *pi = idx + (int64_t)p * stride_k + out;",
                              "const int32_t *pi = idx + (int64_t)p * k + out;"),
     "merge_no_clear": ("for (int64_t i = 0; i < d; ++i) u[i] = 0.0f;", ""),
+    "apply_adds": ("v[i] = v[i] - update[i];", "v[i] = v[i] + update[i];"),
+    "apply_ignores_stride": ("int rc = oracle_merge_sparse(&one, 1, idx + out, val + out, P, stride_k, update);",
+                             "int rc = oracle_merge_sparse(&one, 1, idx + out, val + out, P, k, update);"),
+    "apply_wrong_offset": ("float *v = param_flat + layers[l].offset;", "float *v = param_flat + out;"),
+    "delta_no_randk_factor": ("double den = (1.0 - (double)k / (double)d) * sq;", "double den = sq;"),
+    "delta_factor_k_over_d": ("double den = (1.0 - (double)k / (double)d) * sq;",
+                              "double den = ((double)k / (double)d) * sq;"),
+    "delta_numerator_is_x": ("num += sum_res[i] * sum_res[i];", "num += x * x;"),
+    "delta_denominator_is_residual": ("sq += x * x;", "sq += sum_res[i] * sum_res[i];"),
+    "delta_norm_not_squared": ("num += sum_res[i] * sum_res[i];", "num += fabs(sum_res[i]);"),
+    "delta_sums_norms_per_worker": ("for (int64_t i = 0; i < d; ++i) sum_res[i] += (double)r[i];",
+                                    "for (int64_t i = 0; i < d; ++i) sum_res[i] += fabs((double)r[i]);"),
+    "delta_ignores_res_stride": ("const float *r = residual_flat + (int64_t)p * res_stride + layers[l].offset;",
+                                 "const float *r = residual_flat + (int64_t)p * d + layers[l].offset;"),
+    "delta_ignores_pair_stride": ("const int32_t *sel_i = idx + (int64_t)p * stride_k + out;",
+                                  "const int32_t *sel_i = idx + (int64_t)p * k + out;"),
     "model_no_out_advance": ("    out += k;\n  }\n  return 0;\n}\n\n/*\n * Algorithm 1 lines 8-9",
                              "  }\n  return 0;\n}\n\n/*\n * Algorithm 1 lines 8-9"),
 }
@@ -73,11 +89,11 @@ def test_mutant_is_caught(name):
     src = open(SRC).read()
     if name == "global_indices":
         new = "out_idx[n] = (int32_t)(i + 1);"
-    assert src.count(old) == 1, "mutation site not unique: %s" % name
+    assert src.count(old) >= 1, "mutation site not found: %s" % name      # the first occurrence is mutated
     with tempfile.TemporaryDirectory() as tmp:
         c = os.path.join(tmp, "mutant.c")
         so = os.path.join(tmp, "mutant.so")
-        open(c, "w").write(src.replace(old, new))
+        open(c, "w").write(src.replace(old, new, 1))
         subprocess.check_call(["gcc", *oracle_pkg.CFLAGS, "-o", so, c, "-lm"])
         failed = _run_all_pins(oracle_pkg.OracleLib(so))
     assert failed, "no pin notices mutant %s" % name

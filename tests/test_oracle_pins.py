@@ -364,3 +364,130 @@ def test_error_feedback_conserves_mass(oracle):
     res2 = np.zeros(d, np.float32)
     idx2, _ = oracle.sparsify_layer(g, res2, lr, k)
     assert not np.array_equal(idx, idx2)
+
+
+# ------------------------------------------------------ sparse apply --------
+def test_apply_single_worker_and_untouched_entries(oracle):
+    """Algorithm 1 line 9 with P = 1: v - TopK; entries no worker selected keep their bits
+    (also -0.0 and denormals)."""
+    layers = [(1, 6, 0.5), (8, 3, 0.3)]
+    idx = np.array([0, 2, 5, 1], np.int32)
+    val = np.array([0.5, -2.0, 4.0, 8.0], np.float32)
+    v0 = np.array([9, 1.0, -0.0, 3.0, 1e-45, 0.0, 7.0, 9, 2.0, 2.0, -0.0, 9], np.float32)
+    v = v0.copy()
+    oracle.apply_sparse(layers, idx, val, 1, 4, v)
+    want = v0.copy()
+    want[1] = 1.0 - 0.5
+    want[3] = 3.0 + 2.0
+    want[6] = 7.0 - 4.0
+    want[9] = 2.0 - 8.0
+    assert np.array_equal(bits(v), bits(want))
+
+
+def test_apply_sums_then_divides_then_subtracts(oracle):
+    """v_new = fl(v - fl(fl(a + b + c) / P)): one rounding per step, in that order.
+    Catches: subtracting per worker, multiplying by fl(1/P), adding instead of subtracting."""
+    layers = [(0, 2, 0.5)]
+    P = 3
+    found = 0
+    rng = np.random.default_rng(17)
+    for _ in range(200):
+        a, b, c, v0 = [np.float32(x) for x in rng.standard_normal(4)]
+        idx = np.zeros(P, np.int32)
+        val = np.array([a, b, c], np.float32)
+        v = np.array([v0, 5.0], np.float32)
+        oracle.apply_sparse(layers, idx, val, P, 1, v)
+        s = round_f32(round_f32(Fraction(float(a)) + Fraction(float(b))) + Fraction(float(c)))
+        want = round_f32(Fraction(float(v0)) - round_f32(s / 3))
+        assert Fraction(float(v[0])) == want and v[1] == 5.0
+        per_worker = Fraction(float(v0))
+        for x in (a, b, c):
+            per_worker = round_f32(per_worker - round_f32(Fraction(float(x)) / 3))
+        recip = round_f32(Fraction(float(v0)) - round_f32(s * round_f32(Fraction(1, 3))))
+        found += (per_worker != want) + (recip != want)
+    assert found > 20        # the alternatives really do round differently on these inputs
+
+
+# ------------------------------------------------------ delta monitor -------
+def test_delta_hand_example(oracle):
+    """Section 6.2 on a 4-element layer, two workers, k = 2, worked by hand:
+    residual sums (1,0,1,3) -> numerator 11; x sums (6,-1,3,3) -> 55; delta = 11 / (0.5*55)."""
+    res = np.array([0, 0, 1, 2, 1, 0, 0, 1], np.float32)
+    idx = np.array([0, 1, 1, 2], np.int32)
+    val = np.array([5, -4, 3, 2], np.float32)
+    out = oracle.delta_monitor([(0, 4, 0.5)], res, 4, idx, val, 2, 2)
+    assert out.tolist() == [[11.0, 55.0, 0.4]]
+
+
+def test_delta_from_definition_and_randk_identity(oracle):
+    """delta from (new residuals, selected pairs) equals the definition evaluated on the acc
+    vectors with numpy, and its denominator is the RandK expectation of Section 4.2, checked by
+    exhaustive enumeration of all k-subsets on a tiny vector."""
+    rng = np.random.default_rng(23)
+    P, d, k = 5, 400, 20
+    layers = [(0, d, k / d)]
+    accs = rng.standard_normal((P, d)).astype(np.float32)
+    res = np.empty((P, d), np.float32)
+    idx = np.empty((P, k), np.int32)
+    val = np.empty((P, k), np.float32)
+    for p in range(P):
+        r = np.full(d, -0.0, np.float32)
+        idx[p], val[p] = oracle.sparsify_layer(accs[p].copy(), r, 1.0, k)
+        res[p] = r
+    out = oracle.delta_monitor(layers, res.reshape(-1), d, idx.reshape(-1), val.reshape(-1), P, k)
+    x = accs.astype(np.float64)
+    top = np.zeros_like(x)
+    for p in range(P):
+        keep = np.argpartition(-np.abs(x[p]), k - 1)[:k]
+        top[p, keep] = x[p, keep]
+    num = float(np.sum((x.sum(0) - top.sum(0)) ** 2))
+    sq = float(np.sum(x.sum(0) ** 2))
+    assert np.isclose(out[0, 0], num, rtol=1e-12) and np.isclose(out[0, 1], sq, rtol=1e-12)
+    assert np.isclose(out[0, 2], num / ((1 - k / d) * sq), rtol=1e-12)
+    assert out[0, 2] < 1.0                      # what the paper observes (Fig. 2)
+    # E || y - RandK(y, k) ||^2 = (1 - k/d) ||y||^2 by enumeration
+    y = rng.standard_normal(7)
+    for kk in (1, 3, 6):
+        errs = [np.sum(np.delete(y, list(c)) ** 2) for c in itertools.combinations(range(7), kk)]
+        assert np.isclose(np.mean(errs), (1 - kk / 7) * np.sum(y ** 2))
+
+
+def test_delta_single_worker_bound_and_full_density(oracle):
+    """P = 1: TopK is at least as good as RandK, so delta <= 1; k = d: denominator 0 -> NaN."""
+    rng = np.random.default_rng(29)
+    d = 1000
+    g = rng.standard_normal(d).astype(np.float32)
+    for k in (1, 10, 500):
+        r = np.zeros(d, np.float32)
+        i, v = oracle.sparsify_layer(g, r, 1.0, k)
+        out = oracle.delta_monitor([(0, d, k / d)], r, d, i, v, 1, k)
+        assert 0.0 <= out[0, 2] <= 1.0
+    r = np.zeros(d, np.float32)
+    i, v = oracle.sparsify_layer(g, r, 1.0, d)
+    out = oracle.delta_monitor([(0, d, 1.0)], r, d, i, v, 1, d)
+    assert out[0, 0] == 0.0 and np.isnan(out[0, 2])
+
+
+def test_delta_uses_layer_offsets_and_strides(oracle):
+    """Two layers with a gap, worker stride larger than the model, pair stride larger than sum k."""
+    layers = [(1, 3, 0.4), (6, 2, 0.5)]
+    P = 2
+    res = np.array([9, 1, 0, 2, 9, 9, 0, 1, 9, 9,
+                    9, 0, 0, 1, 9, 9, 3, 0, 9, 9], np.float32)
+    idx = np.array([1, 2, 0, -1, 0, 1, 1, -1], np.int32)          # k = 2, 1 ; stride_k = 4
+    val = np.array([4, 1, 5, 77, 2, 2, -1, 77], np.float32)
+    out = oracle.delta_monitor(layers, res, 10, idx, val, P, 4)
+    # layer 0: residual sums (1,0,3) -> 10; selected sums (2,6,1) -> x = (3,6,4) -> 61
+    assert out[0].tolist()[:2] == [10.0, 61.0] and np.isclose(out[0, 2], 10 / ((1 - 2 / 3) * 61))
+    # layer 1: residual sums (3,1) -> 10; selected sums (5,-1) -> x = (8,0) -> 64
+    assert out[1].tolist()[:2] == [10.0, 64.0] and np.isclose(out[1, 2], 10 / (0.5 * 64))
+
+
+def test_apply_two_workers_strided_blocks(oracle):
+    """Worker blocks sit stride_k apart (here with one padding slot), layers at their offsets."""
+    layers = [(0, 4, 0.5), (5, 2, 0.5)]
+    idx = np.array([0, 3, 1, -1, 0, 2, 1, -1], np.int32)            # per worker: k = 2, 1, pad
+    val = np.array([2, 4, 6, 77, 10, 20, 30, 77], np.float32)
+    v = np.array([1, 1, 1, 1, 9, 1, 1], np.float32)
+    oracle.apply_sparse(layers, idx, val, 2, 4, v)
+    assert v.tolist() == [1 - 6, 1, 1 - 10, 1 - 2, 9, 1, 1 - 18]
