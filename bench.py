@@ -132,6 +132,24 @@ def main():
     prof = ctx.lags_profile_read()
     ctx.lags_profile_reset()
 
+    # the rows next to the hot path, measured apart from the timed steps: the in-place sparse
+    # parameter step (Algorithm 1 line 9) and the delta metric of Section 6.2
+    param = torch.zeros(total, dtype=torch.float32, device=dev)
+    delta = torch.empty(3 * len(layers), dtype=torch.float64, device=dev)
+    reps = 5
+    ctx.lags_apply_sparse(table_1, idx, val, P, K, param, stream)
+    ctx.lags_delta_monitor(table_1, res, total, idx, val, P, K, delta, stream)
+    torch.cuda.synchronize()
+    ctx.lags_profile_enable(True)
+    for _ in range(reps):
+        ctx.lags_apply_sparse(table_1, idx, val, P, K, param, stream)
+        ctx.lags_delta_monitor(table_1, res, total, idx, val, P, K, delta, stream)
+    torch.cuda.synchronize()
+    ctx.lags_profile_enable(False)
+    prof2 = ctx.lags_profile_read()
+    ctx.lags_profile_reset()
+    delta_host = delta.cpu().numpy().reshape(-1, 3)
+
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     elements = P * total
     value = elements / (ms_per_step * 1e-3)
@@ -174,6 +192,13 @@ def main():
                             if sparsify_ms > 0 else None},
         "kernels": kernels,
         "roofline": roofline,
+        "next_rows": {
+            "sparse_apply_ms": round((prof2["k_merge<apply>"][0] + prof2["k_merge_bounds"][0] / 2) / reps, 4),
+            "delta_monitor_ms": round((prof2["k_delta_tiles"][0] + prof2["k_delta_finish"][0]
+                                       + prof2["k_merge_bounds"][0] / 2) / reps, 4),
+            "delta_monitor_gbs": round(4.0 * P * total / (prof2["k_delta_tiles"][0] / reps * 1e-3) / 1e9, 1),
+            "delta_max": float(np.nanmax(delta_host[:, 2])),
+        },
     }
     if not args.no_cpu_baseline:
         threads = min(16, os.cpu_count() or 1)

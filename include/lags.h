@@ -106,6 +106,30 @@ int lags_sparsify_model(lags_ctx *ctx, const lags_table *t, const float *grad_fl
 int lags_merge_sparse(lags_ctx *ctx, const lags_table *t, const int32_t *idx, const float *val,
                       int32_t P, int64_t stride_k, float *update_flat, void *hip_stream);
 
+/* Algorithm 1 line 9 / Eq. 5 applied in place, without materialising the dense update:
+ *     param = param - (sum over p = 0..P-1, in that order, of worker p's selected entries) / P
+ * for every element of every layer (binary32: the sum from +0.0f, one division by (float)P,
+ * one subtraction).  Only elements some worker selected are read or written; all others keep
+ * their bits.  idx, val, P, stride_k as for lags_merge_sparse; param_flat is a device float
+ * array laid out like grad_flat.  The result equals subtracting lags_merge_sparse's update. */
+int lags_apply_sparse(lags_ctx *ctx, const lags_table *t, const int32_t *idx, const float *val,
+                      int32_t P, int64_t stride_k, float *param_flat, void *hip_stream);
+
+/* Section 6.2: the per-layer metric delta^(l) that checks Assumption 1, with x^p = acc^p:
+ *     delta = || sum_p (x^p - TopK(x^p)) ||^2 / ( (1 - k/d) * || sum_p x^p ||^2 )
+ * (the denominator is the expectation over RandK, Section 4.2).  x^p - TopK(x^p) is worker p's
+ * residual after sparsification, so the inputs are
+ *   residual_flat  device float; worker p's residuals (after lags_sparsify_model) at
+ *                  residual_flat + p*res_stride, laid out by this table
+ *   idx, val       device; the selected pairs, worker p at + p*stride_k
+ *   out3           device double[3 * n_layers], written: for layer l
+ *                  out3[3l] = numerator, out3[3l+1] = ||sum_p x^p||^2, out3[3l+2] = delta
+ *                  (NaN if the denominator is 0, e.g. k == d)
+ * All sums are in double, over workers in worker order; reads P*4 bytes per element. */
+int lags_delta_monitor(lags_ctx *ctx, const lags_table *t, const float *residual_flat,
+                       int64_t res_stride, const int32_t *idx, const float *val, int32_t P,
+                       int64_t stride_k, double *out3, void *hip_stream);
+
 /* Diagnostic: which route each layer took in the LAST lags_sparsify_model call made with
  * this table on this context (host-synchronous: waits for the device).  route[l], l in
  * [0, n): 0 = one-workgroup route (small layer); 1 = sampled threshold accepted, selection

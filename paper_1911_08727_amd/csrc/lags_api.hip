@@ -38,6 +38,7 @@ struct lags_ctx {
   // scratch of the multi-block path, sized for the largest table created so far
   DevBuf counters, ghist, lstate, tile_gt, tile_eq, items, chunk_cnt, chunk_off, slots, cand;
   DevBuf bounds;   // merge: P rows of tile start positions, sized at the first merge call that needs it
+  DevBuf partials; // delta metric: two doubles per merge tile
   std::map<std::pair<int64_t, int64_t>, lags_table*> layer_tables;  // (d, k) -> one-layer table
   Prof prof;
   Scratch scratch() const {
@@ -64,7 +65,7 @@ struct lags_table {
   std::vector<SegDesc> segs;                   // host copy
   std::vector<LargeSeg> lsegs;                 // host copy
   int n_small[3] = {0, 0, 0};
-  int n_mtiles = 0, n_bchunks = 0;
+  MergePlan mplan;
   LargePlan plan;                              // device pointers below, owned by the table
   SegDesc* d_segs = nullptr;
   int32_t* d_small[3] = {nullptr, nullptr, nullptr};
@@ -73,6 +74,7 @@ struct lags_table {
   TileDesc* d_ctiles = nullptr;
   TileDesc* d_mtiles = nullptr;
   BChunk* d_bchunks = nullptr;
+  int32_t* d_seg_mtile0 = nullptr;
   int32_t* d_sampled = nullptr;
   int32_t* d_cand_small[3] = {nullptr, nullptr, nullptr};
   int32_t* d_chunk_lseg = nullptr;
@@ -121,6 +123,7 @@ void free_table_device(lags_table* t) {
   if (t->d_ctiles) (void)hipFree(t->d_ctiles);
   if (t->d_mtiles) (void)hipFree(t->d_mtiles);
   if (t->d_bchunks) (void)hipFree(t->d_bchunks);
+  if (t->d_seg_mtile0) (void)hipFree(t->d_seg_mtile0);
   if (t->d_sampled) (void)hipFree(t->d_sampled);
   if (t->d_chunk_lseg) (void)hipFree(t->d_chunk_lseg);
 }
@@ -169,6 +172,7 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
   std::vector<int32_t> small[3], cand_small[3], sampled, chunk_lseg;
   std::vector<TileDesc> tiles, ctiles, mtiles;
   std::vector<BChunk> bchunks;
+  std::vector<int32_t> seg_mtile0;
   int64_t n_ctile_dense = 0;   // tiles of sampled layers: each owns kSlot candidate slots
   int64_t cand_total = 0;
   constexpr int64_t kMaxTiles = 1 << 28;
@@ -239,6 +243,7 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
       }
       const int64_t nmt = (d[l] + kMergeTile - 1) / kMergeTile;
       if ((int64_t)mtiles.size() + nmt > kMaxTiles) { delete t; return LAGS_ECAPACITY; }
+      seg_mtile0.push_back((int32_t)mtiles.size());
       for (int64_t j0 = 0; j0 < k[l]; j0 += kBoundChunk) {
         BChunk bc;
         bc.seg = l;
@@ -258,13 +263,16 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
       }
     }
     t->total_k = outpos;
+    seg_mtile0.push_back((int32_t)mtiles.size());
   } catch (const std::bad_alloc&) {
     delete t;
     return LAGS_ENOMEM;
   }
   for (int c = 0; c < 3; ++c) t->n_small[c] = (int)small[c].size();
-  t->n_mtiles = (int)mtiles.size();
-  t->n_bchunks = (int)bchunks.size();
+  t->mplan.n_layers = n;
+  t->mplan.n_mtiles = (int)mtiles.size();
+  t->mplan.n_bchunks = (int)bchunks.size();
+  t->mplan.nb = (int)mtiles.size() + n;
   LargePlan& pl = t->plan;
   pl.n_large = (int)t->lsegs.size();
   pl.n_tiles = (int)tiles.size();
@@ -281,6 +289,10 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
   if (rc == LAGS_OK) rc = upload(&t->d_ctiles, ctiles);
   if (rc == LAGS_OK) rc = upload(&t->d_mtiles, mtiles);
   if (rc == LAGS_OK) rc = upload(&t->d_bchunks, bchunks);
+  if (rc == LAGS_OK) rc = upload(&t->d_seg_mtile0, seg_mtile0);
+  t->mplan.mtiles = t->d_mtiles;
+  t->mplan.bchunks = t->d_bchunks;
+  t->mplan.seg_mtile0 = t->d_seg_mtile0;
   if (rc == LAGS_OK) rc = upload(&t->d_sampled, sampled);
   if (rc == LAGS_OK) rc = upload(&t->d_chunk_lseg, chunk_lseg);
   pl.lsegs = t->d_lsegs;
@@ -356,7 +368,7 @@ int lags_destroy(lags_ctx* ctx) {
     delete kv.second;
   }
   DevBuf* bufs[] = {&ctx->counters, &ctx->ghist, &ctx->lstate, &ctx->tile_gt, &ctx->tile_eq, &ctx->items,
-                    &ctx->chunk_cnt, &ctx->chunk_off, &ctx->slots, &ctx->cand, &ctx->bounds};
+                    &ctx->chunk_cnt, &ctx->chunk_off, &ctx->slots, &ctx->cand, &ctx->bounds, &ctx->partials};
   for (DevBuf* b : bufs) b->release();
   delete ctx;
   return LAGS_OK;
@@ -451,23 +463,55 @@ int lags_sparsify_model(lags_ctx* ctx, const lags_table* t, const float* grad_fl
   return run_sparsify(ctx, t, grad_flat, residual_flat, lr, out_idx, out_val, (hipStream_t)hip_stream);
 }
 
-int lags_merge_sparse(lags_ctx* ctx, const lags_table* t, const int32_t* idx, const float* val, int32_t P,
-                      int64_t stride_k, float* update_flat, void* hip_stream) {
-  if (!ctx || !t || t->ctx != ctx || !idx || !val || !update_flat) return LAGS_EINVAL;
+namespace {
+// Validation and launch shared by the three merge-type entry points.
+int run_merge(int mode, lags_ctx* ctx, const lags_table* t, const int32_t* idx, const float* val, int32_t P,
+              int64_t stride_k, float* out, const float* res, int64_t res_stride, double* out3, void* hip_stream) {
+  if (!ctx || !t || t->ctx != ctx || !idx || !val) return LAGS_EINVAL;
   if (P < 1 || P > kMaxWorkers || stride_k < t->total_k) return LAGS_EINVAL;
   const int64_t pb = ((int64_t)(P - 1) * stride_k + t->total_k) * 4;
-  const char* up = reinterpret_cast<const char*>(update_flat) + t->span_lo * 4;
-  const int64_t ub = (t->span_hi - t->span_lo) * 4;
-  if (ranges_overlap(up, ub, idx, pb) || ranges_overlap(up, ub, val, pb)) return LAGS_EINVAL;
+  const int64_t lo = t->span_lo * 4, span = (t->span_hi - t->span_lo) * 4;
+  if (mode == MERGE_DELTA) {
+    if (!res || !out3 || res_stride < t->span_hi - t->span_lo) return LAGS_EINVAL;
+    const int64_t ob = (int64_t)t->n * 3 * 8;
+    const char* rp = reinterpret_cast<const char*>(res) + lo;
+    const int64_t rb = (int64_t)(P - 1) * res_stride * 4 + span;
+    if (ranges_overlap(out3, ob, idx, pb) || ranges_overlap(out3, ob, val, pb) || ranges_overlap(out3, ob, rp, rb))
+      return LAGS_EINVAL;
+  } else {
+    if (!out) return LAGS_EINVAL;
+    const char* up = reinterpret_cast<const char*>(out) + lo;
+    if (ranges_overlap(up, span, idx, pb) || ranges_overlap(up, span, val, pb)) return LAGS_EINVAL;
+  }
   DeviceGuard g(ctx->device);
   if (!g.ok) return LAGS_EHIP;
-  const int nb = t->n_mtiles + t->n;
-  // P rows of tile bounds; grows (a synchronous allocation) the first time a larger P or table is merged
-  if (ctx->bounds.grow((size_t)P * (size_t)nb * sizeof(int32_t)) != LAGS_OK) return LAGS_ENOMEM;
-  if (launch_merge(t->n_mtiles, t->d_mtiles, t->n_bchunks, t->d_bchunks, nb, static_cast<int32_t*>(ctx->bounds.p),
-                   t->d_segs, idx, val, P, stride_k, update_flat, (hipStream_t)hip_stream, &ctx->prof) != hipSuccess)
+  // P rows of tile bounds (and the delta partial sums): these grow, with a synchronous
+  // allocation, the first time a larger P or table is used
+  if (ctx->bounds.grow((size_t)P * (size_t)t->mplan.nb * sizeof(int32_t)) != LAGS_OK) return LAGS_ENOMEM;
+  if (mode == MERGE_DELTA && ctx->partials.grow((size_t)t->mplan.n_mtiles * 2 * sizeof(double)) != LAGS_OK)
+    return LAGS_ENOMEM;
+  if (launch_merge(mode, t->mplan, static_cast<int32_t*>(ctx->bounds.p), t->d_segs, idx, val, P, stride_k, out, res,
+                   res_stride, static_cast<double*>(ctx->partials.p), out3, (hipStream_t)hip_stream,
+                   &ctx->prof) != hipSuccess)
     return LAGS_EHIP;
   return LAGS_OK;
+}
+}  // namespace
+
+int lags_merge_sparse(lags_ctx* ctx, const lags_table* t, const int32_t* idx, const float* val, int32_t P,
+                      int64_t stride_k, float* update_flat, void* hip_stream) {
+  return run_merge(MERGE_UPDATE, ctx, t, idx, val, P, stride_k, update_flat, nullptr, 0, nullptr, hip_stream);
+}
+
+int lags_apply_sparse(lags_ctx* ctx, const lags_table* t, const int32_t* idx, const float* val, int32_t P,
+                      int64_t stride_k, float* param_flat, void* hip_stream) {
+  return run_merge(MERGE_APPLY, ctx, t, idx, val, P, stride_k, param_flat, nullptr, 0, nullptr, hip_stream);
+}
+
+int lags_delta_monitor(lags_ctx* ctx, const lags_table* t, const float* residual_flat, int64_t res_stride,
+                       const int32_t* idx, const float* val, int32_t P, int64_t stride_k, double* out3,
+                       void* hip_stream) {
+  return run_merge(MERGE_DELTA, ctx, t, idx, val, P, stride_k, nullptr, residual_flat, res_stride, out3, hip_stream);
 }
 
 int lags_last_routes(lags_ctx* ctx, const lags_table* t, int32_t* route, int32_t n) {
@@ -543,7 +587,7 @@ int64_t lags_profile_kernel_elements(const lags_table* t, int kernel_id) {
     case K_SMALL1: return small[1];
     case K_SMALL2: return small[2];
     case K_STREAM: return large;
-    case K_MERGE: return all;
+    case K_MERGE: case K_MERGE_APPLY: case K_DELTA_TILES: return all;
     default: return 0;
   }
 }

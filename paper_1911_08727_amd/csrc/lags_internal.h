@@ -114,7 +114,8 @@ struct Scratch {        // context-owned device memory, contents meaningless bet
 enum KernelId {
   K_ZERO = 0, K_SMALL0, K_SMALL1, K_SMALL2, K_SAMPLE, K_STREAM, K_CSCAN, K_CGATHER,
   K_CSMALL0, K_CSMALL1, K_CSMALL2, K_HIST_CAND, K_HIST_DENSE, K_CHOOSE, K_COUNT_CAND, K_COUNT_DENSE,
-  K_SCAN, K_EMIT_CAND, K_EMIT_DENSE, K_MERGE_BOUNDS, K_MERGE, K_NUM
+  K_SCAN, K_EMIT_CAND, K_EMIT_DENSE, K_MERGE_BOUNDS, K_MERGE, K_MERGE_APPLY, K_DELTA_TILES, K_DELTA_FINISH,
+  K_NUM
 };
 const char* kernel_name(int id);
 
@@ -142,8 +143,19 @@ hipError_t launch_small(int cls, int nseg, const SegDesc* segs, const int32_t* l
                         float* res, float lr, int32_t* out_idx, float* out_val, hipStream_t s, Prof* prof);
 hipError_t launch_large(const LargePlan& pl, const Scratch& sc, const SegDesc* segs, const float* grad,
                         float* res, float lr, int32_t* out_idx, float* out_val, hipStream_t s, Prof* prof);
-hipError_t launch_merge(int n_tiles, const TileDesc* mtiles, int n_bchunks, const BChunk* bchunks, int nb,
-                        int32_t* bounds, const SegDesc* segs, const int32_t* idx, const float* val, int P,
-                        int64_t stride_k, float* update, hipStream_t s, Prof* prof);
+enum { MERGE_UPDATE = 0, MERGE_APPLY = 1, MERGE_DELTA = 2 };
+
+struct MergePlan {      // device pointers + counts of the merge-type launches
+  int n_layers = 0, n_mtiles = 0, n_bchunks = 0, nb = 0;
+  const TileDesc* mtiles = nullptr;
+  const BChunk* bchunks = nullptr;
+  const int32_t* seg_mtile0 = nullptr;  // n_layers + 1: first merge tile of every layer
+};
+
+// mode MERGE_UPDATE: out = dense update; MERGE_APPLY: out = parameters, updated in place;
+// MERGE_DELTA: res/res_stride/partials/out3 are used instead of out.
+hipError_t launch_merge(int mode, const MergePlan& mp, int32_t* bounds, const SegDesc* segs, const int32_t* idx,
+                        const float* val, int P, int64_t stride_k, float* out, const float* res,
+                        int64_t res_stride, double* partials, double* out3, hipStream_t s, Prof* prof);
 
 }  // namespace lags

@@ -929,27 +929,21 @@ __global__ __launch_bounds__(256) void k_merge_bounds(const BChunk* __restrict__
   }
 }
 
-// k_merge: one workgroup owns one tile of the dense update.  It loads the entries of all
-// workers that fall into the tile (found through the bounds, no searching), accumulates
-// them in LDS in worker order (one barrier per worker; inside one worker the indices are
-// distinct), and writes the tile once, divided by P.  No atomics, fixed summation order.
-__global__ __launch_bounds__(256) void k_merge(const TileDesc* __restrict__ mtiles,
-                                               const SegDesc* __restrict__ segs,
-                                               const int32_t* __restrict__ idx,
-                                               const float* __restrict__ val, int P,
-                                               int64_t stride_k, int nb,
-                                               const int32_t* __restrict__ bounds,
-                                               float* __restrict__ update) {
-  __shared__ float s_acc[kMergeTile];
-  __shared__ uint32_t s_start[257];
-  __shared__ int32_t s_lo[256];
-  __shared__ uint32_t s_wt[4];
-  const TileDesc td = mtiles[blockIdx.x];
-  const SegDesc sd = segs[td.seg];
+// Accumulation shared by the merge-type kernels: the workgroup that owns one tile of the
+// dense layout loads the entries of all workers that fall into the tile (found through the
+// bounds, no searching) and adds them into the LDS tile s_acc in worker order (one barrier per
+// worker; inside one worker the indices are distinct).  T = float: binary32 adds, the sum the
+// method defines.  T = double: exact-order double sums for the delta metric.
+// Returns the number of entries that fell into the tile.
+template <typename T>
+__device__ __forceinline__ uint32_t merge_accumulate(T* s_acc, uint32_t* s_start, int32_t* s_lo, uint32_t* s_wt,
+                                                     const TileDesc& td, const SegDesc& sd, int slot,
+                                                     const int32_t* __restrict__ idx,
+                                                     const float* __restrict__ val, int P, int64_t stride_k,
+                                                     int nb, const int32_t* __restrict__ bounds) {
   const int tid = threadIdx.x;
-  const int slot = (int)blockIdx.x + td.seg;  // every earlier layer owns one extra (end) slot
-  for (int i = tid * 4; i < kMergeTile; i += 1024)
-    *reinterpret_cast<float4*>(&s_acc[i]) = make_float4(0.f, 0.f, 0.f, 0.f);
+  uint32_t entries = 0;
+  for (int i = tid; i < kMergeTile; i += 256) s_acc[i] = (T)0;
   for (int p0 = 0; p0 < P; p0 += 256) {
     const int np = P - p0 < 256 ? P - p0 : 256;
     int lo = 0;
@@ -968,6 +962,7 @@ __global__ __launch_bounds__(256) void k_merge(const TileDesc* __restrict__ mtil
     s_lo[tid] = lo;
     if (tid == 0) s_start[256] = total;
     __syncthreads();
+    entries += total;
     for (uint32_t base = 0; base < total; base += 1024) {
       int pe[4];
       uint32_t off[4];
@@ -1004,15 +999,52 @@ __global__ __launch_bounds__(256) void k_merge(const TileDesc* __restrict__ mtil
       }
       for (int q = qf; q <= ql; ++q) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
-          if (pe[r] == q && off[r] < (uint32_t)td.n) s_acc[off[r]] = __fadd_rn(s_acc[off[r]], v[r]);
+        for (int r = 0; r < 4; ++r) {
+          if (pe[r] == q && off[r] < (uint32_t)td.n) {
+            if (sizeof(T) == 4) s_acc[off[r]] = (T)__fadd_rn((float)s_acc[off[r]], v[r]);
+            else s_acc[off[r]] = s_acc[off[r]] + (T)v[r];
+          }
+        }
         __syncthreads();
       }
     }
     __syncthreads();
   }
+  return entries;
+}
+
+// k_merge<false>: the dense averaged update (Algorithm 1 lines 8-9): the whole tile is written
+// once, divided by P.  k_merge<true>: the parameter step of Algorithm 1 line 9 applied in
+// place, v -= update, touching only the elements whose sum is not zero (v - 0 == v bit for bit,
+// and a sum that starts from +0.0f is never -0.0f).  No atomics, fixed summation order.
+template <bool APPLY>
+__global__ __launch_bounds__(256) void k_merge(const TileDesc* __restrict__ mtiles,
+                                               const SegDesc* __restrict__ segs,
+                                               const int32_t* __restrict__ idx,
+                                               const float* __restrict__ val, int P,
+                                               int64_t stride_k, int nb,
+                                               const int32_t* __restrict__ bounds,
+                                               float* __restrict__ out) {
+  __shared__ float s_acc[kMergeTile];
+  __shared__ uint32_t s_start[257];
+  __shared__ int32_t s_lo[256];
+  __shared__ uint32_t s_wt[4];
+  const TileDesc td = mtiles[blockIdx.x];
+  const SegDesc sd = segs[td.seg];
+  const int tid = threadIdx.x;
+  const int slot = (int)blockIdx.x + td.seg;  // every earlier layer owns one extra (end) slot
+  const uint32_t entries =
+      merge_accumulate<float>(s_acc, s_start, s_lo, s_wt, td, sd, slot, idx, val, P, stride_k, nb, bounds);
   const float fp = (float)P;
-  float* u = update + td.start;
+  float* u = out + td.start;
+  if (APPLY) {
+    if (entries == 0) return;  // uniform over the workgroup
+    for (int e = tid; e < td.n; e += 256) {
+      const float sacc = s_acc[e];
+      if (sacc != 0.0f) u[e] = __fsub_rn(u[e], __fdiv_rn(sacc, fp));
+    }
+    return;
+  }
   const bool vec = aligned16(u, u);
   for (int e = tid * 4; e < td.n; e += 1024) {
     if (vec && e + 3 < td.n) {
@@ -1029,13 +1061,104 @@ __global__ __launch_bounds__(256) void k_merge(const TileDesc* __restrict__ mtil
   }
 }
 
+// Section 6.2, per tile: with s = sum_p residual_p (the residuals after sparsification) and
+// x = s + sum_p selected_p, the tile's parts of ||s||^2 and ||x||^2 in double.  Sums over
+// workers run in worker order; the tile's two partial sums go to partials[2*tile], [2*tile+1].
+__global__ __launch_bounds__(256) void k_delta_tiles(const TileDesc* __restrict__ mtiles,
+                                                     const SegDesc* __restrict__ segs,
+                                                     const float* __restrict__ res, int64_t res_stride,
+                                                     const int32_t* __restrict__ idx,
+                                                     const float* __restrict__ val, int P,
+                                                     int64_t stride_k, int nb,
+                                                     const int32_t* __restrict__ bounds,
+                                                     double* __restrict__ partials) {
+  __shared__ double s_acc[kMergeTile];
+  __shared__ uint32_t s_start[257];
+  __shared__ int32_t s_lo[256];
+  __shared__ uint32_t s_wt[4];
+  __shared__ double s_red[8];
+  const TileDesc td = mtiles[blockIdx.x];
+  const SegDesc sd = segs[td.seg];
+  const int tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
+  const int slot = (int)blockIdx.x + td.seg;
+  (void)merge_accumulate<double>(s_acc, s_start, s_lo, s_wt, td, sd, slot, idx, val, P, stride_k, nb, bounds);
+  double num = 0.0, sq = 0.0;
+  const float* rt = res + td.start;
+  const bool vec = aligned16(rt, rt) && (res_stride & 3) == 0;
+  for (int e = tid * 4; e < td.n; e += 1024) {
+    double ssum[4] = {0.0, 0.0, 0.0, 0.0};
+    if (vec && e + 3 < td.n) {
+      const float* r = rt + e;
+#pragma unroll 8
+      for (int p = 0; p < P; ++p) {
+        const float4 v = *reinterpret_cast<const float4*>(r + (int64_t)p * res_stride);
+        ssum[0] += (double)v.x;
+        ssum[1] += (double)v.y;
+        ssum[2] += (double)v.z;
+        ssum[3] += (double)v.w;
+      }
+    } else {
+      for (int c = 0; c < 4; ++c)
+        if (e + c < td.n)
+          for (int p = 0; p < P; ++p) ssum[c] += (double)rt[e + c + (int64_t)p * res_stride];
+    }
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      if (e + c < td.n) {
+        const double x = ssum[c] + s_acc[e + c];
+        num += ssum[c] * ssum[c];
+        sq += x * x;
+      }
+    }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    num += __shfl_xor(num, o, 64);
+    sq += __shfl_xor(sq, o, 64);
+  }
+  if (lane == 0) { s_red[w] = num; s_red[4 + w] = sq; }
+  __syncthreads();
+  if (tid == 0) {
+    partials[2 * (int64_t)blockIdx.x + 0] = (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]);
+    partials[2 * (int64_t)blockIdx.x + 1] = (s_red[4] + s_red[5]) + (s_red[6] + s_red[7]);
+  }
+}
+
+// Section 6.2, per layer: add the tiles' partial sums in a fixed order and form
+// delta = ||s||^2 / ((1 - k/d) ||x||^2)  (NaN when the denominator is 0).
+// out3[3*l] = ||s||^2, out3[3*l+1] = ||x||^2, out3[3*l+2] = delta.
+__global__ __launch_bounds__(256) void k_delta_finish(const SegDesc* __restrict__ segs,
+                                                      const int32_t* __restrict__ seg_mtile0,
+                                                      const double* __restrict__ partials,
+                                                      double* __restrict__ out3) {
+  __shared__ double s_a[256], s_b[256];
+  const int l = blockIdx.x, tid = threadIdx.x;
+  const int t0 = seg_mtile0[l], t1 = seg_mtile0[l + 1];
+  double a = 0.0, b = 0.0;
+  for (int t = t0 + tid; t < t1; t += 256) { a += partials[2 * (int64_t)t]; b += partials[2 * (int64_t)t + 1]; }
+  s_a[tid] = a;
+  s_b[tid] = b;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if (tid < o) { s_a[tid] += s_a[tid + o]; s_b[tid] += s_b[tid + o]; }
+    __syncthreads();
+  }
+  if (tid == 0) {
+    const SegDesc sd = segs[l];
+    const double den = (1.0 - (double)sd.k / (double)sd.d) * s_b[0];
+    out3[3 * l + 0] = s_a[0];
+    out3[3 * l + 1] = s_b[0];
+    out3[3 * l + 2] = den > 0.0 ? s_a[0] / den : __longlong_as_double(0x7FF8000000000000LL);
+  }
+}
+
 // ------------------------------------------------------------------ launch ---
 const char* kernel_name(int id) {
   static const char* names[K_NUM] = {
       "k_zero_u32", "k_small<4,1>", "k_small<4,8>", "k_small<16,10>", "k_sample", "k_stream", "k_cscan",
       "k_cgather", "k_small<4,1,cand>", "k_small<4,8,cand>", "k_small<16,10,cand>", "k_hist<cand>",
       "k_hist<dense>", "k_choose", "k_count<cand>", "k_count<dense>", "k_scan", "k_emit<cand>",
-      "k_emit<dense>", "k_merge_bounds", "k_merge"};
+      "k_emit<dense>", "k_merge_bounds", "k_merge", "k_merge<apply>", "k_delta_tiles", "k_delta_finish"};
   return (id >= 0 && id < K_NUM) ? names[id] : nullptr;
 }
 
@@ -1167,17 +1290,32 @@ hipError_t launch_large(const LargePlan& pl, const Scratch& sc, const SegDesc* s
   return hipGetLastError();
 }
 
-hipError_t launch_merge(int n_tiles, const TileDesc* mtiles, int n_bchunks, const BChunk* bchunks, int nb,
-                        int32_t* bounds, const SegDesc* segs, const int32_t* idx, const float* val, int P,
-                        int64_t stride_k, float* update, hipStream_t s, Prof* prof) {
-  if (n_tiles <= 0) return hipSuccess;
+hipError_t launch_merge(int mode, const MergePlan& mp, int32_t* bounds, const SegDesc* segs, const int32_t* idx,
+                        const float* val, int P, int64_t stride_k, float* out, const float* res,
+                        int64_t res_stride, double* partials, double* out3, hipStream_t s, Prof* prof) {
+  if (mp.n_mtiles <= 0) return hipSuccess;
   {
     ProfScope ps(prof, K_MERGE_BOUNDS, s);
-    hipLaunchKernelGGL(k_merge_bounds, dim3(n_bchunks, P), dim3(256), 0, s, bchunks, segs, idx, stride_k, nb, bounds);
+    hipLaunchKernelGGL(k_merge_bounds, dim3(mp.n_bchunks, P), dim3(256), 0, s, mp.bchunks, segs, idx, stride_k,
+                       mp.nb, bounds);
   }
-  ProfScope ps(prof, K_MERGE, s);
-  hipLaunchKernelGGL(k_merge, dim3(n_tiles), dim3(256), 0, s, mtiles, segs, idx, val, P, stride_k, nb, bounds,
-                     update);
+  if (mode == MERGE_UPDATE) {
+    ProfScope ps(prof, K_MERGE, s);
+    hipLaunchKernelGGL((k_merge<false>), dim3(mp.n_mtiles), dim3(256), 0, s, mp.mtiles, segs, idx, val, P, stride_k,
+                       mp.nb, bounds, out);
+  } else if (mode == MERGE_APPLY) {
+    ProfScope ps(prof, K_MERGE_APPLY, s);
+    hipLaunchKernelGGL((k_merge<true>), dim3(mp.n_mtiles), dim3(256), 0, s, mp.mtiles, segs, idx, val, P, stride_k,
+                       mp.nb, bounds, out);
+  } else {
+    {
+      ProfScope ps(prof, K_DELTA_TILES, s);
+      hipLaunchKernelGGL(k_delta_tiles, dim3(mp.n_mtiles), dim3(256), 0, s, mp.mtiles, segs, res, res_stride, idx,
+                         val, P, stride_k, mp.nb, bounds, partials);
+    }
+    ProfScope ps(prof, K_DELTA_FINISH, s);
+    hipLaunchKernelGGL(k_delta_finish, dim3(mp.n_layers), dim3(256), 0, s, segs, mp.seg_mtile0, partials, out3);
+  }
   return hipGetLastError();
 }
 

@@ -48,6 +48,10 @@ def lib():
         L.lags_merge_sparse.restype = ctypes.c_int
         L.lags_merge_sparse.argtypes = [vp, vp, vp, vp, i32, i64, vp, vp]
         L.lags_strerror.restype, L.lags_strerror.argtypes = ctypes.c_char_p, [ctypes.c_int]
+        L.lags_apply_sparse.restype = ctypes.c_int
+        L.lags_apply_sparse.argtypes = [vp, vp, vp, vp, i32, i64, vp, vp]
+        L.lags_delta_monitor.restype = ctypes.c_int
+        L.lags_delta_monitor.argtypes = [vp, vp, vp, i64, vp, vp, i32, i64, vp, vp]
         L.lags_last_routes.restype = ctypes.c_int
         L.lags_last_routes.argtypes = [vp, vp, ctypes.POINTER(i32), i32]
         L.lags_profile_enable.restype, L.lags_profile_enable.argtypes = ctypes.c_int, [vp, ctypes.c_int]
@@ -151,6 +155,15 @@ class Context:
     def lags_merge_sparse(self, table, idx, val, P, stride_k, update_flat, stream=None):
         _check(lib().lags_merge_sparse(self.handle, table.handle, _ptr(idx), _ptr(val), int(P), int(stride_k),
                                        _ptr(update_flat), _stream(stream)), "lags_merge_sparse")
+
+    def lags_apply_sparse(self, table, idx, val, P, stride_k, param_flat, stream=None):
+        _check(lib().lags_apply_sparse(self.handle, table.handle, _ptr(idx), _ptr(val), int(P), int(stride_k),
+                                       _ptr(param_flat), _stream(stream)), "lags_apply_sparse")
+
+    def lags_delta_monitor(self, table, residual_flat, res_stride, idx, val, P, stride_k, out3, stream=None):
+        _check(lib().lags_delta_monitor(self.handle, table.handle, _ptr(residual_flat), int(res_stride), _ptr(idx),
+                                        _ptr(val), int(P), int(stride_k), _ptr(out3), _stream(stream)),
+               "lags_delta_monitor")
 
     def lags_last_routes(self, table):
         """Route code per layer of the last lags_sparsify_model call with `table` (diagnostic)."""

@@ -70,6 +70,44 @@ class Gpu:
         return u.cpu().numpy()
 
 
+    def apply(self, layers, idx, val, P, stride_k, param, table=None):
+        """Host arrays in, the updated parameters out (the input array is not modified)."""
+        t = self.torch
+        own = table is None
+        if own:
+            table = self.ctx.table(layers)
+        v = self.to_dev(param)
+        self.ctx.lags_apply_sparse(table, self.to_dev(idx), self.to_dev(val), P, stride_k, v)
+        t.cuda.synchronize()
+        if own:
+            table.destroy()
+        return v.cpu().numpy()
+
+    def delta(self, layers, residual, res_stride, idx, val, P, stride_k, table=None):
+        t = self.torch
+        own = table is None
+        if own:
+            table = self.ctx.table(layers)
+        out = t.full((len(layers) * 3,), -1.0, dtype=t.float64, device=self.dev)
+        self.ctx.lags_delta_monitor(table, self.to_dev(residual), res_stride, self.to_dev(idx), self.to_dev(val),
+                                    P, stride_k, out)
+        t.cuda.synchronize()
+        if own:
+            table.destroy()
+        return out.cpu().numpy().reshape(len(layers), 3)
+
+
+def assert_delta_close(name, got, want, rtol=1e-10):
+    """Tolerance of the delta metric: both sides sum in double, in the same order over workers;
+    only the order of the final sum over elements differs (relative error ~1e-15 * sqrt(d))."""
+    got, want = np.asarray(got), np.asarray(want)
+    assert got.shape == want.shape, name
+    nan_g, nan_w = np.isnan(got), np.isnan(want)
+    assert np.array_equal(nan_g, nan_w), (name, "NaN pattern differs")
+    ok = np.isclose(got[~nan_g], want[~nan_w], rtol=rtol, atol=0.0)
+    assert ok.all(), (name, got[~nan_g][~ok][:5], want[~nan_w][~ok][:5])
+
+
 def oracle_model_parallel(oracle, layers, grad, residual, lr, threads=None):
     """The oracle's per-layer function over all layers of a table, layers spread over host
     threads (ctypes releases the GIL).  Same result as oracle.sparsify_model."""

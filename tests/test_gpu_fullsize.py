@@ -14,7 +14,7 @@ and, on a sample of (worker, layer) pairs, the oracle's sparsifier on the same b
 import numpy as np
 import pytest
 
-from gpu_util import assert_same, note, oracle_model_parallel
+from gpu_util import assert_delta_close, assert_same, note, oracle_model_parallel
 from paper_1911_08727_amd import workloads
 
 pytestmark = pytest.mark.gpu
@@ -74,6 +74,8 @@ def _run_full(name, big_once=()):
     idx = torch.empty(P * K, dtype=torch.int32, device=dev)
     val = torch.empty(P * K, dtype=torch.float32, device=dev)
     upd = torch.empty(total, dtype=torch.float32, device=dev)
+    param = torch.randn(total, dtype=torch.float32, device=dev, generator=torch.Generator(device=dev).manual_seed(7))
+    delta = torch.empty(3 * len(layers), dtype=torch.float64, device=dev)
     fell_back = 0
     for it in range(wl.iters):
         note("%s iteration %d: generate" % (name, it))
@@ -92,6 +94,23 @@ def _run_full(name, big_once=()):
         want_u = np.empty(total, np.float32)
         oracle.merge_sparse(layers, hi, hv, P, K, want_u)
         assert_same("update it=%d" % it, upd.cpu().numpy(), want_u)
+
+        note("%s iteration %d: sparse apply vs oracle" % (name, it))
+        want_v = param.cpu().numpy()
+        oracle.apply_sparse(layers, hi, hv, P, K, want_v)
+        ctx.lags_apply_sparse(t1, idx, val, P, K, param)
+        torch.cuda.synchronize()
+        assert_same("param it=%d" % it, param.cpu().numpy(), want_v)
+
+        if it == wl.iters - 1:
+            note("%s iteration %d: delta metric vs oracle" % (name, it))
+            ctx.lags_delta_monitor(t1, res, total, idx, val, P, K, delta)
+            torch.cuda.synchronize()
+            want_d = oracle.delta_monitor(layers, res.cpu().numpy(), total, hi, hv, P, K)
+            assert_delta_close("delta", delta.cpu().numpy().reshape(-1, 3), want_d)
+            # the paper reports delta < 1 on real gradients (Fig. 2); on independent synthetic noise
+            # tiny layers (k = 1) scatter around 1, so this is reported, not asserted
+            note("%s delta: median %.4f, max %.4f" % (name, np.nanmedian(want_d[:, 2]), np.nanmax(want_d[:, 2])))
 
         note("%s iteration %d: properties" % (name, it))
         acc = _acc(torch, res_before, grad, wl.lr)

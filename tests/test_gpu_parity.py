@@ -7,7 +7,7 @@ import zlib
 import numpy as np
 import pytest
 
-from gpu_util import Gpu, assert_same, bits, note, oracle_model_parallel
+from gpu_util import Gpu, assert_delta_close, assert_same, bits, note, oracle_model_parallel
 from paper_1911_08727_amd import workloads
 
 pytestmark = pytest.mark.gpu
@@ -162,6 +162,18 @@ def _run_config(gpu, oracle, wl, iters, P, check_merge=True):
             oracle.merge_sparse(layers, all_i, all_v, P, K, want_u)
             got_u = gpu.merge(layers, all_i, all_v, P, K, total, table=table)
             assert_same("update it=%d" % it, got_u, want_u)
+            note("config %s iteration %d apply" % (wl.name, it))
+            param = np.random.default_rng(it).standard_normal(total).astype(np.float32)
+            got_v = gpu.apply(layers, all_i, all_v, P, K, param, table=table)
+            want_v = param.copy()
+            oracle.apply_sparse(layers, all_i, all_v, P, K, want_v)
+            assert_same("param it=%d" % it, got_v, want_v)
+            assert_same("param = v - update it=%d" % it, got_v, param - want_u)
+            note("config %s iteration %d delta" % (wl.name, it))
+            res_all = np.concatenate(res_gpu)
+            want_d = oracle.delta_monitor(layers, res_all, total, all_i, all_v, P, K)
+            got_d = gpu.delta(layers, res_all, total, all_i, all_v, P, K, table=table)
+            assert_delta_close("delta it=%d" % it, got_d, want_d)
     table.destroy()
 
 
@@ -295,6 +307,43 @@ def test_merge_closed_forms(gpu, oracle):
         oracle.merge_sparse(layers, idx, val, P, K, want)
         got = gpu.merge(layers, idx, val, P, K, total)
         assert_same("update P=%d" % P, got, want)
+        param = rng.standard_normal(total).astype(np.float32)
+        param[::5] = -0.0
+        want_v = param.copy()
+        oracle.apply_sparse(layers, idx, val, P, K, want_v)
+        assert_same("param P=%d" % P, gpu.apply(layers, idx, val, P, K, param), want_v)
+        res = rng.standard_normal(P * total).astype(np.float32)
+        assert_delta_close("delta P=%d" % P, gpu.delta(layers, res, total, idx, val, P, K),
+                           oracle.delta_monitor(layers, res, total, idx, val, P, K))
+
+
+def test_apply_and_delta_edge_layers(gpu, oracle):
+    """Layers of one element, k == d (delta is NaN), gaps and unaligned offsets, a padded pair
+    stride and a padded worker stride; parameters outside the layers keep their bits."""
+    rng = np.random.default_rng(61)
+    layers = [(3, 1, 1.0), (5, 10, 1.0), (17, 9000, 0.01), (9020, 8192, 0.001), (17220, 3, 0.5)]
+    total = 17230
+    P, K = 5, oracle.total_k(layers)
+    stride_k, res_stride = K + 3, total + 7
+    idx = np.full(P * stride_k, -5, np.int32)
+    val = np.full(P * stride_k, np.nan, np.float32)
+    res = rng.standard_normal(P * res_stride).astype(np.float32)
+    for p in range(P):
+        pos = 0
+        for (off, d, rho) in layers:
+            k = oracle.topk_count(d, rho)
+            idx[p * stride_k + pos:p * stride_k + pos + k] = np.sort(rng.choice(d, k, replace=False))
+            val[p * stride_k + pos:p * stride_k + pos + k] = rng.standard_normal(k)
+            pos += k
+    param = rng.standard_normal(total).astype(np.float32)
+    note("apply/delta edge layers")
+    want_v = param.copy()
+    oracle.apply_sparse(layers, idx, val, P, stride_k, want_v)
+    assert_same("param", gpu.apply(layers, idx, val, P, stride_k, param), want_v)
+    want_d = oracle.delta_monitor(layers, res, res_stride, idx, val, P, stride_k)
+    got_d = gpu.delta(layers, res, res_stride, idx, val, P, stride_k)
+    assert np.isnan(want_d[0, 2]) and np.isnan(want_d[1, 2])
+    assert_delta_close("delta", got_d, want_d)
 
 
 def test_determinism_and_scratch_independence(gpu, oracle):
