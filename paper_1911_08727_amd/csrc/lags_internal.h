@@ -24,10 +24,12 @@ constexpr int kSmall0 = 4 * 1 * 256;     // <= 1024  : 4 waves, 1 round
 constexpr int kSmall1 = 4 * 8 * 256;     // <= 8192  : 4 waves, 8 rounds
 constexpr int kSmall2 = 16 * 10 * 256;   // <= 40960 : 16 waves, 10 rounds
 
-// Threshold guess from a sample (large layers): 1024 pieces of 64 consecutive elements.
+// Threshold guess from a sample (large layers): 256 pieces of 64 consecutive elements.
+// The sample only has to rank the top k roughly: a smaller sample admits more candidates
+// (about k + 6 sqrt(k d / m) (d / m) ...), which costs 8 bytes each and nothing else.
 constexpr int kSamplePiece = 64;
-constexpr int kSamplePieces = 1024;
-constexpr int kSampleMax = kSamplePiece * kSamplePieces;   // 65536 sampled elements
+constexpr int kSamplePieces = 256;
+constexpr int kSampleMax = kSamplePiece * kSamplePieces;   // 16384 sampled elements
 constexpr int kSlot = 256;               // candidate slots per tile of a sampled layer
 constexpr int kDenseGrid = 2048;         // workgroups of the fallback kernels (grid-stride)
 

@@ -19,7 +19,7 @@
 // Three routes, chosen per layer by size:
 //   small  (d <= 40960): one workgroup, acc stays in registers between the single read of
 //          grad/residual and the single write of the residual.
-//   large, sampled: a sample of up to 65536 elements gives a threshold tau that, with high
+//   large, sampled: a sample of 16384 elements gives a threshold tau that, with high
 //          probability, admits slightly more than k entries.  One streaming pass writes acc
 //          into the residual buffer and collects every entry with key >= tau (in index
 //          order).  If at least k were collected (and the lists did not overflow) the exact
@@ -399,7 +399,7 @@ __global__ __launch_bounds__(NW * 64) void k_small(const SegDesc* __restrict__ s
 }
 
 // ------------------------------------------------------------------ sample ---
-// Threshold guess for one large layer: form acc on up to 1024 pieces of 64 consecutive
+// Threshold guess for one large layer: form acc on up to 256 pieces of 64 consecutive
 // elements spread over the layer (with a hashed offset inside each stride), and take the
 // sample's `sample_rank`-th largest key as tau.  Missing sample slots count as key 0.
 __global__ __launch_bounds__(1024) void k_sample(const SegDesc* __restrict__ segs,
@@ -408,7 +408,7 @@ __global__ __launch_bounds__(1024) void k_sample(const SegDesc* __restrict__ seg
                                                  const float* __restrict__ grad,
                                                  const float* __restrict__ res, float lr,
                                                  LState* __restrict__ lstate) {
-  constexpr int NW = 16, V = 16, NT = 1024;
+  constexpr int NW = 16, V = kSamplePieces / 64, NT = 1024;  // a wave takes 4 pieces per round
   __shared__ uint32_t s_hist[kBins0];
   __shared__ uint32_t s_wt[NW];
   __shared__ uint32_t s_sel[2];
@@ -422,7 +422,7 @@ __global__ __launch_bounds__(1024) void k_sample(const SegDesc* __restrict__ seg
   uint32_t a[V][4];
 #pragma unroll
   for (int j = 0; j < V; ++j) {
-    const int piece = w * 64 + j * 4 + (lane >> 4);
+    const int piece = w * (V * 4) + j * 4 + (lane >> 4);
     a[j][0] = a[j][1] = a[j][2] = a[j][3] = 0u;
     if (piece < ls.sample_pieces) {
       int start = piece * ls.sample_stride;
@@ -624,7 +624,11 @@ __global__ __launch_bounds__(1024) void k_cscan(const SegDesc* __restrict__ segs
 }
 
 // Copy the tiles' slots into the layer's contiguous candidate list (index order is kept
-// because tiles are laid out in index order).  One lane per tile.
+// because tiles are laid out in index order).  A wave takes 64 consecutive tiles; lane l
+// learns tile l's count and destination, then the wave copies all their entries 64 at a
+// time: for the e-th entry the owning tile is found by a binary search over the lanes'
+// exclusive counts (shuffles), so neighbouring lanes read neighbouring slots of one tile
+// and write neighbouring list positions.
 __global__ __launch_bounds__(256) void k_cgather(int n_chunks, const int32_t* __restrict__ chunk_lseg,
                                                  const LargeSeg* __restrict__ lsegs,
                                                  const LState* __restrict__ lstate,
@@ -632,14 +636,41 @@ __global__ __launch_bounds__(256) void k_cgather(int n_chunks, const int32_t* __
                                                  const uint32_t* __restrict__ chunk_off,
                                                  const uint2* __restrict__ slots,
                                                  uint2* __restrict__ cand) {
-  const int c = blockIdx.x * 256 + threadIdx.x;
-  if (c >= n_chunks) return;
-  const int li = chunk_lseg[c];
-  if (lstate[li].mode != MODE_SPARSE) return;
-  const uint32_t cnt = chunk_cnt[c];
-  uint2* dst = cand + lsegs[li].cand_base + chunk_off[c];
-  const uint2* src = slots + (int64_t)c * kSlot;
-  for (uint32_t q = 0; q < cnt; ++q) dst[q] = src[q];
+  const int lane = lane_id();
+  const int c0 = (int)((blockIdx.x * 256u + threadIdx.x) >> 6) * 64;  // first tile of the wave
+  if (c0 >= n_chunks) return;  // wave-uniform
+  const int c = c0 + lane;
+  uint32_t cnt = 0;
+  int64_t dst = 0;
+  if (c < n_chunks) {
+    const int li = chunk_lseg[c];
+    if (lstate[li].mode == MODE_SPARSE) {
+      cnt = chunk_cnt[c];
+      dst = lsegs[li].cand_base + chunk_off[c];
+    }
+  }
+  const uint32_t incl = wave_incl_scan(cnt, lane);
+  const uint32_t pre = incl - cnt;
+  const uint32_t total = __shfl(incl, 63, 64);
+  const uint32_t dst_lo = (uint32_t)dst, dst_hi = (uint32_t)(dst >> 32);
+  for (uint32_t base = 0; base < total; base += 64) {  // wave-uniform trip count
+    const bool live = base + lane < total;
+    const uint32_t e = live ? base + lane : total - 1;  // idle lanes search along, then skip the copy
+    int lo = 0, hi = 63;  // last lane whose exclusive count is <= e: the tile that owns entry e
+#pragma unroll
+    for (int step = 0; step < 6; ++step) {
+      const int mid = (lo + hi + 1) >> 1;
+      const uint32_t v = __shfl(pre, mid, 64);
+      if (v <= e) lo = mid; else hi = mid - 1;
+    }
+    const uint32_t p0 = __shfl(pre, lo, 64);
+    const uint32_t d_lo = __shfl(dst_lo, lo, 64), d_hi = __shfl(dst_hi, lo, 64);
+    if (live) {
+      const uint32_t q = e - p0;
+      const int64_t d = (int64_t)(((uint64_t)d_hi << 32) | d_lo) + q;
+      cand[d] = slots[(int64_t)(c0 + lo) * kSlot + q];
+    }
+  }
 }
 
 // ------------------------------------------------------------------ multi-block select
