@@ -1,0 +1,168 @@
+"""GPU tests at the limits of the interface: the largest layer the ABI admits, resuming from a
+saved residual in a fresh context, a non-default stream, the worker-count limit of the merge,
+and rejected arguments of the merge-type entry points."""
+import numpy as np
+import pytest
+
+from gpu_util import Gpu, assert_same, note, oracle_model_parallel
+from paper_1911_08727_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    g = Gpu()
+    yield g
+    g.close()
+
+
+def test_largest_layer_properties(gpu):
+    """d = 2^31 - 1 (the largest layer the ABI admits; int32 indices reach 2^31 - 2), checked by
+    properties that hold at any size: k strictly ascending in-range indices, values are acc,
+    residual is +0 at kept entries and acc elsewhere, kept magnitudes dominate, tie rule."""
+    torch = gpu.torch
+    d = 2 ** 31 - 1
+    k = 2_147_484                          # ceil(0.001 * d)
+    gen = torch.Generator(device=gpu.dev).manual_seed(5)
+    g = torch.empty(d, dtype=torch.float32, device=gpu.dev)
+    g.normal_(0.0, 1.0, generator=gen)
+    g[-1] = 100.0                          # the last element must be kept: index 2^31 - 2
+    res0 = torch.empty(d, dtype=torch.float32, device=gpu.dev)
+    res0.normal_(0.0, 0.5, generator=gen)
+    res = res0.clone()
+    oi = torch.empty(k, dtype=torch.int32, device=gpu.dev)
+    ov = torch.empty(k, dtype=torch.float32, device=gpu.dev)
+    note("largest layer d=%d k=%d" % (d, k))
+    gpu.ctx.lags_sparsify_layer(g, res, 0.1, k, oi, ov)
+    torch.cuda.synchronize()
+    acc = torch.add(res0, torch.mul(g, float(np.float32(0.1))))
+    del g, res0
+    i = oi.long()
+    assert int(i[0]) >= 0 and int(i[-1]) == d - 1
+    assert bool((i[1:] > i[:-1]).all())
+    assert torch.equal(ov.view(torch.int32), acc[i].view(torch.int32))
+    assert bool((res[i].view(torch.int32) == 0).all())
+    key = acc.view(torch.int32) & 0x7FFFFFFF
+    T = int(key[i].min())
+    ties_kept = i[key[i] == T]
+    res_bits = res.view(torch.int32)
+    acc_bits = acc.view(torch.int32)
+    acc_bits[i] = 0                        # acc with the kept entries zeroed is the expected residual
+    assert torch.equal(res_bits, acc_bits)
+    key[i] = -1
+    assert int(key.max()) <= T
+    dropped_ties = torch.nonzero(key == T).flatten()
+    if len(dropped_ties):
+        assert int(ties_kept.max()) < int(dropped_ties.min())
+
+
+def test_resume_from_saved_residual(gpu, oracle):
+    """The context holds nothing that influences results: 6 iterations in one context equal
+    3 iterations, a fresh context fed the saved residual, and 3 more."""
+    from paper_1911_08727_amd import lags
+    rng = np.random.default_rng(71)
+    layers = [(0, 200_000, 0.002), (200_000, 5_000, 0.01), (205_000, 90_000, 0.001)]
+    total = 295_000
+    grads = [rng.standard_normal(total).astype(np.float32) for _ in range(6)]
+    straight = np.zeros(total, np.float32)
+    outs = []
+    for it in range(6):
+        note("resume: straight iteration %d" % it)
+        gi, gv, straight = gpu.sparsify_model(layers, grads[it], straight, 0.1)
+        outs.append((gi, gv))
+    res = np.zeros(total, np.float32)
+    for it in range(3):
+        _, _, res = gpu.sparsify_model(layers, grads[it], res, 0.1)
+    other = Gpu()
+    try:
+        for it in range(3, 6):
+            note("resume: fresh context iteration %d" % it)
+            gi, gv, res = other.sparsify_model(layers, grads[it], res, 0.1)
+            assert_same("idx it=%d" % it, gi, outs[it][0])
+            assert_same("val it=%d" % it, gv, outs[it][1])
+    finally:
+        other.close()
+    assert_same("residual", res, straight)
+
+
+def test_non_default_stream(gpu, oracle):
+    """Work is enqueued on the stream the caller names and ordered with the caller's other work on it."""
+    torch = gpu.torch
+    rng = np.random.default_rng(73)
+    layers = [(0, 500_000, 0.001), (500_000, 3000, 0.01)]
+    total = 503_000
+    g_h = rng.standard_normal(total).astype(np.float32)
+    want_r = np.zeros(total, np.float32)
+    wi, wv = oracle_model_parallel(oracle, layers, g_h, want_r, 0.1)
+    table = gpu.ctx.table(layers)
+    K = table.total_k
+    stream = torch.cuda.Stream(device=gpu.dev)          # default priority
+    g = gpu.to_dev(g_h)
+    oi = torch.empty(K, dtype=torch.int32, device=gpu.dev)
+    ov = torch.empty(K, dtype=torch.float32, device=gpu.dev)
+    upd = torch.empty(total, dtype=torch.float32, device=gpu.dev)
+    torch.cuda.synchronize()
+    note("non-default stream")
+    with torch.cuda.stream(stream):
+        r = torch.zeros(total, dtype=torch.float32, device=gpu.dev)   # produced on the same stream
+        gpu.ctx.lags_sparsify_model(table, g, r, 0.1, oi, ov, stream)
+        gpu.ctx.lags_merge_sparse(table, oi, ov, 1, K, upd, stream)
+    stream.synchronize()
+    assert_same("idx", oi.cpu().numpy(), wi)
+    assert_same("val", ov.cpu().numpy(), wv)
+    assert_same("res", r.cpu().numpy(), want_r)
+    want_u = np.empty(total, np.float32)
+    oracle.merge_sparse(layers, wi, wv, 1, K, want_u)
+    assert_same("update", upd.cpu().numpy(), want_u)
+    table.destroy()
+
+
+def test_merge_worker_limit_and_rejected_arguments(gpu, oracle):
+    """P = 1024 is the most the merge accepts; P = 0, P = 1025, a pair stride below sum k, a
+    worker stride below the model and null pointers are rejected before anything is written."""
+    torch = gpu.torch
+    from paper_1911_08727_amd import lags
+    rng = np.random.default_rng(79)
+    layers = [(0, 3000, 0.002), (3000, 9000, 0.001)]
+    total, K, P = 12000, oracle.total_k(layers), 1024
+    idx = np.empty(P * K, np.int32)
+    val = rng.standard_normal(P * K).astype(np.float32)
+    for p in range(P):
+        pos = 0
+        for (_, d, rho) in layers:
+            k = oracle.topk_count(d, rho)
+            idx[p * K + pos:p * K + pos + k] = np.sort(rng.choice(d, k, replace=False))
+            pos += k
+    note("merge with P=1024")
+    want = np.empty(total, np.float32)
+    oracle.merge_sparse(layers, idx, val, P, K, want)
+    assert_same("update", gpu.merge(layers, idx, val, P, K, total), want)
+
+    table = gpu.ctx.table(layers)
+    di, dv = gpu.to_dev(idx), gpu.to_dev(val)
+    upd = torch.full((total,), 5.0, dtype=torch.float32, device=gpu.dev)
+    out3 = torch.full((6,), 5.0, dtype=torch.float64, device=gpu.dev)
+    res = torch.zeros(2 * total, dtype=torch.float32, device=gpu.dev)
+    for bad in (dict(P=0), dict(P=1025), dict(stride=K - 1)):
+        with pytest.raises(lags.LagsError):
+            gpu.ctx.lags_merge_sparse(table, di, dv, bad.get("P", 2), bad.get("stride", K), upd)
+        with pytest.raises(lags.LagsError):
+            gpu.ctx.lags_apply_sparse(table, di, dv, bad.get("P", 2), bad.get("stride", K), upd)
+        with pytest.raises(lags.LagsError):
+            gpu.ctx.lags_delta_monitor(table, res, total, di, dv, bad.get("P", 2), bad.get("stride", K), out3)
+    with pytest.raises(lags.LagsError):
+        gpu.ctx.lags_delta_monitor(table, res, total - 1, di, dv, 2, K, out3)     # workers would overlap
+    with pytest.raises(lags.LagsError):
+        gpu.ctx.lags_merge_sparse(table, None, dv, 2, K, upd)
+    with pytest.raises(lags.LagsError):
+        gpu.ctx.lags_apply_sparse(table, di, dv, 2, K, None)
+    torch.cuda.synchronize()
+    assert bool((upd == 5.0).all()) and bool((out3 == 5.0).all())
+    with pytest.raises(lags.LagsError):
+        gpu.ctx.table([])                                                         # no layers
+    with pytest.raises(lags.LagsError):
+        gpu.ctx.table([(0, 0, 0.5)])                                              # empty layer
+    with pytest.raises(lags.LagsError):
+        gpu.ctx.table([(0, 2 ** 31, 0.5)])                                        # beyond int32 indices
+    table.destroy()
