@@ -145,6 +145,9 @@ int lags_last_routes(lags_ctx *ctx, const lags_table *t, int32_t *route, int32_t
  * (0 <= kernel_id < lags_profile_num_kernels()) to *total_ms / *launches, and
  * lags_profile_reset drops everything recorded so far.  All three are host-synchronous. */
 int lags_profile_enable(lags_ctx *ctx, int on);
+/* Like lags_profile_enable(ctx, 1) but only launches of kernel `kernel_id` are bracketed
+ * (two events per launch of that kernel instead of two per launch of every kernel). */
+int lags_profile_enable_kernel(lags_ctx *ctx, int kernel_id);
 int lags_profile_num_kernels(void);
 const char *lags_profile_kernel_name(int kernel_id); /* NULL if out of range */
 int lags_profile_read(lags_ctx *ctx, int kernel_id, double *total_ms, int64_t *launches);

@@ -540,6 +540,14 @@ int lags_last_routes(lags_ctx* ctx, const lags_table* t, int32_t* route, int32_t
 int lags_profile_enable(lags_ctx* ctx, int on) {
   if (!ctx) return LAGS_EINVAL;
   ctx->prof.on = on != 0;
+  ctx->prof.only = -1;
+  return LAGS_OK;
+}
+
+int lags_profile_enable_kernel(lags_ctx* ctx, int kernel_id) {
+  if (!ctx || kernel_id < 0 || kernel_id >= K_NUM) return LAGS_EINVAL;
+  ctx->prof.on = true;
+  ctx->prof.only = kernel_id;
   return LAGS_OK;
 }
 

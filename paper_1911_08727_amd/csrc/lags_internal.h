@@ -123,6 +123,7 @@ const char* kernel_name(int id);
 
 struct Prof {
   bool on = false;
+  int only = -1;        // >= 0: record this kernel id only
   struct Rec { int id; hipEvent_t a, b; };
   std::vector<Rec> recs;
 };
@@ -130,7 +131,8 @@ struct Prof {
 // Brackets one kernel launch with events when profiling is on.
 struct ProfScope {
   Prof* p; hipStream_t s; hipEvent_t a = nullptr, b = nullptr; int id;
-  ProfScope(Prof* prof, int kid, hipStream_t st) : p(prof && prof->on ? prof : nullptr), s(st), id(kid) {
+  ProfScope(Prof* prof, int kid, hipStream_t st)
+      : p(prof && prof->on && (prof->only < 0 || prof->only == kid) ? prof : nullptr), s(st), id(kid) {
     if (p && hipEventCreate(&a) == hipSuccess && hipEventCreate(&b) == hipSuccess) (void)hipEventRecord(a, s);
     else p = nullptr;
   }

@@ -55,6 +55,8 @@ def lib():
         L.lags_last_routes.restype = ctypes.c_int
         L.lags_last_routes.argtypes = [vp, vp, ctypes.POINTER(i32), i32]
         L.lags_profile_enable.restype, L.lags_profile_enable.argtypes = ctypes.c_int, [vp, ctypes.c_int]
+        L.lags_profile_enable_kernel.restype = ctypes.c_int
+        L.lags_profile_enable_kernel.argtypes = [vp, ctypes.c_int]
         L.lags_profile_num_kernels.restype, L.lags_profile_num_kernels.argtypes = ctypes.c_int, []
         L.lags_profile_kernel_name.restype, L.lags_profile_kernel_name.argtypes = ctypes.c_char_p, [ctypes.c_int]
         L.lags_profile_read.restype = ctypes.c_int
@@ -173,6 +175,13 @@ class Context:
 
     def lags_profile_enable(self, on):
         _check(lib().lags_profile_enable(self.handle, int(bool(on))), "lags_profile_enable")
+
+    def lags_profile_enable_kernel(self, name):
+        for kid in range(lib().lags_profile_num_kernels()):
+            if lib().lags_profile_kernel_name(kid).decode() == name:
+                _check(lib().lags_profile_enable_kernel(self.handle, kid), "lags_profile_enable_kernel")
+                return
+        raise KeyError(name)
 
     def lags_profile_reset(self):
         _check(lib().lags_profile_reset(self.handle), "lags_profile_reset")
