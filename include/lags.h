@@ -69,7 +69,7 @@ int lags_destroy(lags_ctx *ctx);
  * `layers` is read during the call only.  A caller may list P workers x L layers of one
  * flat buffer in a single table.  Synchronous (allocates and copies). */
 int lags_table_create(lags_ctx *ctx, const lags_layer_desc *layers, int32_t n, lags_table **out);
-int lags_table_destroy(lags_table *t);
+int lags_table_destroy(lags_table *t); /* before lags_destroy of its context; not while work using it is in flight */
 int32_t lags_table_num_layers(const lags_table *t);
 int64_t lags_table_total_k(const lags_table *t);              /* sum_l k_l = length of out_idx/out_val */
 int64_t lags_table_k(const lags_table *t, int32_t l);         /* -1 if l is out of range               */
@@ -80,7 +80,8 @@ int64_t lags_table_out_offset(const lags_table *t, int32_t l);/* -1 if l is out 
  *   residual  device, float[d], read then overwritten with the new residual
  *   out_idx   device, int32[k], written: selected indices, ascending
  *   out_val   device, float[k], written: acc at those indices (bit exact)
- * Buffers must not overlap.  `lr` must be finite. */
+ * Buffers must not overlap.  `lr` must be finite.  The first call for a new (d, k) prepares
+ * and caches a one-layer plan (a synchronous allocation); later calls only enqueue. */
 int lags_sparsify_layer(lags_ctx *ctx, const float *grad, float *residual, int64_t d, float lr,
                         int64_t k, int32_t *out_idx, float *out_val, void *hip_stream);
 

@@ -82,6 +82,8 @@ struct lags_table {
 
 namespace {
 
+constexpr size_t kMaxLayerPlans = 4096;  // cached one-layer plans of lags_sparsify_layer
+
 struct DeviceGuard {
   int prev = -1;
   bool ok = true;
@@ -433,6 +435,15 @@ int lags_sparsify_layer(lags_ctx* ctx, const float* grad, float* residual, int64
   if (it != ctx->layer_tables.end()) {
     t = it->second;
   } else {
+    // the cache of one-layer plans is bounded: when full it is emptied (hipFree waits for the
+    // device, so no launch still reads the plans that go away)
+    if (ctx->layer_tables.size() >= kMaxLayerPlans) {
+      for (auto& kv : ctx->layer_tables) {
+        free_table_device(kv.second);
+        delete kv.second;
+      }
+      ctx->layer_tables.clear();
+    }
     std::vector<int64_t> off(1, 0), dd(1, d), kk(1, k);
     int rc = build_table(ctx, off, dd, kk, &t);
     if (rc != LAGS_OK) return rc;
