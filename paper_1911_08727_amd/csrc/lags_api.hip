@@ -133,7 +133,7 @@ void free_table_device(lags_table* t) {
 // Plan of the threshold guess for a large layer of d elements keeping k: how many sample
 // pieces, which rank of the sample becomes the threshold, how long the candidate list may
 // get.  Returns false if the layer is not worth sampling (k too large for the slots).
-bool plan_sample(int64_t d, int64_t k, LargeSeg* ls) {
+bool plan_sample(int64_t d, int64_t k, LargeSeg* ls, double* per_tile) {
   int64_t pieces, stride;
   if (d >= kSampleMax) {
     pieces = kSamplePieces;
@@ -148,8 +148,9 @@ bool plan_sample(int64_t d, int64_t k, LargeSeg* ls) {
   // deviations of the sampled count plus a constant, so that fewer than k is very unlikely
   const double jd = std::ceil(fk + 6.0 * std::sqrt(fk) + 20.0);
   if (jd > m) return false;
-  // expected candidates per tile must stay well inside the tile's slots
-  if (jd / m * (double)kTile > (double)kSlot * 0.5) return false;
+  // expected candidates per tile must stay well inside the largest slot size
+  *per_tile = jd / m * (double)kTile;
+  if (*per_tile > (double)kSlotMax * 0.5) return false;
   const double expect = jd / m * (double)d;
   const int64_t cap = std::min<int64_t>(d, (int64_t)(2.0 * expect) + 8192);
   ls->sample_rank = (int32_t)jd;
@@ -175,7 +176,8 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
   std::vector<TileDesc> tiles, ctiles, mtiles;
   std::vector<BChunk> bchunks;
   std::vector<int32_t> seg_mtile0;
-  int64_t n_ctile_dense = 0;   // tiles of sampled layers: each owns kSlot candidate slots
+  int64_t n_ctile_dense = 0;   // tiles of sampled layers: each owns `slot` candidate slots
+  double max_per_tile = 0.0;   // largest expected candidate count per tile over the sampled layers
   int64_t cand_total = 0;
   constexpr int64_t kMaxTiles = 1 << 28;
   try {
@@ -200,7 +202,9 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
         const int32_t li = (int32_t)t->lsegs.size();
         ls.seg = l;
         ls.cand_class = CAND_NONE;
-        const bool sampled_layer = plan_sample(d[l], k[l], &ls);
+        double per_tile = 0.0;
+        const bool sampled_layer = plan_sample(d[l], k[l], &ls, &per_tile);
+        if (sampled_layer) max_per_tile = std::max(max_per_tile, per_tile);
         ls.tile_begin = (int32_t)tiles.size();
         const int64_t nt = (d[l] + kTile - 1) / kTile;
         if ((int64_t)tiles.size() + nt > kMaxTiles) { delete t; return LAGS_ECAPACITY; }
@@ -281,6 +285,8 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
   pl.n_sampled = (int)sampled.size();
   pl.n_chunks = (int)chunk_lseg.size();
   pl.n_ctiles = (int)ctiles.size();
+  pl.slot = kSlotMin;
+  while ((double)pl.slot < 2.0 * max_per_tile && pl.slot < kSlotMax) pl.slot *= 2;
   for (int c = 0; c < 3; ++c) pl.n_cand_small[c] = (int)cand_small[c].size();
 
   int rc = upload(&t->d_segs, t->segs);
@@ -313,7 +319,7 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
     if (rc == LAGS_OK) rc = ctx->items.grow((size_t)pl.n_tiles * sizeof(int32_t));
     if (rc == LAGS_OK) rc = ctx->chunk_cnt.grow((size_t)pl.n_chunks * sizeof(uint32_t));
     if (rc == LAGS_OK) rc = ctx->chunk_off.grow((size_t)pl.n_chunks * sizeof(uint32_t));
-    if (rc == LAGS_OK) rc = ctx->slots.grow((size_t)pl.n_chunks * kSlot * sizeof(uint2));
+    if (rc == LAGS_OK) rc = ctx->slots.grow((size_t)pl.n_chunks * (size_t)pl.slot * sizeof(uint2));
     if (rc == LAGS_OK) rc = ctx->cand.grow((size_t)cand_total * sizeof(uint2));
   }
   if (rc != LAGS_OK) {

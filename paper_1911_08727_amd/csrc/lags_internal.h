@@ -10,7 +10,7 @@ namespace lags {
 // Geometry of the multi-block ("large") path: one workgroup of 4 waves per tile,
 // each wave owns a contiguous quarter of the tile and walks it in rounds of 64 lanes x 4
 // consecutive elements.  A tile of a sampled layer is also the unit ("chunk") that owns
-// kSlot candidate slots.
+// `slot` candidate slots (a power of two between kSlotMin and kSlotMax chosen per table).
 constexpr int kTileWaves = 4;
 constexpr int kTileV = 4;                               // rounds per wave
 constexpr int kWaveChunk = kTileV * 256;                // 1024 elements per wave
@@ -30,7 +30,8 @@ constexpr int kSmall2 = 16 * 10 * 256;   // <= 40960 : 16 waves, 10 rounds
 constexpr int kSamplePiece = 64;
 constexpr int kSamplePieces = 256;
 constexpr int kSampleMax = kSamplePiece * kSamplePieces;   // 16384 sampled elements
-constexpr int kSlot = 256;               // candidate slots per tile of a sampled layer
+constexpr int kSlotMin = 256;            // candidate slots per tile of a sampled layer: the table uses the
+constexpr int kSlotMax = 2048;           // smallest power of two >= twice the expected count of any layer
 constexpr int kDenseGrid = 2048;         // workgroups of the fallback kernels (grid-stride)
 
 constexpr int kMergeTile = 8192;
@@ -90,6 +91,7 @@ struct LState {         // per call, per large layer
 
 struct LargePlan {      // everything launch_large needs (device pointers + counts)
   int n_large = 0, n_tiles = 0, n_sampled = 0, n_chunks = 0, n_ctiles = 0;
+  int slot = kSlotMin;                  // candidate slots per sampled tile
   int n_cand_small[3] = {0, 0, 0};
   const LargeSeg* lsegs = nullptr;
   const TileDesc* tiles = nullptr;      // dense tiles
@@ -108,7 +110,7 @@ struct Scratch {        // context-owned device memory, contents meaningless bet
   int32_t* items = nullptr;       // n_tiles: dense tiles to process in fallback mode
   uint32_t* chunk_cnt = nullptr;  // n_chunks
   uint32_t* chunk_off = nullptr;  // n_chunks
-  uint2* slots = nullptr;         // n_chunks * kSlot
+  uint2* slots = nullptr;         // n_chunks * slot
   uint2* cand = nullptr;          // sum of cap over sampled layers
 };
 

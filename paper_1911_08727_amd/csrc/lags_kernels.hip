@@ -465,7 +465,7 @@ __global__ __launch_bounds__(256) void k_stream(const TileDesc* __restrict__ til
                                                 float* __restrict__ res, float lr,
                                                 const LState* __restrict__ lstate,
                                                 uint32_t* __restrict__ chunk_cnt,
-                                                uint2* __restrict__ slots,
+                                                uint2* __restrict__ slots, int nslot,
                                                 uint32_t* __restrict__ ghist) {
   __shared__ uint32_t s_hist[kBins0];
   __shared__ uint32_t s_cnt[kTileWaves];
@@ -526,9 +526,9 @@ __global__ __launch_bounds__(256) void k_stream(const TileDesc* __restrict__ til
       if (i < w) base += t;
       total += t;
     }
-    if (tid == 0) chunk_cnt[td.ctile] = total;  // a count above kSlot marks the tile as overflowed
+    if (tid == 0) chunk_cnt[td.ctile] = total;  // a count above nslot marks the tile as overflowed
     if (wtot) {  // wave-uniform
-      uint2* slot = slots + (int64_t)td.ctile * kSlot;
+      uint2* slot = slots + (int64_t)td.ctile * nslot;
       const int32_t idx0 = td.local0 + w * kWaveChunk;
 #pragma unroll
       for (int j = 0; j < kTileV; ++j) {
@@ -543,7 +543,7 @@ __global__ __launch_bounds__(256) void k_stream(const TileDesc* __restrict__ til
 #pragma unroll
           for (int c = 0; c < 4; ++c) {
             if (f[c]) {
-              if (pos < (uint32_t)kSlot) slot[pos] = make_uint2((uint32_t)(idx0 + e + c), a[j][c]);
+              if (pos < (uint32_t)nslot) slot[pos] = make_uint2((uint32_t)(idx0 + e + c), a[j][c]);
               ++pos;
             }
           }
@@ -576,7 +576,7 @@ __global__ __launch_bounds__(256) void k_stream(const TileDesc* __restrict__ til
 __global__ __launch_bounds__(1024) void k_cscan(const SegDesc* __restrict__ segs,
                                                 const LargeSeg* __restrict__ lsegs,
                                                 LState* __restrict__ lstate,
-                                                const uint32_t* __restrict__ chunk_cnt,
+                                                const uint32_t* __restrict__ chunk_cnt, int nslot,
                                                 uint32_t* __restrict__ chunk_off,
                                                 uint32_t* __restrict__ counters,
                                                 int32_t* __restrict__ items) {
@@ -595,7 +595,7 @@ __global__ __launch_bounds__(1024) void k_cscan(const SegDesc* __restrict__ segs
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         v[e] = (i0 + e < ls.chunk_end) ? chunk_cnt[i0 + e] : 0u;
-        over |= v[e] > (uint32_t)kSlot;
+        over |= v[e] > (uint32_t)nslot;
         s += v[e];
       }
       uint32_t tot;
@@ -634,7 +634,7 @@ __global__ __launch_bounds__(256) void k_cgather(int n_chunks, const int32_t* __
                                                  const LState* __restrict__ lstate,
                                                  const uint32_t* __restrict__ chunk_cnt,
                                                  const uint32_t* __restrict__ chunk_off,
-                                                 const uint2* __restrict__ slots,
+                                                 const uint2* __restrict__ slots, int nslot,
                                                  uint2* __restrict__ cand) {
   const int lane = lane_id();
   const int c0 = (int)((blockIdx.x * 256u + threadIdx.x) >> 6) * 64;  // first tile of the wave
@@ -668,7 +668,7 @@ __global__ __launch_bounds__(256) void k_cgather(int n_chunks, const int32_t* __
     if (live) {
       const uint32_t q = e - p0;
       const int64_t d = (int64_t)(((uint64_t)d_hi << 32) | d_lo) + q;
-      cand[d] = slots[(int64_t)(c0 + lo) * kSlot + q];
+      cand[d] = slots[(int64_t)(c0 + lo) * nslot + q];
     }
   }
 }
@@ -1236,17 +1236,17 @@ hipError_t launch_large(const LargePlan& pl, const Scratch& sc, const SegDesc* s
   {
     ProfScope ps(prof, K_STREAM, s);
     hipLaunchKernelGGL(k_stream, dim3(pl.n_tiles), dim3(256), 0, s, pl.tiles, grad, res, lr, sc.lstate,
-                       sc.chunk_cnt, sc.slots, sc.ghist);
+                       sc.chunk_cnt, sc.slots, pl.slot, sc.ghist);
   }
   {
     ProfScope ps(prof, K_CSCAN, s);
     hipLaunchKernelGGL(k_cscan, dim3(pl.n_large), dim3(1024), 0, s, segs, pl.lsegs, sc.lstate, sc.chunk_cnt,
-                       sc.chunk_off, sc.counters, sc.items);
+                       pl.slot, sc.chunk_off, sc.counters, sc.items);
   }
   if (pl.n_chunks > 0) {
     ProfScope ps(prof, K_CGATHER, s);
     hipLaunchKernelGGL(k_cgather, dim3((pl.n_chunks + 255) / 256), dim3(256), 0, s, pl.n_chunks, pl.chunk_lseg,
-                       pl.lsegs, sc.lstate, sc.chunk_cnt, sc.chunk_off, sc.slots, sc.cand);
+                       pl.lsegs, sc.lstate, sc.chunk_cnt, sc.chunk_off, sc.slots, pl.slot, sc.cand);
   }
   const float* ng = nullptr;
   if (pl.n_cand_small[0] > 0) {

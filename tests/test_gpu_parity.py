@@ -216,7 +216,7 @@ def test_sampled_route_is_taken_and_exact(gpu, oracle):
     (route 1) with short and with multi-tile candidate lists; results equal the oracle."""
     rng = np.random.default_rng(51)
     sizes = [(1 << 20, 0.001), (3_000_017, 0.01), (70_001, 0.001), (500_000, 0.02), (41_000, 0.005),
-             (2_500_000, 0.0004)]
+             (2_500_000, 0.0004), (600_000, 0.1), (90_000, 0.18)]
     layers, off = [], 0
     for d, rho in sizes:
         layers.append((off, d, rho))
@@ -282,6 +282,51 @@ def test_mixed_routes_in_one_table(gpu, oracle):
         assert routes[0] == 0 and routes[4] == 0 and routes[1] == 1 and routes[5] == 1 and routes[2] == 3
         assert routes[3] == 2
     table.destroy()
+
+
+def test_random_tables(gpu, oracle):
+    """Seeded random tables: layer sizes across all routes, densities from 1e-4 to 1, arbitrary
+    offsets with gaps, several value distributions, three iterations with error feedback,
+    sparsify + merge + apply against the oracle."""
+    kinds = ["normal", "ties", "mostly_zero", "narrow", "denormal", "zeros"]
+    for case in range(12):
+        rng = np.random.default_rng(1000 + case)
+        n = int(rng.integers(1, 9))
+        layers, off = [], int(rng.integers(0, 5))
+        for _ in range(n):
+            d = int(rng.choice([rng.integers(1, 50), rng.integers(50, 9000), rng.integers(9000, 45000),
+                                rng.integers(45000, 400000)]))
+            rho = float(rng.choice([1e-4, 1e-3, 5e-3, 0.03, 0.15, 0.6, 1.0]))
+            layers.append((off, d, rho))
+            off += d + int(rng.integers(0, 4))
+        total = off + 2
+        P = int(rng.integers(1, 5))
+        table = gpu.ctx.table(layers)
+        K = table.total_k
+        res_g = [np.zeros(total, np.float32) for _ in range(P)]
+        res_c = [np.zeros(total, np.float32) for _ in range(P)]
+        for it in range(3):
+            all_i, all_v = np.empty(P * K, np.int32), np.empty(P * K, np.float32)
+            for p in range(P):
+                g = np.zeros(total, np.float32)
+                for (o, d, _) in layers:
+                    g[o:o + d] = _values(str(rng.choice(kinds)), d, rng)
+                note("random table %d iteration %d worker %d: %r" % (case, it, p, layers))
+                wi, wv = oracle_model_parallel(oracle, layers, g, res_c[p], 0.25)
+                gi, gv, res_g[p] = gpu.sparsify_model(layers, g, res_g[p], 0.25, table=table)
+                assert_same("idx case=%d it=%d p=%d" % (case, it, p), gi, wi)
+                assert_same("val case=%d it=%d p=%d" % (case, it, p), gv, wv)
+                assert_same("res case=%d it=%d p=%d" % (case, it, p), res_g[p], res_c[p])
+                all_i[p * K:(p + 1) * K], all_v[p * K:(p + 1) * K] = gi, gv
+            want_u = np.full(total, 9.0, np.float32)
+            oracle.merge_sparse(layers, all_i, all_v, P, K, want_u)
+            assert_same("update case=%d" % case, gpu.merge(layers, all_i, all_v, P, K, total, table=table, fill=9.0),
+                        want_u)
+            param = rng.standard_normal(total).astype(np.float32)
+            want_v = param.copy()
+            oracle.apply_sparse(layers, all_i, all_v, P, K, want_v)
+            assert_same("param case=%d" % case, gpu.apply(layers, all_i, all_v, P, K, param, table=table), want_v)
+        table.destroy()
 
 
 def test_merge_closed_forms(gpu, oracle):
