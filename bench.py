@@ -163,6 +163,12 @@ def main():
     prof2 = ctx.lags_profile_read()
     ctx.lags_profile_reset()
     delta_host = delta.cpu().numpy().reshape(-1, 3)
+    ctx.lags_sparsify_model(table_b, grad, res, wl.lr, idx, val, stream)
+    routes = ctx.lags_last_routes(table_b)
+    route_names = {0: "one_workgroup", 1: "sampled_single_pass", 2: "sampled_fell_back", 3: "multi_pass"}
+    route_elems = {}
+    for (off, d, r), code in zip(batched, routes):
+        route_elems[route_names[code]] = route_elems.get(route_names[code], 0) + d
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     elements = P * total
@@ -205,6 +211,7 @@ def main():
                                                            (sparsify_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
                             if sparsify_ms > 0 else None},
         "kernels": kernels,
+        "elements_by_route": route_elems,
         "roofline": roofline,
         "next_rows": {
             "sparse_apply_ms": round((prof2["k_merge<apply>"][0] + prof2["k_merge_bounds"][0] / 2) / reps, 4),

@@ -285,8 +285,10 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
   pl.n_sampled = (int)sampled.size();
   pl.n_chunks = (int)chunk_lseg.size();
   pl.n_ctiles = (int)ctiles.size();
+  // candidates cluster (e.g. the few non-zero rows of an embedding gradient), so a tile may
+  // hold several times the layer's average: the slots leave a factor 8 where they can
   pl.slot = kSlotMin;
-  while ((double)pl.slot < 2.0 * max_per_tile && pl.slot < kSlotMax) pl.slot *= 2;
+  while ((double)pl.slot < 8.0 * max_per_tile && pl.slot < kSlotMax) pl.slot *= 2;
   for (int c = 0; c < 3; ++c) pl.n_cand_small[c] = (int)cand_small[c].size();
 
   int rc = upload(&t->d_segs, t->segs);

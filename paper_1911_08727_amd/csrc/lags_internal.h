@@ -31,7 +31,7 @@ constexpr int kSamplePiece = 64;
 constexpr int kSamplePieces = 256;
 constexpr int kSampleMax = kSamplePiece * kSamplePieces;   // 16384 sampled elements
 constexpr int kSlotMin = 256;            // candidate slots per tile of a sampled layer: the table uses the
-constexpr int kSlotMax = 2048;           // smallest power of two >= twice the expected count of any layer
+constexpr int kSlotMax = 2048;           // smallest power of two >= 8x the expected count of any layer
 constexpr int kDenseGrid = 2048;         // workgroups of the fallback kernels (grid-stride)
 
 constexpr int kMergeTile = 8192;
