@@ -154,6 +154,10 @@ bool plan_sample(int64_t d, int64_t k, LargeSeg* ls, double* per_tile) {
   const double expect = jd / m * (double)d;
   const int64_t cap = std::min<int64_t>(d, (int64_t)(2.0 * expect) + 8192);
   ls->sample_rank = (int32_t)jd;
+  // the sample's best estimate of the k-th largest key: entries above it are zeroed in the
+  // streaming pass, the final pass fixes the difference (about k / sqrt(fk) entries either way)
+  // (not worth a second selection over the sample where k is small)
+  ls->sample_rank_hi = k >= 8192 ? (int32_t)std::floor(fk) : 0;
   ls->sample_pieces = (int32_t)pieces;
   ls->sample_stride = (int32_t)stride;
   ls->cap = (int32_t)cap;

@@ -73,7 +73,8 @@ struct LargeSeg {       // static plan of one large layer
   int32_t cap;          // capacity of the candidate list
   int32_t ctile_begin;  // candidate tiles (CAND_LARGE) [ctile_begin, ctile_end)
   int32_t ctile_end;
-  int32_t sample_rank;  // rank (1-based, from the top) of the sample key used as threshold
+  int32_t sample_rank;  // rank (1-based, from the top) of the sample key used as threshold tau
+  int32_t sample_rank_hi;  // rank of the sample key used as tau_hi (0: none): about k's share of the sample
   int32_t sample_pieces;
   int32_t sample_stride;
 };
@@ -82,11 +83,12 @@ enum : uint32_t { MODE_DENSE = 0, MODE_SPARSE = 1 };
 
 struct LState {         // per call, per large layer
   uint32_t tau;         // candidates are the entries with key >= tau
+  uint32_t tau_hi;      // candidates with key >= tau_hi had their residual zeroed by the streaming pass
   uint32_t ncand;       // number of candidates found
   uint32_t mode;        // MODE_SPARSE: the candidate list holds the top k; MODE_DENSE: fall back
   uint32_t prefix;      // radix select: key bits decided so far
   uint32_t k_rem;       // entries still to take among keys matching the prefix
-  uint32_t pad[3];
+  uint32_t pad[2];
 };
 
 struct LargePlan {      // everything launch_large needs (device pointers + counts)

@@ -251,14 +251,16 @@ enum { EMIT_FULL = 0, EMIT_ZERO = 1, EMIT_CAND = 2 };
 //            zeroed).  r = the chunk's residual.
 // EMIT_ZERO: the residual already holds acc; only the kept entries are zeroed.  r = the
 //            chunk's residual.
-// EMIT_CAND: the chunk is part of a candidate list cw ((index, bits) pairs); the kept
-//            entries' residual slots r[index] are zeroed.  r = the layer's residual.
+// EMIT_CAND: the chunk is part of a candidate list cw ((index, bits) pairs).  The streaming
+//            pass already wrote zero for the entries with key >= tau_hi and acc for the others,
+//            so r[index] is written only where that differs from the outcome: zero for kept
+//            entries below tau_hi, acc for dropped entries at or above it.  r = the layer's residual.
 template <int V, int MODE>
 __device__ __forceinline__ void wave_emit(uint32_t (&a)[V][4], int n_w, int lane, uint32_t T,
                                           uint32_t rtake, uint32_t gt_before, uint32_t eq_before,
                                           uint32_t k, int32_t idx_base, int32_t* __restrict__ oi,
                                           float* __restrict__ ov, float* __restrict__ r, bool vec,
-                                          const uint2* __restrict__ cw) {
+                                          const uint2* __restrict__ cw, uint32_t tau_hi) {
 #pragma unroll
   for (int j = 0; j < V; ++j) {
     if (j * 256 >= n_w) break;  // wave-uniform
@@ -284,16 +286,21 @@ __device__ __forceinline__ void wave_emit(uint32_t (&a)[V][4], int n_w, int lane
     for (int c = 0; c < 4; ++c) {
       const bool sel = fg[c] || (fe[c] && eb < rtake);
       const uint32_t pos = gb + (eb < rtake ? eb : rtake);
-      if (sel && pos < k) {  // pos < k always holds; the check keeps a wrong T from writing out of bounds
-        ov[pos] = __uint_as_float(a[j][c]);
-        if (MODE == EMIT_CAND) {
+      if (MODE == EMIT_CAND) {
+        const bool zeroed = (a[j][c] & 0x7FFFFFFFu) >= tau_hi;  // what the streaming pass assumed
+        if (e + c < n_w && (sel || zeroed)) {
           const int32_t index = (int32_t)cw[e + c].x;
-          oi[pos] = index;
-          r[index] = 0.0f;
-        } else {
-          oi[pos] = idx_base + e + c;
-          if (MODE == EMIT_FULL) a[j][c] = 0u; else r[e + c] = 0.0f;
+          if (sel && pos < k) {  // pos < k always holds; the check keeps a wrong T from writing out of bounds
+            ov[pos] = __uint_as_float(a[j][c]);
+            oi[pos] = index;
+          }
+          if (sel && !zeroed) r[index] = 0.0f;
+          if (!sel && zeroed) r[index] = __uint_as_float(a[j][c]);
         }
+      } else if (sel && pos < k) {
+        ov[pos] = __uint_as_float(a[j][c]);
+        oi[pos] = idx_base + e + c;
+        if (MODE == EMIT_FULL) a[j][c] = 0u; else r[e + c] = 0.0f;
       }
       gb += fg[c];
       eb += fe[c];
@@ -354,11 +361,13 @@ __global__ __launch_bounds__(NW * 64) void k_small(const SegDesc* __restrict__ s
   SegDesc sd;
   int n;
   const uint2* cw = nullptr;
+  uint32_t tau_hi = 0xFFFFFFFFu;
   if (CAND) {
     const int li = list[blockIdx.x];
     const LargeSeg ls = lsegs[li];
     const LState st = lstate[li];
     if (st.mode != MODE_SPARSE) return;  // uniform over the workgroup
+    tau_hi = st.tau_hi;
     sd = segs[ls.seg];
     n = (int)st.ncand;
     cw = cand + ls.cand_base + (int64_t)w * CH;
@@ -392,16 +401,17 @@ __global__ __launch_bounds__(NW * 64) void k_small(const SegDesc* __restrict__ s
   for (int i = 0; i < w; ++i) { gb += s_wg[i]; eb += s_we[i]; }
   if (CAND)
     wave_emit<V, EMIT_CAND>(a, n_w, lane, T, rtake, gb, eb, (uint32_t)sd.k, 0, out_idx + sd.out_offset,
-                            out_val + sd.out_offset, res + sd.offset, false, cw);
+                            out_val + sd.out_offset, res + sd.offset, false, cw, tau_hi);
   else
     wave_emit<V, EMIT_FULL>(a, n_w, lane, T, rtake, gb, eb, (uint32_t)sd.k, w * CH, out_idx + sd.out_offset,
-                            out_val + sd.out_offset, r, vec, nullptr);
+                            out_val + sd.out_offset, r, vec, nullptr, 0u);
 }
 
 // ------------------------------------------------------------------ sample ---
 // Threshold guess for one large layer: form acc on up to 256 pieces of 64 consecutive
 // elements spread over the layer (with a hashed offset inside each stride), and take the
-// sample's `sample_rank`-th largest key as tau.  Missing sample slots count as key 0.
+// sample's `sample_rank`-th largest key as tau and its `sample_rank_hi`-th largest (the
+// sample's estimate of the layer's k-th largest) as tau_hi.  Missing sample slots count as key 0.
 __global__ __launch_bounds__(1024) void k_sample(const SegDesc* __restrict__ segs,
                                                  const int32_t* __restrict__ sampled,
                                                  const LargeSeg* __restrict__ lsegs,
@@ -445,20 +455,38 @@ __global__ __launch_bounds__(1024) void k_sample(const SegDesc* __restrict__ seg
       }
     }
   }
-  uint32_t T, rtake;
+  uint32_t T, rtake, Thi = 0xFFFFFFFFu;
   block_radix_select<NT, V>(a, V * 256, lane, (uint32_t)ls.sample_rank, s_hist, s_wt, s_sel, T, rtake);
-  if (tid == 0) lstate[li].tau = T;
+  if (ls.sample_rank_hi > 0)  // uniform over the workgroup
+    block_radix_select<NT, V>(a, V * 256, lane, (uint32_t)ls.sample_rank_hi, s_hist, s_wt, s_sel, Thi, rtake);
+  if (tid == 0) {
+    lstate[li].tau = T;
+    lstate[li].tau_hi = Thi;  // >= T because sample_rank_hi <= sample_rank
+  }
 }
 
 // ------------------------------------------------------------------ stream ---
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+// Non-temporal store of a wave's full, 16-byte aligned chunk.
+template <int V>
+__device__ __forceinline__ void store_bits_nt(float* __restrict__ r, int lane, const uint32_t (&a)[V][4]) {
+#pragma unroll
+  for (int j = 0; j < V; ++j) {
+    u32x4 o;
+    o.x = a[j][0]; o.y = a[j][1]; o.z = a[j][2]; o.w = a[j][3];
+    __builtin_nontemporal_store(o, reinterpret_cast<u32x4*>(r + j * 256 + lane * 4));
+  }
+}
+
 // The one pass over grad and residual of every large layer: acc = residual + lr*grad is
 // written into the residual buffer (it is the final residual everywhere but at the k kept
 // entries).  Tiles of sampled layers also collect, in index order, the entries with
-// key >= tau into the tile's slots; tiles of the other layers add to the layer's histogram
-// of key bits 30..20.  Both arrays are touched exactly once, so full aligned tiles use
+// key >= tau into the tile's slots, and write zero instead of acc for the collected entries
+// with key >= tau_hi (the sample's estimate of the k-th largest key: most of them are kept, so
+// most kept entries get their zero in this pass instead of a scattered write later); tiles of
+// the other layers add to the layer's histogram of key bits 30..20.  Both arrays are touched exactly once, so full aligned tiles use
 // non-temporal 16-byte loads and stores.
 __global__ __launch_bounds__(256) void k_stream(const TileDesc* __restrict__ tiles,
                                                 const float* __restrict__ grad,
@@ -472,9 +500,10 @@ __global__ __launch_bounds__(256) void k_stream(const TileDesc* __restrict__ til
   const TileDesc td = tiles[blockIdx.x];
   const int tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
   const bool collect = td.ctile >= 0;  // uniform over the workgroup
-  uint32_t tau = 0;
+  uint32_t tau = 0, tau_hi = 0xFFFFFFFFu;
   if (collect) {
     tau = lstate[td.seg].tau;
+    tau_hi = lstate[td.seg].tau_hi;
   } else {
     for (int i = tid; i < kBins0; i += 256) s_hist[i] = 0u;
   }
@@ -483,7 +512,8 @@ __global__ __launch_bounds__(256) void k_stream(const TileDesc* __restrict__ til
   const int n_w = td.n - w * kWaveChunk;
   const bool vec = aligned16(g, r);
   uint32_t a[kTileV][4];
-  if (vec && td.n == kTile) {  // uniform over the workgroup
+  const bool fast = vec && td.n == kTile;  // uniform over the workgroup
+  if (fast) {
     f32x4 gv[kTileV], rv[kTileV];
 #pragma unroll
     for (int j = 0; j < kTileV; ++j) {
@@ -493,18 +523,13 @@ __global__ __launch_bounds__(256) void k_stream(const TileDesc* __restrict__ til
     }
 #pragma unroll
     for (int j = 0; j < kTileV; ++j) {
-      const int e = j * 256 + lane * 4;
       a[j][0] = acc_bits(gv[j].x, rv[j].x, lr);
       a[j][1] = acc_bits(gv[j].y, rv[j].y, lr);
       a[j][2] = acc_bits(gv[j].z, rv[j].z, lr);
       a[j][3] = acc_bits(gv[j].w, rv[j].w, lr);
-      u32x4 o;
-      o.x = a[j][0]; o.y = a[j][1]; o.z = a[j][2]; o.w = a[j][3];
-      __builtin_nontemporal_store(o, reinterpret_cast<u32x4*>(r + e));
     }
   } else {
     load_acc<kTileV>(g, r, n_w, lr, vec, lane, a);
-    store_bits<kTileV>(r, n_w, vec, lane, a);
   }
   if (collect) {
     // candidates of the wave, then its position among the tile's waves
@@ -543,7 +568,13 @@ __global__ __launch_bounds__(256) void k_stream(const TileDesc* __restrict__ til
 #pragma unroll
           for (int c = 0; c < 4; ++c) {
             if (f[c]) {
-              if (pos < (uint32_t)nslot) slot[pos] = make_uint2((uint32_t)(idx0 + e + c), a[j][c]);
+              if (pos < (uint32_t)nslot) {
+                slot[pos] = make_uint2((uint32_t)(idx0 + e + c), a[j][c]);
+                // an entry at or above tau_hi is expected to be kept: its residual is written
+                // as zero right here (its value is safe in the slot); the final pass corrects
+                // the few entries for which that expectation turns out wrong
+                if ((a[j][c] & 0x7FFFFFFFu) >= tau_hi) a[j][c] = 0u;
+              }
               ++pos;
             }
           }
@@ -551,7 +582,11 @@ __global__ __launch_bounds__(256) void k_stream(const TileDesc* __restrict__ til
         }
       }
     }
+    if (fast) store_bits_nt<kTileV>(r, lane, a);
+    else store_bits<kTileV>(r, n_w, vec, lane, a);
   } else {
+    if (fast) store_bits_nt<kTileV>(r, lane, a);
+    else store_bits<kTileV>(r, n_w, vec, lane, a);
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < kTileV; ++j) {
@@ -624,7 +659,8 @@ __global__ __launch_bounds__(1024) void k_cscan(const SegDesc* __restrict__ segs
 }
 
 // Copy the tiles' slots into the layer's contiguous candidate list (index order is kept
-// because tiles are laid out in index order).  A wave takes 64 consecutive tiles; lane l
+// because tiles are laid out in index order); for layers whose guess was rejected, undo the
+// streaming pass's early zeros instead.  A wave takes 64 consecutive tiles; lane l
 // learns tile l's count and destination, then the wave copies all their entries 64 at a
 // time: for the e-th entry the owning tile is found by a binary search over the lanes'
 // exclusive counts (shuffles), so neighbouring lanes read neighbouring slots of one tile
@@ -635,7 +671,9 @@ __global__ __launch_bounds__(256) void k_cgather(int n_chunks, const int32_t* __
                                                  const uint32_t* __restrict__ chunk_cnt,
                                                  const uint32_t* __restrict__ chunk_off,
                                                  const uint2* __restrict__ slots, int nslot,
-                                                 uint2* __restrict__ cand) {
+                                                 uint2* __restrict__ cand,
+                                                 const SegDesc* __restrict__ segs,
+                                                 float* __restrict__ res) {
   const int lane = lane_id();
   const int c0 = (int)((blockIdx.x * 256u + threadIdx.x) >> 6) * 64;  // first tile of the wave
   if (c0 >= n_chunks) return;  // wave-uniform
@@ -644,9 +682,21 @@ __global__ __launch_bounds__(256) void k_cgather(int n_chunks, const int32_t* __
   int64_t dst = 0;
   if (c < n_chunks) {
     const int li = chunk_lseg[c];
-    if (lstate[li].mode == MODE_SPARSE) {
+    const LState st = lstate[li];
+    if (st.mode == MODE_SPARSE) {
       cnt = chunk_cnt[c];
       dst = lsegs[li].cand_base + chunk_off[c];
+    } else {
+      // the layer falls back to the multi-pass route, which reads acc from the residual
+      // buffer: give the entries that the streaming pass zeroed (slotted, key >= tau_hi)
+      // their acc back.  Rare path, one lane per tile.
+      const uint32_t stored = chunk_cnt[c] < (uint32_t)nslot ? chunk_cnt[c] : (uint32_t)nslot;
+      float* rl = res + segs[lsegs[li].seg].offset;
+      const uint2* src = slots + (int64_t)c * nslot;
+      for (uint32_t q = 0; q < stored; ++q) {
+        const uint2 en = src[q];
+        if ((en.y & 0x7FFFFFFFu) >= st.tau_hi) rl[en.x] = __uint_as_float(en.y);
+      }
     }
   }
   const uint32_t incl = wave_incl_scan(cnt, lane);
@@ -914,15 +964,18 @@ __global__ __launch_bounds__(256) void k_emit(const TileDesc* __restrict__ tiles
     __syncthreads();
     uint32_t gb = tg, eb = te;
     for (int i = 0; i < w; ++i) { gb += s_g[i]; eb += s_e[i]; }
-    // nothing to emit in this wave if it holds no key above T and its ties come too late
-    if (cg == 0 && (ce == 0 || eb >= rtake)) continue;
     if (CAND) {
+      // every wave runs: entries zeroed by the streaming pass but not kept must get acc back
       wave_emit<kTileV, EMIT_CAND>(a, n_w, lane, T, rtake, gb, eb, (uint32_t)sd.k, 0, out_idx + sd.out_offset,
-                                   out_val + sd.out_offset, res + sd.offset, false, tw.cand + w * kWaveChunk);
+                                   out_val + sd.out_offset, res + sd.offset, false, tw.cand + w * kWaveChunk,
+                                   st.tau_hi);
     } else {
+      // nothing to emit in this wave if it holds no key above T and its ties come too late
+      if (cg == 0 && (ce == 0 || eb >= rtake)) continue;
       float* r = tw.res + w * kWaveChunk;
       wave_emit<kTileV, EMIT_ZERO>(a, n_w, lane, T, rtake, gb, eb, (uint32_t)sd.k, tw.local0 + w * kWaveChunk,
-                                   out_idx + sd.out_offset, out_val + sd.out_offset, r, aligned16(r, r), nullptr);
+                                   out_idx + sd.out_offset, out_val + sd.out_offset, r, aligned16(r, r), nullptr,
+                                   0u);
     }
   }
 }
@@ -1246,7 +1299,7 @@ hipError_t launch_large(const LargePlan& pl, const Scratch& sc, const SegDesc* s
   if (pl.n_chunks > 0) {
     ProfScope ps(prof, K_CGATHER, s);
     hipLaunchKernelGGL(k_cgather, dim3((pl.n_chunks + 255) / 256), dim3(256), 0, s, pl.n_chunks, pl.chunk_lseg,
-                       pl.lsegs, sc.lstate, sc.chunk_cnt, sc.chunk_off, sc.slots, pl.slot, sc.cand);
+                       pl.lsegs, sc.lstate, sc.chunk_cnt, sc.chunk_off, sc.slots, pl.slot, sc.cand, segs, res);
   }
   const float* ng = nullptr;
   if (pl.n_cand_small[0] > 0) {

@@ -258,6 +258,23 @@ def test_sampled_route_rejections_fall_back(gpu, oracle):
     assert _check_table(gpu, oracle, [(0, d, 0.5)], g, np.zeros(d, np.float32), 1.0) == [3]
 
 
+def test_fallback_after_early_zeros(gpu, oracle):
+    """A large layer with k >= 8192 (so the streaming pass zeroes the entries it expects to be
+    kept) whose candidates overflow the slots of a few tiles: the layer falls back to the
+    multi-pass route, which must first see every early zero undone."""
+    rng = np.random.default_rng(54)
+    d, rho = 2_000_000, 0.01
+    g = rng.standard_normal(d).astype(np.float32)
+    g[100_000:110_000] *= 100.0                      # 10000 huge entries in three tiles
+    r0 = (0.1 * rng.standard_normal(d)).astype(np.float32)
+    note("fallback after early zeros")
+    routes = _check_table(gpu, oracle, [(0, d, rho)], g, r0, 1.0)
+    assert routes == [2], routes
+    # and the same layer without the cluster stays on the single-pass route
+    g2 = rng.standard_normal(d).astype(np.float32)
+    assert _check_table(gpu, oracle, [(0, d, rho)], g2, r0, 1.0) == [1]
+
+
 def test_mixed_routes_in_one_table(gpu, oracle):
     """One table whose layers take all four routes at once, over several iterations."""
     rng = np.random.default_rng(53)
