@@ -17,7 +17,9 @@
  *     pointers owned by the caller; the library neither frees nor keeps them.
  *     Everything else (descriptors, handles, out-parameters) is host memory.
  *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL = the
- *     default stream) and the call returns without waiting for it.
+ *     default stream) and the call returns without waiting for it.  A call may also use a
+ *     side stream of the context; that work is ordered after everything enqueued on
+ *     `hip_stream` before the call and before everything enqueued on it after the call.
  *   - Argument validation happens before anything is enqueued: on an error return
  *     no output buffer has been touched.
  *   - A context owns scratch memory only (histograms, counters, candidate lists);

@@ -41,6 +41,10 @@ struct lags_ctx {
   DevBuf partials; // delta metric: two doubles per merge tile
   std::map<std::pair<int64_t, int64_t>, lags_table*> layer_tables;  // (d, k) -> one-layer table
   Prof prof;
+  // side stream (default priority) on which the small layers' kernels run beside the large
+  // layers' pipeline; forked from and joined to the caller's stream with events in every call
+  hipStream_t aux = nullptr;
+  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
   Scratch scratch() const {
     Scratch sc;
     sc.counters = static_cast<uint32_t*>(counters.p);
@@ -152,7 +156,7 @@ bool plan_sample(int64_t d, int64_t k, LargeSeg* ls, double* per_tile) {
   *per_tile = jd / m * (double)kTile;
   if (*per_tile > (double)kSlotMax * 0.5) return false;
   const double expect = jd / m * (double)d;
-  const int64_t cap = std::min<int64_t>(d, (int64_t)(2.0 * expect) + 8192);
+  const int64_t cap = std::min<int64_t>(d, (int64_t)(2.0 * expect) + 1024);
   ls->sample_rank = (int32_t)jd;
   // the sample's best estimate of the k-th largest key: entries above it are zeroed in the
   // streaming pass, the final pass fixes the difference (about k / sqrt(fk) entries either way)
@@ -339,13 +343,26 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
 
 int run_sparsify(lags_ctx* ctx, const lags_table* t, const float* grad, float* res, float lr,
                  int32_t* out_idx, float* out_val, hipStream_t s) {
-  for (int c = 0; c < 3; ++c) {
-    if (launch_small(c, t->n_small[c], t->d_segs, t->d_small[c], grad, res, lr, out_idx, out_val, s, &ctx->prof) != hipSuccess)
-      return LAGS_EHIP;
+  // small and large layers touch disjoint parts of every buffer, so the small layers' kernels
+  // can run on the side stream while the large layers' pipeline occupies the caller's stream
+  const bool have_small = t->n_small[0] + t->n_small[1] + t->n_small[2] > 0;
+  bool fork = ctx->aux && have_small && t->plan.n_large > 0;
+  if (fork && (hipEventRecord(ctx->ev_fork, s) != hipSuccess ||
+               hipStreamWaitEvent(ctx->aux, ctx->ev_fork, 0) != hipSuccess))
+    fork = false;
+  hipStream_t ss = fork ? ctx->aux : s;
+  int rc = LAGS_OK;
+  for (int c = 0; c < 3 && rc == LAGS_OK; ++c) {
+    if (launch_small(c, t->n_small[c], t->d_segs, t->d_small[c], grad, res, lr, out_idx, out_val, ss, &ctx->prof) != hipSuccess)
+      rc = LAGS_EHIP;
   }
-  if (launch_large(t->plan, ctx->scratch(), t->d_segs, grad, res, lr, out_idx, out_val, s, &ctx->prof) != hipSuccess)
-    return LAGS_EHIP;
-  return LAGS_OK;
+  if (fork && hipEventRecord(ctx->ev_join, ctx->aux) != hipSuccess) rc = LAGS_EHIP;
+  if (rc == LAGS_OK &&
+      launch_large(t->plan, ctx->scratch(), t->d_segs, grad, res, lr, out_idx, out_val, s, &ctx->prof) != hipSuccess)
+    rc = LAGS_EHIP;
+  // always join what was forked, also on an error path, so the caller's stream stays ordered
+  if (fork && hipStreamWaitEvent(s, ctx->ev_join, 0) != hipSuccess) rc = LAGS_EHIP;
+  return rc;
 }
 
 }  // namespace
@@ -369,6 +386,21 @@ int lags_create(lags_ctx** out, int device) {
   lags_ctx* c = new (std::nothrow) lags_ctx();
   if (!c) return LAGS_ENOMEM;
   c->device = device;
+  {
+    DeviceGuard g(device);
+    if (g.ok && hipStreamCreateWithFlags(&c->aux, hipStreamNonBlocking) == hipSuccess) {
+      if (hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) != hipSuccess ||
+          hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming) != hipSuccess) {
+        if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
+        if (c->ev_join) (void)hipEventDestroy(c->ev_join);
+        (void)hipStreamDestroy(c->aux);
+        c->aux = nullptr;   // everything then runs on the caller's stream
+        c->ev_fork = c->ev_join = nullptr;
+      }
+    } else {
+      c->aux = nullptr;
+    }
+  }
   *out = c;
   return LAGS_OK;
 }
@@ -377,6 +409,12 @@ int lags_destroy(lags_ctx* ctx) {
   if (!ctx) return LAGS_EINVAL;
   DeviceGuard g(ctx->device);
   (void)lags_profile_reset(ctx);
+  if (ctx->aux) {
+    (void)hipStreamSynchronize(ctx->aux);
+    (void)hipStreamDestroy(ctx->aux);
+    (void)hipEventDestroy(ctx->ev_fork);
+    (void)hipEventDestroy(ctx->ev_join);
+  }
   for (auto& kv : ctx->layer_tables) {
     free_table_device(kv.second);
     delete kv.second;
