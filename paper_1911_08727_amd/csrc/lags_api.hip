@@ -193,6 +193,15 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
     int64_t outpos = 0;
     t->span_lo = off[0];
     t->span_hi = off[0] + d[0];
+    // If some layer's candidate list needs the multi-block selection, those launches happen
+    // anyway: then every sampled layer uses them and the one-workgroup launches are saved.
+    bool any_cand_large = false;
+    for (int32_t l = 0; l < n && !any_cand_large; ++l) {
+      LargeSeg probe = {};
+      double per_tile = 0.0;
+      if (d[l] > kSmall2 && plan_sample(d[l], k[l], &probe, &per_tile) && probe.cand_class == CAND_LARGE)
+        any_cand_large = true;
+    }
     for (int32_t l = 0; l < n; ++l) {
       SegDesc& s = t->segs[l];
       s.offset = off[l];
@@ -213,6 +222,7 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
         double per_tile = 0.0;
         const bool sampled_layer = plan_sample(d[l], k[l], &ls, &per_tile);
         if (sampled_layer) max_per_tile = std::max(max_per_tile, per_tile);
+        if (sampled_layer && any_cand_large) ls.cand_class = CAND_LARGE;
         ls.tile_begin = (int32_t)tiles.size();
         const int64_t nt = (d[l] + kTile - 1) / kTile;
         if ((int64_t)tiles.size() + nt > kMaxTiles) { delete t; return LAGS_ECAPACITY; }
