@@ -1119,28 +1119,37 @@ __global__ __launch_bounds__(256) void k_merge(const TileDesc* __restrict__ mtil
   const int slot = (int)blockIdx.x + td.seg;  // every earlier layer owns one extra (end) slot
   const uint32_t entries =
       merge_accumulate<float>(s_acc, s_start, s_lo, s_wt, td, sd, slot, idx, val, P, stride_k, nb, bounds);
+  // sum / P: for P a power of two the product with 1/P is the same binary32 value as the
+  // quotient (an exact scaling, rounded identically when the result is subnormal), and it is
+  // much cheaper than a correctly rounded division
   const float fp = (float)P;
+  const bool pow2 = (P & (P - 1)) == 0;
+  const float inv = 1.0f / fp;
   float* u = out + td.start;
   if (APPLY) {
     if (entries == 0) return;  // uniform over the workgroup
     for (int e = tid; e < td.n; e += 256) {
       const float sacc = s_acc[e];
-      if (sacc != 0.0f) u[e] = __fsub_rn(u[e], __fdiv_rn(sacc, fp));
+      if (sacc != 0.0f) u[e] = __fsub_rn(u[e], pow2 ? __fmul_rn(sacc, inv) : __fdiv_rn(sacc, fp));
     }
     return;
   }
   const bool vec = aligned16(u, u);
   for (int e = tid * 4; e < td.n; e += 1024) {
     if (vec && e + 3 < td.n) {
+      const float4 sv = *reinterpret_cast<const float4*>(&s_acc[e]);
       float4 v;
-      v.x = __fdiv_rn(s_acc[e + 0], fp);
-      v.y = __fdiv_rn(s_acc[e + 1], fp);
-      v.z = __fdiv_rn(s_acc[e + 2], fp);
-      v.w = __fdiv_rn(s_acc[e + 3], fp);
+      if (pow2) {
+        v.x = __fmul_rn(sv.x, inv); v.y = __fmul_rn(sv.y, inv);
+        v.z = __fmul_rn(sv.z, inv); v.w = __fmul_rn(sv.w, inv);
+      } else {
+        v.x = __fdiv_rn(sv.x, fp); v.y = __fdiv_rn(sv.y, fp);
+        v.z = __fdiv_rn(sv.z, fp); v.w = __fdiv_rn(sv.w, fp);
+      }
       *reinterpret_cast<float4*>(u + e) = v;
     } else {
       for (int c = 0; c < 4; ++c)
-        if (e + c < td.n) u[e + c] = __fdiv_rn(s_acc[e + c], fp);
+        if (e + c < td.n) u[e + c] = pow2 ? __fmul_rn(s_acc[e + c], inv) : __fdiv_rn(s_acc[e + c], fp);
     }
   }
 }

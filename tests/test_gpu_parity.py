@@ -379,6 +379,26 @@ def test_merge_closed_forms(gpu, oracle):
                            oracle.delta_monitor(layers, res, total, idx, val, P, K))
 
 
+def test_merge_subnormal_results(gpu, oracle):
+    """Sums whose quotient by P is subnormal or rounds at the last subnormal bit, for worker
+    counts that are powers of two (scaled by 1/P in the kernel) and that are not."""
+    rng = np.random.default_rng(63)
+    layers = [(0, 5000, 0.01)]
+    K = oracle.total_k(layers)
+    for P in (2, 3, 4, 16, 24, 64):
+        idx = np.tile(np.sort(rng.choice(5000, K, replace=False)).astype(np.int32), P)
+        val = (rng.integers(-40, 41, P * K).astype(np.float64) * 2.0 ** -149).astype(np.float32)
+        val[::7] = np.float32(1.1754944e-38) * rng.standard_normal(len(val[::7])).astype(np.float32)
+        note("merge subnormal P=%d" % P)
+        want = np.empty(5000, np.float32)
+        oracle.merge_sparse(layers, idx, val, P, K, want)
+        assert_same("update P=%d" % P, gpu.merge(layers, idx, val, P, K, 5000), want)
+        param = (rng.integers(-5, 6, 5000).astype(np.float64) * 2.0 ** -149).astype(np.float32)
+        want_v = param.copy()
+        oracle.apply_sparse(layers, idx, val, P, K, want_v)
+        assert_same("param P=%d" % P, gpu.apply(layers, idx, val, P, K, param), want_v)
+
+
 def test_apply_and_delta_edge_layers(gpu, oracle):
     """Layers of one element, k == d (delta is NaN), gaps and unaligned offsets, a padded pair
     stride and a padded worker stride; parameters outside the layers keep their bits."""
