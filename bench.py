@@ -66,6 +66,8 @@ def main():
     ap.add_argument("--workload", default="vgg16", help="single|resnet20|vgg16|resnet50|lstm")
     ap.add_argument("--rho", default="0.001", help="density for every layer, or 'config' for the workload's own")
     ap.add_argument("--workers", type=int, default=0, help="simulated workers P (0 = the workload's)")
+    ap.add_argument("--per-worker", action="store_true",
+                    help="one lags_sparsify_model call per worker (L layers each) instead of one batched call")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain device copy of 1 GiB (for scaling rocprofv3 byte counters)")
@@ -115,7 +117,12 @@ def main():
     stream = torch.cuda.current_stream()
 
     def step():
-        ctx.lags_sparsify_model(table_b, grad, res, wl.lr, idx, val, stream)
+        if args.per_worker:
+            for p in range(P):
+                ctx.lags_sparsify_model(table_1, grad[p * total:(p + 1) * total], res[p * total:(p + 1) * total],
+                                        wl.lr, idx[p * K:(p + 1) * K], val[p * K:(p + 1) * K], stream)
+        else:
+            ctx.lags_sparsify_model(table_b, grad, res, wl.lr, idx, val, stream)
         ctx.lags_merge_sparse(table_1, idx, val, P, K, upd, stream)
 
     for _ in range(args.warmup):
@@ -176,20 +183,24 @@ def main():
 
     # dominant kernel = largest total time; its algorithmic bytes per launch
     rho_mean = float(K) / float(total)
-    kel = dict(table_b.kernel_elements())
+    kel = dict((table_1 if args.per_worker else table_b).kernel_elements())
     kel.update({k: v for k, v in table_1.kernel_elements().items() if k == "k_merge"})
-    dom_ms = prof[dom][0] / prof[dom][1]
+    dom_ms = prof[dom][0] / prof[dom][1]                 # average duration of one launch
     launches_per_step = prof[dom][1] / args.steps
+    dom_ms_per_step = prof[dom][0] / args.steps
     if dom == "k_merge":
         bpe = 4.0 + 8.0 * P * rho_mean
     else:
         bpe = 12.0 + 8.0 * rho_mean
-    # a kernel launched several times per step (e.g. k_hist) shares the per-step algorithmic bytes
-    achieved = bpe * kel.get(dom, elements) / (dom_ms * 1e-3) / 1e9
+    # algorithmic bytes of the elements the kernel covers in one step / its time in one step
+    # (= bytes per launch / average launch duration when every launch covers an equal share)
+    achieved = bpe * kel.get(dom, elements) / (dom_ms_per_step * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(dom, wl.name, P),
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": (lambda t: None if t is None else t / launches_per_step)(measured_traffic(dom, wl.name, P)),
                 "avg_kernel_ms": round(dom_ms, 4), "launches_per_step": launches_per_step,
-                "bytes_per_element": round(bpe, 4), "elements_per_launch": kel.get(dom, elements)}
+                "bytes_per_element": round(bpe, 4),
+                "elements_per_launch": kel.get(dom, elements) / launches_per_step}
     kernels = {k: {"ms_per_step": round(v[0] / n_table, 4), "launches_per_step": v[1] / n_table}
                for k, v in sorted(prof_all.items(), key=lambda kv: -kv[1][0])}
     merge_names = ("k_merge", "k_merge_bounds")
@@ -202,6 +213,8 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": wl.name, "layers": len(layers), "elements_per_worker": total, "workers": P,
+                   "calls_per_step": "one sparsify call per worker + merge" if args.per_worker
+                   else "one batched sparsify call (P x L layers) + merge",
                    "sum_k_per_worker": K, "lr": wl.lr, "distribution": wl.dist},
         "algorithmic_gbs": {"sparsify": round((12.0 + 8.0 * rho_mean) * elements / (sparsify_ms * 1e-3) / 1e9, 1)
                             if sparsify_ms > 0 else None,

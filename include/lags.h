@@ -143,7 +143,9 @@ int lags_last_routes(lags_ctx *ctx, const lags_table *t, int32_t *route, int32_t
 
 /* Optional per-kernel timing with HIP events recorded on the caller's stream (measurement
  * aid; off by default; no effect on results).  While enabled every kernel launch of this
- * context is bracketed by a pair of events.  lags_profile_read waits for all recorded
+ * context is bracketed by a pair of events (a kernel that is enqueued as a back-to-back group
+ * of launches, like the streaming pass, is bracketed as a group and counted with its number
+ * of launches).  lags_profile_read waits for all recorded
  * events, adds the elapsed milliseconds and launch count of kernel `kernel_id`
  * (0 <= kernel_id < lags_profile_num_kernels()) to *total_ms / *launches, and
  * lags_profile_reset drops everything recorded so far.  All three are host-synchronous. */

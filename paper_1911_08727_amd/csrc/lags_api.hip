@@ -634,7 +634,7 @@ int lags_profile_read(lags_ctx* ctx, int kernel_id, double* total_ms, int64_t* l
     float ms = 0.f;
     if (hipEventSynchronize(r.b) != hipSuccess || hipEventElapsedTime(&ms, r.a, r.b) != hipSuccess) return LAGS_EHIP;
     *total_ms += (double)ms;
-    *launches += 1;
+    *launches += r.launches;
   }
   return LAGS_OK;
 }

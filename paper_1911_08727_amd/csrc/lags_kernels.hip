@@ -1296,9 +1296,13 @@ hipError_t launch_large(const LargePlan& pl, const Scratch& sc, const SegDesc* s
                        sc.lstate);
   }
   {
-    ProfScope ps(prof, K_STREAM, s);
-    hipLaunchKernelGGL(k_stream, dim3(pl.n_tiles), dim3(256), 0, s, pl.tiles, grad, res, lr, sc.lstate,
-                       sc.chunk_cnt, sc.slots, pl.slot, sc.ghist);
+    const int nl = (pl.n_tiles + kStreamLaunchTiles - 1) / kStreamLaunchTiles;
+    ProfScope ps(prof, K_STREAM, s, nl);
+    for (int t0 = 0; t0 < pl.n_tiles; t0 += kStreamLaunchTiles) {
+      const int nt = pl.n_tiles - t0 < kStreamLaunchTiles ? pl.n_tiles - t0 : kStreamLaunchTiles;
+      hipLaunchKernelGGL(k_stream, dim3(nt), dim3(256), 0, s, pl.tiles + t0, grad, res, lr, sc.lstate,
+                         sc.chunk_cnt, sc.slots, pl.slot, sc.ghist);
+    }
   }
   {
     ProfScope ps(prof, K_CSCAN, s);
