@@ -37,6 +37,11 @@ constexpr int kDenseGrid = 2048;         // workgroups of the fallback kernels (
 // on MI355X, a 26 GB stream runs 8 % faster as 32-64 launches than as one (the workgroups in
 // flight stay within a narrower address window), and slower again beyond ~128 launches.
 constexpr int kStreamLaunchTiles = 16384;
+// Shape of the streaming workgroup: 4 waves x 4 rounds.  (A bare stream kernel is 2 % faster
+// with 16 waves x 1 round, but with the candidate collection and its barrier that shape
+// measured 6 % slower.)
+constexpr int kStreamWaves = 4;
+constexpr int kStreamV = 4;
 
 constexpr int kMergeTile = 8192;
 constexpr int kMaxWorkers = 1024;

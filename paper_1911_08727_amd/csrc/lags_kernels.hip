@@ -488,7 +488,8 @@ __device__ __forceinline__ void store_bits_nt(float* __restrict__ r, int lane, c
 // most kept entries get their zero in this pass instead of a scattered write later); tiles of
 // the other layers add to the layer's histogram of key bits 30..20.  Both arrays are touched exactly once, so full aligned tiles use
 // non-temporal 16-byte loads and stores.
-__global__ __launch_bounds__(256) void k_stream(const TileDesc* __restrict__ tiles,
+template <int NW, int V>
+__global__ __launch_bounds__(NW * 64) void k_stream(const TileDesc* __restrict__ tiles,
                                                 const float* __restrict__ grad,
                                                 float* __restrict__ res, float lr,
                                                 const LState* __restrict__ lstate,
@@ -496,7 +497,9 @@ __global__ __launch_bounds__(256) void k_stream(const TileDesc* __restrict__ til
                                                 uint2* __restrict__ slots, int nslot,
                                                 uint32_t* __restrict__ ghist) {
   __shared__ uint32_t s_hist[kBins0];
-  __shared__ uint32_t s_cnt[kTileWaves];
+  __shared__ uint32_t s_cnt[NW];
+  static_assert(NW * V * 256 == kTile, "the workgroup covers exactly one tile");
+  constexpr int NT = NW * 64, WC = V * 256;  // threads per workgroup, elements per wave
   const TileDesc td = tiles[blockIdx.x];
   const int tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
   const bool collect = td.ctile >= 0;  // uniform over the workgroup
@@ -505,37 +508,37 @@ __global__ __launch_bounds__(256) void k_stream(const TileDesc* __restrict__ til
     tau = lstate[td.seg].tau;
     tau_hi = lstate[td.seg].tau_hi;
   } else {
-    for (int i = tid; i < kBins0; i += 256) s_hist[i] = 0u;
+    for (int i = tid; i < kBins0; i += NT) s_hist[i] = 0u;
   }
-  const float* g = grad + td.start + w * kWaveChunk;
-  float* r = res + td.start + w * kWaveChunk;
-  const int n_w = td.n - w * kWaveChunk;
+  const float* g = grad + td.start + w * WC;
+  float* r = res + td.start + w * WC;
+  const int n_w = td.n - w * WC;
   const bool vec = aligned16(g, r);
-  uint32_t a[kTileV][4];
+  uint32_t a[V][4];
   const bool fast = vec && td.n == kTile;  // uniform over the workgroup
   if (fast) {
-    f32x4 gv[kTileV], rv[kTileV];
+    f32x4 gv[V], rv[V];
 #pragma unroll
-    for (int j = 0; j < kTileV; ++j) {
+    for (int j = 0; j < V; ++j) {
       const int e = j * 256 + lane * 4;
       gv[j] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(g + e));
       rv[j] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(r + e));
     }
 #pragma unroll
-    for (int j = 0; j < kTileV; ++j) {
+    for (int j = 0; j < V; ++j) {
       a[j][0] = acc_bits(gv[j].x, rv[j].x, lr);
       a[j][1] = acc_bits(gv[j].y, rv[j].y, lr);
       a[j][2] = acc_bits(gv[j].z, rv[j].z, lr);
       a[j][3] = acc_bits(gv[j].w, rv[j].w, lr);
     }
   } else {
-    load_acc<kTileV>(g, r, n_w, lr, vec, lane, a);
+    load_acc<V>(g, r, n_w, lr, vec, lane, a);
   }
   if (collect) {
     // candidates of the wave, then its position among the tile's waves
     uint32_t wtot = 0;
 #pragma unroll
-    for (int j = 0; j < kTileV; ++j) {
+    for (int j = 0; j < V; ++j) {
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
         const int e = j * 256 + lane * 4 + c;
@@ -546,7 +549,7 @@ __global__ __launch_bounds__(256) void k_stream(const TileDesc* __restrict__ til
     __syncthreads();
     uint32_t base = 0, total = 0;
 #pragma unroll
-    for (int i = 0; i < kTileWaves; ++i) {
+    for (int i = 0; i < NW; ++i) {
       const uint32_t t = s_cnt[i];
       if (i < w) base += t;
       total += t;
@@ -554,9 +557,9 @@ __global__ __launch_bounds__(256) void k_stream(const TileDesc* __restrict__ til
     if (tid == 0) chunk_cnt[td.ctile] = total;  // a count above nslot marks the tile as overflowed
     if (wtot) {  // wave-uniform
       uint2* slot = slots + (int64_t)td.ctile * nslot;
-      const int32_t idx0 = td.local0 + w * kWaveChunk;
+      const int32_t idx0 = td.local0 + w * WC;
 #pragma unroll
-      for (int j = 0; j < kTileV; ++j) {
+      for (int j = 0; j < V; ++j) {
         const int e = j * 256 + lane * 4;
         bool f[4];
 #pragma unroll
@@ -582,14 +585,14 @@ __global__ __launch_bounds__(256) void k_stream(const TileDesc* __restrict__ til
         }
       }
     }
-    if (fast) store_bits_nt<kTileV>(r, lane, a);
-    else store_bits<kTileV>(r, n_w, vec, lane, a);
+    if (fast) store_bits_nt<V>(r, lane, a);
+    else store_bits<V>(r, n_w, vec, lane, a);
   } else {
-    if (fast) store_bits_nt<kTileV>(r, lane, a);
-    else store_bits<kTileV>(r, n_w, vec, lane, a);
+    if (fast) store_bits_nt<V>(r, lane, a);
+    else store_bits<V>(r, n_w, vec, lane, a);
     __syncthreads();
 #pragma unroll
-    for (int j = 0; j < kTileV; ++j) {
+    for (int j = 0; j < V; ++j) {
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
         const int e = j * 256 + lane * 4 + c;
@@ -598,7 +601,7 @@ __global__ __launch_bounds__(256) void k_stream(const TileDesc* __restrict__ til
     }
     __syncthreads();
     uint32_t* gh = ghist + (int64_t)td.seg * kHistStride;
-    for (int i = tid; i < kBins0; i += 256) {
+    for (int i = tid; i < kBins0; i += NT) {
       const uint32_t h = s_hist[i];
       if (h) atomicAdd(&gh[i], h);
     }
@@ -1300,8 +1303,8 @@ hipError_t launch_large(const LargePlan& pl, const Scratch& sc, const SegDesc* s
     ProfScope ps(prof, K_STREAM, s, nl);
     for (int t0 = 0; t0 < pl.n_tiles; t0 += kStreamLaunchTiles) {
       const int nt = pl.n_tiles - t0 < kStreamLaunchTiles ? pl.n_tiles - t0 : kStreamLaunchTiles;
-      hipLaunchKernelGGL(k_stream, dim3(nt), dim3(256), 0, s, pl.tiles + t0, grad, res, lr, sc.lstate,
-                         sc.chunk_cnt, sc.slots, pl.slot, sc.ghist);
+      hipLaunchKernelGGL((k_stream<kStreamWaves, kStreamV>), dim3(nt), dim3(kStreamWaves * 64), 0, s, pl.tiles + t0,
+                         grad, res, lr, sc.lstate, sc.chunk_cnt, sc.slots, pl.slot, sc.ghist);
     }
   }
   {
