@@ -148,9 +148,10 @@ bool plan_sample(int64_t d, int64_t k, LargeSeg* ls, double* per_tile) {
   }
   const double m = (double)std::min<int64_t>(d, pieces * kSamplePiece);
   const double fk = (double)k * m / (double)d;
-  // the sample's rank-j key admits about j/m of the layer; j is fk plus six standard
-  // deviations of the sampled count plus a constant, so that fewer than k is very unlikely
-  const double jd = std::ceil(fk + 6.0 * std::sqrt(fk) + 20.0);
+  // the sample's rank-j key admits about j/m of the layer; j is fk plus four standard
+  // deviations of the sampled count plus a constant: fewer than k candidates (which only
+  // costs the fallback for that layer in that call) then has a probability of a few 1e-5
+  const double jd = std::ceil(fk + 4.0 * std::sqrt(fk) + 8.0);
   if (jd > m) return false;
   // expected candidates per tile must stay well inside the largest slot size
   *per_tile = jd / m * (double)kTile;

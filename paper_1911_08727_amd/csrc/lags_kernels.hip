@@ -567,19 +567,18 @@ __global__ __launch_bounds__(NW * 64) void k_stream(const TileDesc* __restrict__
         const uint64_t b0 = __ballot(f[0]), b1 = __ballot(f[1]), b2 = __ballot(f[2]), b3 = __ballot(f[3]);
         const uint32_t tot = (uint32_t)(__popcll(b0) + __popcll(b1) + __popcll(b2) + __popcll(b3));
         if (tot) {  // wave-uniform
+          // slot of the lane's first candidate of this round, then one predicated store and one
+          // select per component (flat code: no nested divergent branches)
           uint32_t pos = base + mbcnt64(b0) + mbcnt64(b1) + mbcnt64(b2) + mbcnt64(b3);
 #pragma unroll
           for (int c = 0; c < 4; ++c) {
-            if (f[c]) {
-              if (pos < (uint32_t)nslot) {
-                slot[pos] = make_uint2((uint32_t)(idx0 + e + c), a[j][c]);
-                // an entry at or above tau_hi is expected to be kept: its residual is written
-                // as zero right here (its value is safe in the slot); the final pass corrects
-                // the few entries for which that expectation turns out wrong
-                if ((a[j][c] & 0x7FFFFFFFu) >= tau_hi) a[j][c] = 0u;
-              }
-              ++pos;
-            }
+            const bool put = f[c] && pos < (uint32_t)nslot;
+            if (put) slot[pos] = make_uint2((uint32_t)(idx0 + e + c), a[j][c]);
+            // an entry at or above tau_hi is expected to be kept: its residual is written as
+            // zero right here (its value is safe in the slot); the final pass corrects the few
+            // entries for which that expectation turns out wrong
+            a[j][c] = (put && (a[j][c] & 0x7FFFFFFFu) >= tau_hi) ? 0u : a[j][c];
+            pos += f[c] ? 1u : 0u;
           }
           base += tot;
         }
