@@ -148,7 +148,11 @@ int lags_last_routes(lags_ctx *ctx, const lags_table *t, int32_t *route, int32_t
  * of launches).  lags_profile_read waits for all recorded
  * events, adds the elapsed milliseconds and launch count of kernel `kernel_id`
  * (0 <= kernel_id < lags_profile_num_kernels()) to *total_ms / *launches, and
- * lags_profile_reset drops everything recorded so far.  All three are host-synchronous. */
+ * lags_profile_reset drops everything recorded so far.  All three are host-synchronous.
+ * The id named "sparsify_call" is not a kernel: it brackets a whole sparsify call on the
+ * caller's stream, from its first enqueue to the join of the side stream.  The small layers'
+ * kernels run on the side stream beside the streaming pass, so the per-kernel times of a call
+ * can add up to more than the call takes. */
 int lags_profile_enable(lags_ctx *ctx, int on);
 /* Like lags_profile_enable(ctx, 1) but only launches of kernel `kernel_id` are bracketed
  * (two events per launch of that kernel instead of two per launch of every kernel). */

@@ -354,6 +354,7 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
 
 int run_sparsify(lags_ctx* ctx, const lags_table* t, const float* grad, float* res, float lr,
                  int32_t* out_idx, float* out_val, hipStream_t s) {
+  ProfScope whole(&ctx->prof, K_SPARSIFY_CALL, s);
   // small and large layers touch disjoint parts of every buffer, so the small layers' kernels
   // can run on the side stream while the large layers' pipeline occupies the caller's stream
   const bool have_small = t->n_small[0] + t->n_small[1] + t->n_small[2] > 0;
@@ -667,7 +668,7 @@ int64_t lags_profile_kernel_elements(const lags_table* t, int kernel_id) {
     case K_SMALL1: return small[1];
     case K_SMALL2: return small[2];
     case K_STREAM: return large;
-    case K_MERGE: case K_MERGE_APPLY: case K_DELTA_TILES: return all;
+    case K_MERGE: case K_MERGE_APPLY: case K_DELTA_TILES: case K_SPARSIFY_CALL: return all;
     default: return 0;
   }
 }

@@ -26,13 +26,14 @@ constexpr int kSmall2 = 16 * 10 * 256;   // <= 40960 : 16 waves, 10 rounds
 
 // Threshold guess from a sample (large layers): 256 pieces of 64 consecutive elements.
 // The sample only has to rank the top k roughly: a smaller sample admits more candidates
-// (about k + 6 sqrt(k d / m) (d / m) ...), which costs 8 bytes each and nothing else.
+// (the threshold sits four standard deviations of the sample count below the top k), which
+// costs 8 bytes each and nothing else.
 constexpr int kSamplePiece = 64;
 constexpr int kSamplePieces = 256;
 constexpr int kSampleMax = kSamplePiece * kSamplePieces;   // 16384 sampled elements
 constexpr int kSlotMin = 256;            // candidate slots per tile of a sampled layer: the table uses the
 constexpr int kSlotMax = 2048;           // smallest power of two >= 8x the expected count of any layer
-constexpr int kDenseGrid = 2048;         // workgroups of the fallback kernels (grid-stride)
+constexpr int kDenseGrid = 1024;         // workgroups of the fallback kernels (grid-stride)
 // The streaming pass is enqueued as back-to-back launches of at most this many tiles: measured
 // on MI355X, a 26 GB stream runs 8 % faster as 32-64 launches than as one (the workgroups in
 // flight stay within a narrower address window), and slower again beyond ~128 launches.
@@ -128,8 +129,9 @@ struct Scratch {        // context-owned device memory, contents meaningless bet
 // Kernel ids for the optional event timing.
 enum KernelId {
   K_ZERO = 0, K_SMALL0, K_SMALL1, K_SMALL2, K_SAMPLE, K_STREAM, K_CSCAN, K_CGATHER,
-  K_CSMALL0, K_CSMALL1, K_CSMALL2, K_HIST_CAND, K_HIST_DENSE, K_CHOOSE, K_COUNT_CAND, K_COUNT_DENSE,
-  K_SCAN, K_EMIT_CAND, K_EMIT_DENSE, K_MERGE_BOUNDS, K_MERGE, K_MERGE_APPLY, K_DELTA_TILES, K_DELTA_FINISH,
+  K_CSMALL0, K_CSMALL1, K_CSMALL2, K_HIST, K_CHOOSE, K_COUNT, K_SCAN, K_EMIT,
+  K_MERGE_BOUNDS, K_MERGE, K_MERGE_APPLY, K_DELTA_TILES, K_DELTA_FINISH,
+  K_SPARSIFY_CALL,      // not a kernel: the whole sparsify call on the caller's stream, fork to join
   K_NUM
 };
 const char* kernel_name(int id);

@@ -480,6 +480,67 @@ __device__ __forceinline__ void store_bits_nt(float* __restrict__ r, int lane, c
   }
 }
 
+// Candidate collection of one tile inside the streaming pass (all waves of the workgroup call
+// it; contains one barrier).  Every entry with key >= tau goes, in index order, into the
+// tile's slots (entries beyond nslot are dropped; the count written to *cnt then exceeds nslot
+// and marks the tile as overflowed), and collected entries with key >= tau_hi are replaced by
+// zero in `a`.  FULL: the wave's chunk is complete, no bounds checks.
+template <int NW, int V, bool FULL>
+__device__ __forceinline__ void stream_collect(uint32_t (&a)[V][4], int n_w, int lane, int w, uint32_t tau,
+                                               uint32_t tau_hi, int32_t idx0, uint2* __restrict__ slot,
+                                               int nslot, uint32_t* __restrict__ cnt, uint32_t* s_cnt) {
+  // one ballot per element slot of the wave; bitwise & keeps the code free of branches
+  uint64_t m[V][4];
+#pragma unroll
+  for (int j = 0; j < V; ++j) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const bool ge = (a[j][c] & 0x7FFFFFFFu) >= tau;
+      if (FULL) m[j][c] = __builtin_amdgcn_ballot_w64(ge);
+      else m[j][c] = __builtin_amdgcn_ballot_w64(ge & (j * 256 + lane * 4 + c < n_w));
+    }
+  }
+  uint32_t wtot = 0;
+#pragma unroll
+  for (int j = 0; j < V; ++j)
+    wtot += (uint32_t)(__popcll(m[j][0]) + __popcll(m[j][1]) + __popcll(m[j][2]) + __popcll(m[j][3]));
+  if (lane == 0) s_cnt[w] = wtot;
+  __syncthreads();
+  uint32_t base = 0, total = 0;
+#pragma unroll
+  for (int i = 0; i < NW; ++i) {
+    const uint32_t t = s_cnt[i];
+    if (i < w) base += t;
+    total += t;
+  }
+  if (threadIdx.x == 0) *cnt = total;
+  if (wtot == 0) return;  // wave-uniform
+#pragma unroll
+  for (int j = 0; j < V; ++j) {
+    const uint32_t tot =
+        (uint32_t)(__popcll(m[j][0]) + __popcll(m[j][1]) + __popcll(m[j][2]) + __popcll(m[j][3]));
+    if (tot) {  // wave-uniform
+      const int e = j * 256 + lane * 4;
+      // slot of the lane's first candidate of this round, then one predicated store and one
+      // select per component
+      uint32_t pos = base + mbcnt64(m[j][0]) + mbcnt64(m[j][1]) + mbcnt64(m[j][2]) + mbcnt64(m[j][3]);
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const uint32_t key = a[j][c] & 0x7FFFFFFFu;
+        const bool f = FULL ? key >= tau : ((key >= tau) & (e + c < n_w));
+        const bool put = f & (pos < (uint32_t)nslot);
+        if (put) slot[pos] = make_uint2((uint32_t)(idx0 + e + c), a[j][c]);
+        // an entry at or above tau_hi is expected to be kept: its residual is written as zero
+        // right here (its value is safe in the slot); the final pass corrects the few entries
+        // for which that expectation turns out wrong
+        a[j][c] = (put & (key >= tau_hi)) ? 0u : a[j][c];
+        pos += f ? 1u : 0u;
+      }
+      base += tot;
+    }
+  }
+}
+
 // The one pass over grad and residual of every large layer: acc = residual + lr*grad is
 // written into the residual buffer (it is the final residual everywhere but at the k kept
 // entries).  Tiles of sampled layers also collect, in index order, the entries with
@@ -535,55 +596,11 @@ __global__ __launch_bounds__(NW * 64) void k_stream(const TileDesc* __restrict__
     load_acc<V>(g, r, n_w, lr, vec, lane, a);
   }
   if (collect) {
-    // candidates of the wave, then its position among the tile's waves
-    uint32_t wtot = 0;
-#pragma unroll
-    for (int j = 0; j < V; ++j) {
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const int e = j * 256 + lane * 4 + c;
-        wtot += (uint32_t)__popcll(__ballot(e < n_w && (a[j][c] & 0x7FFFFFFFu) >= tau));
-      }
-    }
-    if (lane == 0) s_cnt[w] = wtot;
-    __syncthreads();
-    uint32_t base = 0, total = 0;
-#pragma unroll
-    for (int i = 0; i < NW; ++i) {
-      const uint32_t t = s_cnt[i];
-      if (i < w) base += t;
-      total += t;
-    }
-    if (tid == 0) chunk_cnt[td.ctile] = total;  // a count above nslot marks the tile as overflowed
-    if (wtot) {  // wave-uniform
-      uint2* slot = slots + (int64_t)td.ctile * nslot;
-      const int32_t idx0 = td.local0 + w * WC;
-#pragma unroll
-      for (int j = 0; j < V; ++j) {
-        const int e = j * 256 + lane * 4;
-        bool f[4];
-#pragma unroll
-        for (int c = 0; c < 4; ++c) f[c] = (e + c < n_w) && ((a[j][c] & 0x7FFFFFFFu) >= tau);
-        const uint64_t b0 = __ballot(f[0]), b1 = __ballot(f[1]), b2 = __ballot(f[2]), b3 = __ballot(f[3]);
-        const uint32_t tot = (uint32_t)(__popcll(b0) + __popcll(b1) + __popcll(b2) + __popcll(b3));
-        if (tot) {  // wave-uniform
-          // slot of the lane's first candidate of this round, then one predicated store and one
-          // select per component (flat code: no nested divergent branches)
-          uint32_t pos = base + mbcnt64(b0) + mbcnt64(b1) + mbcnt64(b2) + mbcnt64(b3);
-#pragma unroll
-          for (int c = 0; c < 4; ++c) {
-            const bool put = f[c] && pos < (uint32_t)nslot;
-            if (put) slot[pos] = make_uint2((uint32_t)(idx0 + e + c), a[j][c]);
-            // an entry at or above tau_hi is expected to be kept: its residual is written as
-            // zero right here (its value is safe in the slot); the final pass corrects the few
-            // entries for which that expectation turns out wrong
-            a[j][c] = (put && (a[j][c] & 0x7FFFFFFFu) >= tau_hi) ? 0u : a[j][c];
-            pos += f[c] ? 1u : 0u;
-          }
-          base += tot;
-        }
-      }
-    }
+    uint2* slot = slots + (int64_t)td.ctile * nslot;
+    uint32_t* cnt = chunk_cnt + td.ctile;
+    const int32_t idx0 = td.local0 + w * WC;
+    if (fast) stream_collect<NW, V, true>(a, n_w, lane, w, tau, tau_hi, idx0, slot, nslot, cnt, s_cnt);
+    else stream_collect<NW, V, false>(a, n_w, lane, w, tau, tau_hi, idx0, slot, nslot, cnt, s_cnt);
     if (fast) store_bits_nt<V>(r, lane, a);
     else store_bits<V>(r, n_w, vec, lane, a);
   } else {
@@ -615,7 +632,7 @@ __global__ __launch_bounds__(1024) void k_cscan(const SegDesc* __restrict__ segs
                                                 LState* __restrict__ lstate,
                                                 const uint32_t* __restrict__ chunk_cnt, int nslot,
                                                 uint32_t* __restrict__ chunk_off,
-                                                uint32_t* __restrict__ counters,
+                                                uint32_t* __restrict__ counter,
                                                 int32_t* __restrict__ items) {
   __shared__ uint32_t s_wt[16];
   __shared__ uint32_t s_base;
@@ -653,7 +670,7 @@ __global__ __launch_bounds__(1024) void k_cscan(const SegDesc* __restrict__ segs
   if (tid == 0) lstate[li].mode = mode;
   if (mode == MODE_DENSE) {
     const int nt = ls.tile_end - ls.tile_begin;
-    if (tid == 0) s_base = atomicAdd(&counters[0], (uint32_t)nt);
+    if (tid == 0) s_base = atomicAdd(counter, (uint32_t)nt);
     __syncthreads();
     const uint32_t b = s_base;
     for (int j = tid; j < nt; j += 1024) items[b + j] = ls.tile_begin + j;
@@ -785,22 +802,24 @@ __device__ __forceinline__ void load_tile(const TileWork& tw, int w, int lane, u
   }
 }
 
+// The three per-tile kernels below serve both sources in one launch: workgroups
+// [0, n_cblocks) take one candidate tile each (ctiles[blockIdx.x]); the kDenseGrid workgroups
+// after them walk the fallback work list (items[0 .. *counter)), which is empty unless a
+// layer's guess was rejected.
+
 // Histogram of one radix digit over the entries whose higher key bits equal the prefix.
 template <int LEVEL, bool CAND>
-__global__ __launch_bounds__(256) void k_hist(const TileDesc* __restrict__ tiles,
-                                              const int32_t* __restrict__ items,
-                                              const uint32_t* __restrict__ counters, int n_tiles,
-                                              float* __restrict__ res,
-                                              const uint2* __restrict__ cand,
-                                              const LState* __restrict__ lstate,
-                                              uint32_t* __restrict__ ghist) {
+__device__ __forceinline__ void hist_tiles(int first, int end, int step, uint32_t* s_hist,
+                                           const TileDesc* __restrict__ tiles,
+                                           const int32_t* __restrict__ items, int n_tiles,
+                                           float* __restrict__ res, const uint2* __restrict__ cand,
+                                           const LState* __restrict__ lstate,
+                                           uint32_t* __restrict__ ghist) {
   constexpr int shift = LEVEL == 0 ? 20 : (LEVEL == 1 ? 10 : 0);
   constexpr uint32_t mask = LEVEL == 0 ? 0u : (LEVEL == 1 ? 0x7FF00000u : 0x7FFFFC00u);
   constexpr int nb = LEVEL == 0 ? kBins0 : kBins12;
-  __shared__ uint32_t s_hist[nb];
   const int tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
-  const int n_items = CAND ? (int)gridDim.x : (int)counters[0];
-  for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
+  for (int item = first; item < end; item += step) {
     TileWork tw;
     if (!get_tile<CAND>(item, tiles, items, res, cand, lstate, n_tiles, tw)) continue;
     if (LEVEL == 0 && tw.skip_level0) continue;
@@ -831,9 +850,27 @@ __global__ __launch_bounds__(256) void k_hist(const TileDesc* __restrict__ tiles
   }
 }
 
+template <int LEVEL>
+__global__ __launch_bounds__(256) void k_hist(int n_cblocks, const TileDesc* __restrict__ ctiles,
+                                              const TileDesc* __restrict__ tiles,
+                                              const int32_t* __restrict__ items,
+                                              const uint32_t* __restrict__ counter, int n_tiles,
+                                              float* __restrict__ res,
+                                              const uint2* __restrict__ cand,
+                                              const LState* __restrict__ lstate,
+                                              uint32_t* __restrict__ ghist) {
+  __shared__ uint32_t s_hist[LEVEL == 0 ? kBins0 : kBins12];
+  const int b = (int)blockIdx.x;
+  if (b < n_cblocks)  // uniform over the workgroup
+    hist_tiles<LEVEL, true>(b, b + 1, 1, s_hist, ctiles, items, n_tiles, res, cand, lstate, ghist);
+  else
+    hist_tiles<LEVEL, false>(b - n_cblocks, (int)*counter, kDenseGrid, s_hist, tiles, items, n_tiles, res, cand,
+                             lstate, ghist);
+}
+
 // Decide one digit of T for every large layer from its histogram, then clear the
-// histogram for the next pass.  One workgroup of 256 threads per layer.  Layers whose
-// histogram is empty (their selection runs elsewhere) are left alone.
+// histogram for the next pass.  One workgroup of 256 threads per
+// layer.  Layers whose histogram is empty (their selection runs elsewhere) are left alone.
 __global__ __launch_bounds__(256) void k_choose(int level, const LargeSeg* __restrict__ lsegs,
                                                 const SegDesc* __restrict__ segs,
                                                 uint32_t* __restrict__ ghist,
@@ -865,18 +902,15 @@ __global__ __launch_bounds__(256) void k_choose(int level, const LargeSeg* __res
 
 // With T known: per tile, how many keys are above T and how many equal T.
 template <bool CAND>
-__global__ __launch_bounds__(256) void k_count(const TileDesc* __restrict__ tiles,
-                                               const int32_t* __restrict__ items,
-                                               const uint32_t* __restrict__ counters, int n_tiles,
-                                               float* __restrict__ res,
-                                               const uint2* __restrict__ cand,
-                                               const LState* __restrict__ lstate,
-                                               uint32_t* __restrict__ tile_gt,
-                                               uint32_t* __restrict__ tile_eq) {
-  __shared__ uint32_t s_g[4], s_e[4];
+__device__ __forceinline__ void count_tiles(int first, int end, int step, uint32_t* s_g, uint32_t* s_e,
+                                            const TileDesc* __restrict__ tiles,
+                                            const int32_t* __restrict__ items, int n_tiles,
+                                            float* __restrict__ res, const uint2* __restrict__ cand,
+                                            const LState* __restrict__ lstate,
+                                            uint32_t* __restrict__ tile_gt,
+                                            uint32_t* __restrict__ tile_eq) {
   const int tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
-  const int n_items = CAND ? (int)gridDim.x : (int)counters[0];
-  for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
+  for (int item = first; item < end; item += step) {
     TileWork tw;
     if (!get_tile<CAND>(item, tiles, items, res, cand, lstate, n_tiles, tw)) {
       // an empty candidate tile of a layer in candidate mode still takes part in the scan
@@ -898,6 +932,25 @@ __global__ __launch_bounds__(256) void k_count(const TileDesc* __restrict__ tile
       tile_eq[tw.slot] = s_e[0] + s_e[1] + s_e[2] + s_e[3];
     }
   }
+}
+
+__global__ __launch_bounds__(256) void k_count(int n_cblocks, const TileDesc* __restrict__ ctiles,
+                                               const TileDesc* __restrict__ tiles,
+                                               const int32_t* __restrict__ items,
+                                               const uint32_t* __restrict__ counter, int n_tiles,
+                                               float* __restrict__ res,
+                                               const uint2* __restrict__ cand,
+                                               const LState* __restrict__ lstate,
+                                               uint32_t* __restrict__ tile_gt,
+                                               uint32_t* __restrict__ tile_eq) {
+  __shared__ uint32_t s_g[4], s_e[4];
+  const int b = (int)blockIdx.x;
+  if (b < n_cblocks)  // uniform over the workgroup
+    count_tiles<true>(b, b + 1, 1, s_g, s_e, ctiles, items, n_tiles, res, cand, lstate, tile_gt,
+                      tile_eq);
+  else
+    count_tiles<false>(b - n_cblocks, (int)*counter, kDenseGrid, s_g, s_e, tiles, items, n_tiles, res, cand, lstate,
+                       tile_gt, tile_eq);
 }
 
 // Exclusive scan of the per-tile counts inside each large layer (in place): over the
@@ -932,22 +985,18 @@ __global__ __launch_bounds__(1024) void k_scan(const LargeSeg* __restrict__ lseg
 
 // Final pass: ordered emission of the kept pairs and zeroing of their residual slots.
 template <bool CAND>
-__global__ __launch_bounds__(256) void k_emit(const TileDesc* __restrict__ tiles,
-                                              const int32_t* __restrict__ items,
-                                              const uint32_t* __restrict__ counters, int n_tiles,
-                                              const LargeSeg* __restrict__ lsegs,
-                                              const SegDesc* __restrict__ segs,
-                                              float* __restrict__ res,
-                                              const uint2* __restrict__ cand,
-                                              const LState* __restrict__ lstate,
-                                              const uint32_t* __restrict__ tile_gt,
-                                              const uint32_t* __restrict__ tile_eq,
-                                              int32_t* __restrict__ out_idx,
-                                              float* __restrict__ out_val) {
-  __shared__ uint32_t s_g[4], s_e[4];
+__device__ __forceinline__ void emit_tiles(int first, int end, int step, uint32_t* s_g, uint32_t* s_e,
+                                           const TileDesc* __restrict__ tiles,
+                                           const int32_t* __restrict__ items, int n_tiles,
+                                           const LargeSeg* __restrict__ lsegs,
+                                           const SegDesc* __restrict__ segs, float* __restrict__ res,
+                                           const uint2* __restrict__ cand,
+                                           const LState* __restrict__ lstate,
+                                           const uint32_t* __restrict__ tile_gt,
+                                           const uint32_t* __restrict__ tile_eq,
+                                           int32_t* __restrict__ out_idx, float* __restrict__ out_val) {
   const int tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
-  const int n_items = CAND ? (int)gridDim.x : (int)counters[0];
-  for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
+  for (int item = first; item < end; item += step) {
     TileWork tw;
     if (!get_tile<CAND>(item, tiles, items, res, cand, lstate, n_tiles, tw)) continue;
     const LState st = lstate[tw.lseg];
@@ -980,6 +1029,29 @@ __global__ __launch_bounds__(256) void k_emit(const TileDesc* __restrict__ tiles
                                    0u);
     }
   }
+}
+
+__global__ __launch_bounds__(256) void k_emit(int n_cblocks, const TileDesc* __restrict__ ctiles,
+                                              const TileDesc* __restrict__ tiles,
+                                              const int32_t* __restrict__ items,
+                                              const uint32_t* __restrict__ counter, int n_tiles,
+                                              const LargeSeg* __restrict__ lsegs,
+                                              const SegDesc* __restrict__ segs,
+                                              float* __restrict__ res,
+                                              const uint2* __restrict__ cand,
+                                              const LState* __restrict__ lstate,
+                                              const uint32_t* __restrict__ tile_gt,
+                                              const uint32_t* __restrict__ tile_eq,
+                                              int32_t* __restrict__ out_idx,
+                                              float* __restrict__ out_val) {
+  __shared__ uint32_t s_g[4], s_e[4];
+  const int b = (int)blockIdx.x;
+  if (b < n_cblocks)  // uniform over the workgroup
+    emit_tiles<true>(b, b + 1, 1, s_g, s_e, ctiles, items, n_tiles, lsegs, segs, res, cand, lstate,
+                     tile_gt, tile_eq, out_idx, out_val);
+  else
+    emit_tiles<false>(b - n_cblocks, (int)*counter, kDenseGrid, s_g, s_e, tiles, items, n_tiles, lsegs, segs, res,
+                      cand, lstate, tile_gt, tile_eq, out_idx, out_val);
 }
 
 // ------------------------------------------------------------------ merge ----
@@ -1251,9 +1323,9 @@ __global__ __launch_bounds__(256) void k_delta_finish(const SegDesc* __restrict_
 const char* kernel_name(int id) {
   static const char* names[K_NUM] = {
       "k_zero_u32", "k_small<4,1>", "k_small<4,8>", "k_small<16,10>", "k_sample", "k_stream", "k_cscan",
-      "k_cgather", "k_small<4,1,cand>", "k_small<4,8,cand>", "k_small<16,10,cand>", "k_hist<cand>",
-      "k_hist<dense>", "k_choose", "k_count<cand>", "k_count<dense>", "k_scan", "k_emit<cand>",
-      "k_emit<dense>", "k_merge_bounds", "k_merge", "k_merge<apply>", "k_delta_tiles", "k_delta_finish"};
+      "k_cgather", "k_small<4,1,cand>", "k_small<4,8,cand>", "k_small<16,10,cand>", "k_hist", "k_choose",
+      "k_count", "k_scan", "k_emit", "k_merge_bounds", "k_merge", "k_merge<apply>", "k_delta_tiles",
+      "k_delta_finish", "sparsify_call"};
   return (id >= 0 && id < K_NUM) ? names[id] : nullptr;
 }
 
@@ -1332,59 +1404,39 @@ hipError_t launch_large(const LargePlan& pl, const Scratch& sc, const SegDesc* s
     hipLaunchKernelGGL((k_small<16, 10, true>), dim3(pl.n_cand_small[2]), dim3(1024), 0, s, segs,
                        pl.cand_small[2], pl.lsegs, sc.lstate, sc.cand, ng, res, lr, out_idx, out_val);
   }
-  const dim3 gc(pl.n_ctiles > 0 ? pl.n_ctiles : 1), gd(kDenseGrid), b(256);
+  // candidate tiles first, then the workgroups of the fallback work list
+  const int nct = pl.n_ctiles;
+  const dim3 grid(nct + kDenseGrid), b(256);
   for (int level = 0; level < 3; ++level) {
-    if (pl.n_ctiles > 0) {
-      ProfScope ps(prof, K_HIST_CAND, s);
-      if (level == 0)
-        hipLaunchKernelGGL((k_hist<0, true>), gc, b, 0, s, pl.ctiles, sc.items, sc.counters, pl.n_tiles, res,
-                           sc.cand, sc.lstate, sc.ghist);
-      else if (level == 1)
-        hipLaunchKernelGGL((k_hist<1, true>), gc, b, 0, s, pl.ctiles, sc.items, sc.counters, pl.n_tiles, res,
-                           sc.cand, sc.lstate, sc.ghist);
-      else
-        hipLaunchKernelGGL((k_hist<2, true>), gc, b, 0, s, pl.ctiles, sc.items, sc.counters, pl.n_tiles, res,
-                           sc.cand, sc.lstate, sc.ghist);
-    }
     {
-      ProfScope ps(prof, K_HIST_DENSE, s);
+      ProfScope ps(prof, K_HIST, s);
       if (level == 0)
-        hipLaunchKernelGGL((k_hist<0, false>), gd, b, 0, s, pl.tiles, sc.items, sc.counters, pl.n_tiles, res,
-                           sc.cand, sc.lstate, sc.ghist);
+        hipLaunchKernelGGL((k_hist<0>), grid, b, 0, s, nct, pl.ctiles, pl.tiles, sc.items, sc.counters, pl.n_tiles,
+                           res, sc.cand, sc.lstate, sc.ghist);
       else if (level == 1)
-        hipLaunchKernelGGL((k_hist<1, false>), gd, b, 0, s, pl.tiles, sc.items, sc.counters, pl.n_tiles, res,
-                           sc.cand, sc.lstate, sc.ghist);
+        hipLaunchKernelGGL((k_hist<1>), grid, b, 0, s, nct, pl.ctiles, pl.tiles, sc.items, sc.counters, pl.n_tiles,
+                           res, sc.cand, sc.lstate, sc.ghist);
       else
-        hipLaunchKernelGGL((k_hist<2, false>), gd, b, 0, s, pl.tiles, sc.items, sc.counters, pl.n_tiles, res,
-                           sc.cand, sc.lstate, sc.ghist);
+        hipLaunchKernelGGL((k_hist<2>), grid, b, 0, s, nct, pl.ctiles, pl.tiles, sc.items, sc.counters, pl.n_tiles,
+                           res, sc.cand, sc.lstate, sc.ghist);
     }
     ProfScope ps(prof, K_CHOOSE, s);
     hipLaunchKernelGGL(k_choose, dim3(pl.n_large), b, 0, s, level, pl.lsegs, segs, sc.ghist, sc.lstate);
   }
-  if (pl.n_ctiles > 0) {
-    ProfScope ps(prof, K_COUNT_CAND, s);
-    hipLaunchKernelGGL((k_count<true>), gc, b, 0, s, pl.ctiles, sc.items, sc.counters, pl.n_tiles, res, sc.cand,
-                       sc.lstate, sc.tile_gt, sc.tile_eq);
-  }
   {
-    ProfScope ps(prof, K_COUNT_DENSE, s);
-    hipLaunchKernelGGL((k_count<false>), gd, b, 0, s, pl.tiles, sc.items, sc.counters, pl.n_tiles, res, sc.cand,
-                       sc.lstate, sc.tile_gt, sc.tile_eq);
+    ProfScope ps(prof, K_COUNT, s);
+    hipLaunchKernelGGL(k_count, grid, b, 0, s, nct, pl.ctiles, pl.tiles, sc.items, sc.counters, pl.n_tiles, res,
+                       sc.cand, sc.lstate, sc.tile_gt, sc.tile_eq);
   }
   {
     ProfScope ps(prof, K_SCAN, s);
     hipLaunchKernelGGL(k_scan, dim3(pl.n_large), dim3(1024), 0, s, pl.lsegs, sc.lstate, pl.n_tiles, sc.tile_gt,
                        sc.tile_eq);
   }
-  if (pl.n_ctiles > 0) {
-    ProfScope ps(prof, K_EMIT_CAND, s);
-    hipLaunchKernelGGL((k_emit<true>), gc, b, 0, s, pl.ctiles, sc.items, sc.counters, pl.n_tiles, pl.lsegs, segs,
-                       res, sc.cand, sc.lstate, sc.tile_gt, sc.tile_eq, out_idx, out_val);
-  }
   {
-    ProfScope ps(prof, K_EMIT_DENSE, s);
-    hipLaunchKernelGGL((k_emit<false>), gd, b, 0, s, pl.tiles, sc.items, sc.counters, pl.n_tiles, pl.lsegs, segs,
-                       res, sc.cand, sc.lstate, sc.tile_gt, sc.tile_eq, out_idx, out_val);
+    ProfScope ps(prof, K_EMIT, s);
+    hipLaunchKernelGGL(k_emit, grid, b, 0, s, nct, pl.ctiles, pl.tiles, sc.items, sc.counters, pl.n_tiles, pl.lsegs,
+                       segs, res, sc.cand, sc.lstate, sc.tile_gt, sc.tile_eq, out_idx, out_val);
   }
   return hipGetLastError();
 }
