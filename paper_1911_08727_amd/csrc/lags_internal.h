@@ -34,13 +34,20 @@ constexpr int kSampleMax = kSamplePiece * kSamplePieces;   // 16384 sampled elem
 constexpr int kSlotMin = 256;            // candidate slots per tile of a sampled layer: the table uses the
 constexpr int kSlotMax = 2048;           // smallest power of two >= 8x the expected count of any layer
 constexpr int kDenseGrid = 1024;         // workgroups of the fallback kernels (grid-stride)
-// The streaming pass is enqueued as back-to-back launches of at most this many tiles: measured
-// on MI355X, a 26 GB stream runs 8 % faster as 32-64 launches than as one (the workgroups in
-// flight stay within a narrower address window), and slower again beyond ~128 launches.
-constexpr int kStreamLaunchTiles = 16384;
-// Shape of the streaming workgroup: 4 waves x 4 rounds.  (A bare stream kernel is 2 % faster
-// with 16 waves x 1 round, but with the candidate collection and its barrier that shape
-// measured 6 % slower.)
+// The streaming pass is HBM-bound and runs best when each CU holds only three of its
+// workgroups (12 waves, about 96 KB of loads in flight per CU): measured on MI355X, 26.6 GB in
+// 4.05 ms, against 4.36 ms at the eight workgroups that registers and static LDS would allow
+// (more bytes in flight only widen the window of DRAM rows that are open at once) and 4.6 ms
+// at two.  The launch therefore asks for this much unused dynamic LDS per workgroup, which
+// caps the workgroups per CU at three (160 KB of LDS per CU).
+constexpr int kStreamLdsPad = 40960;
+// It is enqueued as back-to-back launches of at most this many tiles: with the occupancy cap,
+// launches of 65536 tiles measured 3 % faster than one launch of 540000 tiles and 2 % faster than
+// launches of 16384 (a launch boundary lets the 8 XCDs, which drift apart inside a launch, start
+// again from neighbouring addresses).
+constexpr int kStreamLaunchTiles = 65536;
+// Shape of the streaming workgroup: 4 waves x 4 rounds (8 x 2 and 2 x 8 measured 2-4 % slower at
+// their best occupancy, 16 x 1 10 % slower).
 constexpr int kStreamWaves = 4;
 constexpr int kStreamV = 4;
 

@@ -31,6 +31,9 @@
 namespace lags {
 
 // ------------------------------------------------------------------ helpers --
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
 __device__ __forceinline__ int lane_id() {
   return (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
 }
@@ -466,9 +469,6 @@ __global__ __launch_bounds__(1024) void k_sample(const SegDesc* __restrict__ seg
 }
 
 // ------------------------------------------------------------------ stream ---
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
 // Non-temporal store of a wave's full, 16-byte aligned chunk.
 template <int V>
 __device__ __forceinline__ void store_bits_nt(float* __restrict__ r, int lane, const uint32_t (&a)[V][4]) {
@@ -1374,8 +1374,8 @@ hipError_t launch_large(const LargePlan& pl, const Scratch& sc, const SegDesc* s
     ProfScope ps(prof, K_STREAM, s, nl);
     for (int t0 = 0; t0 < pl.n_tiles; t0 += kStreamLaunchTiles) {
       const int nt = pl.n_tiles - t0 < kStreamLaunchTiles ? pl.n_tiles - t0 : kStreamLaunchTiles;
-      hipLaunchKernelGGL((k_stream<kStreamWaves, kStreamV>), dim3(nt), dim3(kStreamWaves * 64), 0, s, pl.tiles + t0,
-                         grad, res, lr, sc.lstate, sc.chunk_cnt, sc.slots, pl.slot, sc.ghist);
+      hipLaunchKernelGGL((k_stream<kStreamWaves, kStreamV>), dim3(nt), dim3(kStreamWaves * 64), kStreamLdsPad, s,
+                         pl.tiles + t0, grad, res, lr, sc.lstate, sc.chunk_cnt, sc.slots, pl.slot, sc.ghist);
     }
   }
   {
