@@ -36,7 +36,7 @@ struct DevBuf {
 struct lags_ctx {
   int device = 0;
   // scratch of the multi-block path, sized for the largest table created so far
-  DevBuf counters, ghist, lstate, tile_gt, tile_eq, items, chunk_cnt, chunk_off, slots, cand;
+  DevBuf ghist, lstate, tile_gt, tile_eq, items, chunk_cnt, chunk_off, slots, cand;
   DevBuf bounds;   // merge: P rows of tile start positions, sized at the first merge call that needs it
   DevBuf partials; // delta metric: two doubles per merge tile
   std::map<std::pair<int64_t, int64_t>, lags_table*> layer_tables;  // (d, k) -> one-layer table
@@ -47,7 +47,6 @@ struct lags_ctx {
   hipEvent_t ev_fork = nullptr, ev_join = nullptr;
   Scratch scratch() const {
     Scratch sc;
-    sc.counters = static_cast<uint32_t*>(counters.p);
     sc.ghist = static_cast<uint32_t*>(ghist.p);
     sc.lstate = static_cast<LState*>(lstate.p);
     sc.tile_gt = static_cast<uint32_t*>(tile_gt.p);
@@ -332,8 +331,7 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
   for (int c = 0; c < 3; ++c) pl.cand_small[c] = t->d_cand_small[c];
   if (pl.n_large > 0) {
     const size_t nt = (size_t)pl.n_tiles + (size_t)pl.n_ctiles;
-    if (rc == LAGS_OK) rc = ctx->counters.grow(16 * sizeof(uint32_t));
-    if (rc == LAGS_OK) rc = ctx->ghist.grow((size_t)pl.n_large * kHistStride * sizeof(uint32_t));
+    if (rc == LAGS_OK) rc = ctx->ghist.grow(((size_t)pl.n_large * kHistStride + 16) * sizeof(uint32_t));
     if (rc == LAGS_OK) rc = ctx->lstate.grow((size_t)pl.n_large * sizeof(LState));
     if (rc == LAGS_OK) rc = ctx->tile_gt.grow(nt * sizeof(uint32_t));
     if (rc == LAGS_OK) rc = ctx->tile_eq.grow(nt * sizeof(uint32_t));
@@ -431,7 +429,7 @@ int lags_destroy(lags_ctx* ctx) {
     free_table_device(kv.second);
     delete kv.second;
   }
-  DevBuf* bufs[] = {&ctx->counters, &ctx->ghist, &ctx->lstate, &ctx->tile_gt, &ctx->tile_eq, &ctx->items,
+  DevBuf* bufs[] = {&ctx->ghist, &ctx->lstate, &ctx->tile_gt, &ctx->tile_eq, &ctx->items,
                     &ctx->chunk_cnt, &ctx->chunk_off, &ctx->slots, &ctx->cand, &ctx->bounds, &ctx->partials};
   for (DevBuf* b : bufs) b->release();
   delete ctx;

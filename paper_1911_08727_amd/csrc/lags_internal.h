@@ -17,7 +17,9 @@ constexpr int kWaveChunk = kTileV * 256;                // 1024 elements per wav
 constexpr int kTile = kTileWaves * kWaveChunk;          // 4096 elements per tile
 constexpr int kBins0 = 2048;                            // key bits 30..20
 constexpr int kBins12 = 1024;                           // key bits 19..10, 9..0
-constexpr int kHistStride = 2048;
+constexpr int kHistLevel1 = kBins0;                     // a layer's three histograms sit side by side:
+constexpr int kHistLevel2 = kBins0 + kBins12;           // level 0 at [0, 2048), level 1 at [2048, 3072),
+constexpr int kHistStride = kBins0 + 2 * kBins12;       // level 2 at [3072, 4096)
 
 // Size classes of the one-workgroup-per-layer ("small") path: NW waves x V rounds.
 constexpr int kSmall0 = 4 * 1 * 256;     // <= 1024  : 4 waves, 1 round
@@ -103,8 +105,10 @@ struct LState {         // per call, per large layer
   uint32_t tau_hi;      // candidates with key >= tau_hi had their residual zeroed by the streaming pass
   uint32_t ncand;       // number of candidates found
   uint32_t mode;        // MODE_SPARSE: the candidate list holds the top k; MODE_DENSE: fall back
-  uint32_t prefix;      // radix select: key bits decided so far
-  uint32_t k_rem;       // entries still to take among keys matching the prefix
+  uint32_t p0, k0;      // radix select after digit 0: key bits decided, entries still to take below them
+  uint32_t p1, k1;      // ... after digit 1
+  uint32_t prefix;      // ... after digit 2: the k-th largest key T
+  uint32_t k_rem;       //     and how many entries equal to T belong to the top k
   uint32_t pad[2];
 };
 
@@ -121,8 +125,8 @@ struct LargePlan {      // everything launch_large needs (device pointers + coun
 };
 
 struct Scratch {        // context-owned device memory, contents meaningless between calls
-  uint32_t* counters = nullptr;   // [0] = number of dense work items; zeroed each call
-  uint32_t* ghist = nullptr;      // n_large * kHistStride
+  uint32_t* ghist = nullptr;      // n_large * kHistStride, then 16 counters ([0] = number of dense
+                                  // work items); zeroed each call
   LState* lstate = nullptr;       // n_large
   uint32_t* tile_gt = nullptr;    // n_tiles + n_ctiles
   uint32_t* tile_eq = nullptr;
@@ -136,7 +140,7 @@ struct Scratch {        // context-owned device memory, contents meaningless bet
 // Kernel ids for the optional event timing.
 enum KernelId {
   K_ZERO = 0, K_SMALL0, K_SMALL1, K_SMALL2, K_SAMPLE, K_STREAM, K_CSCAN, K_CGATHER,
-  K_CSMALL0, K_CSMALL1, K_CSMALL2, K_HIST, K_CHOOSE, K_COUNT, K_SCAN, K_EMIT,
+  K_CSMALL0, K_CSMALL1, K_CSMALL2, K_HIST, K_COUNT, K_SCAN, K_EMIT,
   K_MERGE_BOUNDS, K_MERGE, K_MERGE_APPLY, K_DELTA_TILES, K_DELTA_FINISH,
   K_SPARSIFY_CALL,      // not a kernel: the whole sparsify call on the caller's stream, fork to join
   K_NUM

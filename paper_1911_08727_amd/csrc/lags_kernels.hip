@@ -807,14 +807,32 @@ __device__ __forceinline__ void load_tile(const TileWork& tw, int w, int lane, u
 // after them walk the fallback work list (items[0 .. *counter)), which is empty unless a
 // layer's guess was rejected.
 
-// Histogram of one radix digit over the entries whose higher key bits equal the prefix.
+// One digit of the radix select, decided from the layer's histogram of that digit (complete
+// since the previous launch): every workgroup that needs the result computes it for itself,
+// and the workgroup that holds the layer's first tile also records it in the layer's state for
+// the launches after this one.  k_before: entries still to take before this digit.
+// Returns false if the histogram holds fewer than k_before entries (nothing to select).
+__device__ __forceinline__ bool decide_digit(const uint32_t* __restrict__ gh, int nb, int shift, uint32_t p_before,
+                                             uint32_t k_before, uint32_t* s_wt, uint32_t* s_sel,
+                                             uint32_t& p_after, uint32_t& k_after) {
+  __syncthreads();
+  if (threadIdx.x == 0) { s_sel[0] = 0u; s_sel[1] = 0u; }
+  __syncthreads();
+  block_find_bucket<256>(gh, nb, k_before, s_wt, s_sel);
+  p_after = p_before | (s_sel[0] << shift);
+  k_after = s_sel[1];
+  return k_after != 0u;
+}
+
+// Histogram of one radix digit over the entries whose higher key bits equal the prefix
+// (levels 1 and 2 first decide the digit before theirs from its histogram).
 template <int LEVEL, bool CAND>
-__device__ __forceinline__ void hist_tiles(int first, int end, int step, uint32_t* s_hist,
-                                           const TileDesc* __restrict__ tiles,
+__device__ __forceinline__ void hist_tiles(int first, int end, int step, uint32_t* s_hist, uint32_t* s_wt,
+                                           uint32_t* s_sel, const TileDesc* __restrict__ tiles,
                                            const int32_t* __restrict__ items, int n_tiles,
+                                           const LargeSeg* __restrict__ lsegs, const SegDesc* __restrict__ segs,
                                            float* __restrict__ res, const uint2* __restrict__ cand,
-                                           const LState* __restrict__ lstate,
-                                           uint32_t* __restrict__ ghist) {
+                                           LState* __restrict__ lstate, uint32_t* __restrict__ ghist) {
   constexpr int shift = LEVEL == 0 ? 20 : (LEVEL == 1 ? 10 : 0);
   constexpr uint32_t mask = LEVEL == 0 ? 0u : (LEVEL == 1 ? 0x7FF00000u : 0x7FFFFC00u);
   constexpr int nb = LEVEL == 0 ? kBins0 : kBins12;
@@ -823,9 +841,20 @@ __device__ __forceinline__ void hist_tiles(int first, int end, int step, uint32_
     TileWork tw;
     if (!get_tile<CAND>(item, tiles, items, res, cand, lstate, n_tiles, tw)) continue;
     if (LEVEL == 0 && tw.skip_level0) continue;
+    uint32_t* gh = ghist + (int64_t)tw.lseg * kHistStride;
+    uint32_t prefix = 0u;
+    if (LEVEL == 1) {
+      uint32_t kr;
+      if (!decide_digit(gh, kBins0, 20, 0u, (uint32_t)segs[lsegs[tw.lseg].seg].k, s_wt, s_sel, prefix, kr)) continue;
+      if (tw.local0 == 0 && tid == 0) { lstate[tw.lseg].p0 = prefix; lstate[tw.lseg].k0 = kr; }
+    } else if (LEVEL == 2) {
+      uint32_t kr;
+      const uint32_t p0 = lstate[tw.lseg].p0, k0 = lstate[tw.lseg].k0;
+      if (!decide_digit(gh + kHistLevel1, kBins12, 10, p0, k0, s_wt, s_sel, prefix, kr)) continue;
+      if (tw.local0 == 0 && tid == 0) { lstate[tw.lseg].p1 = prefix; lstate[tw.lseg].k1 = kr; }
+    }
     __syncthreads();
     for (int i = tid; i < nb; i += 256) s_hist[i] = 0u;
-    const uint32_t prefix = LEVEL == 0 ? 0u : lstate[tw.lseg].prefix;
     uint32_t a[kTileV][4];
     load_tile<CAND>(tw, w, lane, a);
     const int n_w = tw.n - w * kWaveChunk;
@@ -842,10 +871,10 @@ __device__ __forceinline__ void hist_tiles(int first, int end, int step, uint32_
       }
     }
     __syncthreads();
-    uint32_t* gh = ghist + (int64_t)tw.lseg * kHistStride;
+    uint32_t* gl = gh + (LEVEL == 0 ? 0 : (LEVEL == 1 ? kHistLevel1 : kHistLevel2));
     for (int i = tid; i < nb; i += 256) {
       const uint32_t h = s_hist[i];
-      if (h) atomicAdd(&gh[i], h);
+      if (h) atomicAdd(&gl[i], h);
     }
   }
 }
@@ -855,58 +884,33 @@ __global__ __launch_bounds__(256) void k_hist(int n_cblocks, const TileDesc* __r
                                               const TileDesc* __restrict__ tiles,
                                               const int32_t* __restrict__ items,
                                               const uint32_t* __restrict__ counter, int n_tiles,
+                                              const LargeSeg* __restrict__ lsegs,
+                                              const SegDesc* __restrict__ segs,
                                               float* __restrict__ res,
                                               const uint2* __restrict__ cand,
-                                              const LState* __restrict__ lstate,
+                                              LState* __restrict__ lstate,
                                               uint32_t* __restrict__ ghist) {
   __shared__ uint32_t s_hist[LEVEL == 0 ? kBins0 : kBins12];
-  const int b = (int)blockIdx.x;
-  if (b < n_cblocks)  // uniform over the workgroup
-    hist_tiles<LEVEL, true>(b, b + 1, 1, s_hist, ctiles, items, n_tiles, res, cand, lstate, ghist);
-  else
-    hist_tiles<LEVEL, false>(b - n_cblocks, (int)*counter, kDenseGrid, s_hist, tiles, items, n_tiles, res, cand,
-                             lstate, ghist);
-}
-
-// Decide one digit of T for every large layer from its histogram, then clear the
-// histogram for the next pass.  One workgroup of 256 threads per
-// layer.  Layers whose histogram is empty (their selection runs elsewhere) are left alone.
-__global__ __launch_bounds__(256) void k_choose(int level, const LargeSeg* __restrict__ lsegs,
-                                                const SegDesc* __restrict__ segs,
-                                                uint32_t* __restrict__ ghist,
-                                                LState* __restrict__ lstate) {
   __shared__ uint32_t s_wt[4];
   __shared__ uint32_t s_sel[2];
-  const int ls = blockIdx.x;
-  const int shift = level == 0 ? 20 : (level == 1 ? 10 : 0);
-  const int nb = level == 0 ? kBins0 : kBins12;
-  uint32_t* gh = ghist + (int64_t)ls * kHistStride;
-  uint32_t prefix = 0, k_rem;
-  if (level == 0) {
-    k_rem = (uint32_t)segs[lsegs[ls].seg].k;
-  } else {
-    prefix = lstate[ls].prefix;
-    k_rem = lstate[ls].k_rem;
-  }
-  if (threadIdx.x == 0) { s_sel[0] = 0u; s_sel[1] = 0u; }
-  __syncthreads();
-  block_find_bucket<256>(gh, nb, k_rem, s_wt, s_sel);
-  const uint32_t b = s_sel[0], kr = s_sel[1];
-  __syncthreads();
-  for (int i = threadIdx.x; i < nb; i += 256) gh[i] = 0u;
-  if (threadIdx.x == 0 && kr != 0u) {
-    lstate[ls].prefix = prefix | (b << shift);
-    lstate[ls].k_rem = kr;
-  }
+  const int b = (int)blockIdx.x;
+  if (b < n_cblocks)  // uniform over the workgroup
+    hist_tiles<LEVEL, true>(b, b + 1, 1, s_hist, s_wt, s_sel, ctiles, items, n_tiles, lsegs, segs, res, cand, lstate,
+                            ghist);
+  else
+    hist_tiles<LEVEL, false>(b - n_cblocks, (int)*counter, kDenseGrid, s_hist, s_wt, s_sel, tiles, items, n_tiles,
+                             lsegs, segs, res, cand, lstate, ghist);
 }
 
-// With T known: per tile, how many keys are above T and how many equal T.
+// Decides the last digit (which fixes the k-th largest key T and the number of entries equal
+// to T to take), then counts per tile how many keys are above T and how many equal T.
 template <bool CAND>
 __device__ __forceinline__ void count_tiles(int first, int end, int step, uint32_t* s_g, uint32_t* s_e,
+                                            uint32_t* s_wt, uint32_t* s_sel,
                                             const TileDesc* __restrict__ tiles,
                                             const int32_t* __restrict__ items, int n_tiles,
                                             float* __restrict__ res, const uint2* __restrict__ cand,
-                                            const LState* __restrict__ lstate,
+                                            LState* __restrict__ lstate, const uint32_t* __restrict__ ghist,
                                             uint32_t* __restrict__ tile_gt,
                                             uint32_t* __restrict__ tile_eq) {
   const int tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
@@ -917,7 +921,12 @@ __device__ __forceinline__ void count_tiles(int first, int end, int step, uint32
       if (CAND && tw.active && tid == 0) { tile_gt[tw.slot] = 0u; tile_eq[tw.slot] = 0u; }
       continue;
     }
-    const uint32_t T = lstate[tw.lseg].prefix;
+    uint32_t T, rtake;
+    const uint32_t p1 = lstate[tw.lseg].p1, k1 = lstate[tw.lseg].k1;
+    if (!decide_digit(ghist + (int64_t)tw.lseg * kHistStride + kHistLevel2, kBins12, 0, p1, k1, s_wt, s_sel, T,
+                      rtake))
+      continue;
+    if (tw.local0 == 0 && tid == 0) { lstate[tw.lseg].prefix = T; lstate[tw.lseg].k_rem = rtake; }
     uint32_t a[kTileV][4];
     load_tile<CAND>(tw, w, lane, a);
     uint32_t cg, ce;
@@ -940,17 +949,20 @@ __global__ __launch_bounds__(256) void k_count(int n_cblocks, const TileDesc* __
                                                const uint32_t* __restrict__ counter, int n_tiles,
                                                float* __restrict__ res,
                                                const uint2* __restrict__ cand,
-                                               const LState* __restrict__ lstate,
+                                               LState* __restrict__ lstate,
+                                               const uint32_t* __restrict__ ghist,
                                                uint32_t* __restrict__ tile_gt,
                                                uint32_t* __restrict__ tile_eq) {
   __shared__ uint32_t s_g[4], s_e[4];
+  __shared__ uint32_t s_wt[4];
+  __shared__ uint32_t s_sel[2];
   const int b = (int)blockIdx.x;
   if (b < n_cblocks)  // uniform over the workgroup
-    count_tiles<true>(b, b + 1, 1, s_g, s_e, ctiles, items, n_tiles, res, cand, lstate, tile_gt,
+    count_tiles<true>(b, b + 1, 1, s_g, s_e, s_wt, s_sel, ctiles, items, n_tiles, res, cand, lstate, ghist, tile_gt,
                       tile_eq);
   else
-    count_tiles<false>(b - n_cblocks, (int)*counter, kDenseGrid, s_g, s_e, tiles, items, n_tiles, res, cand, lstate,
-                       tile_gt, tile_eq);
+    count_tiles<false>(b - n_cblocks, (int)*counter, kDenseGrid, s_g, s_e, s_wt, s_sel, tiles, items, n_tiles, res,
+                       cand, lstate, ghist, tile_gt, tile_eq);
 }
 
 // Exclusive scan of the per-tile counts inside each large layer (in place): over the
@@ -1220,7 +1232,11 @@ __global__ __launch_bounds__(256) void k_merge(const TileDesc* __restrict__ mtil
         v.x = __fdiv_rn(sv.x, fp); v.y = __fdiv_rn(sv.y, fp);
         v.z = __fdiv_rn(sv.z, fp); v.w = __fdiv_rn(sv.w, fp);
       }
-      *reinterpret_cast<float4*>(u + e) = v;
+      // the update is written once and not read again by this library: non-temporal stores
+      // (measured: 0.138 ms instead of 0.176 ms for 553 MB)
+      f32x4 o;
+      o.x = v.x; o.y = v.y; o.z = v.z; o.w = v.w;
+      __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(u + e));
     } else {
       for (int c = 0; c < 4; ++c)
         if (e + c < td.n) u[e + c] = pow2 ? __fmul_rn(s_acc[e + c], inv) : __fdiv_rn(s_acc[e + c], fp);
@@ -1323,9 +1339,9 @@ __global__ __launch_bounds__(256) void k_delta_finish(const SegDesc* __restrict_
 const char* kernel_name(int id) {
   static const char* names[K_NUM] = {
       "k_zero_u32", "k_small<4,1>", "k_small<4,8>", "k_small<16,10>", "k_sample", "k_stream", "k_cscan",
-      "k_cgather", "k_small<4,1,cand>", "k_small<4,8,cand>", "k_small<16,10,cand>", "k_hist", "k_choose",
-      "k_count", "k_scan", "k_emit", "k_merge_bounds", "k_merge", "k_merge<apply>", "k_delta_tiles",
-      "k_delta_finish", "sparsify_call"};
+      "k_cgather", "k_small<4,1,cand>", "k_small<4,8,cand>", "k_small<16,10,cand>", "k_hist", "k_count",
+      "k_scan", "k_emit", "k_merge_bounds", "k_merge", "k_merge<apply>", "k_delta_tiles", "k_delta_finish",
+      "sparsify_call"};
   return (id >= 0 && id < K_NUM) ? names[id] : nullptr;
 }
 
@@ -1360,9 +1376,9 @@ hipError_t launch_small(int cls, int nseg, const SegDesc* segs, const int32_t* l
 hipError_t launch_large(const LargePlan& pl, const Scratch& sc, const SegDesc* segs, const float* grad,
                         float* res, float lr, int32_t* out_idx, float* out_val, hipStream_t s, Prof* prof) {
   if (pl.n_large <= 0) return hipSuccess;
-  hipError_t e = launch_zero_u32(sc.counters, 16, s, prof);
-  if (e != hipSuccess) return e;
-  e = launch_zero_u32(sc.ghist, (int64_t)pl.n_large * kHistStride, s, prof);
+  // the layers' histograms and, behind them, the counters: one clearing launch per call
+  uint32_t* counters = sc.ghist + (int64_t)pl.n_large * kHistStride;
+  hipError_t e = launch_zero_u32(sc.ghist, (int64_t)pl.n_large * kHistStride + 16, s, prof);
   if (e != hipSuccess) return e;
   if (pl.n_sampled > 0) {
     ProfScope ps(prof, K_SAMPLE, s);
@@ -1381,7 +1397,7 @@ hipError_t launch_large(const LargePlan& pl, const Scratch& sc, const SegDesc* s
   {
     ProfScope ps(prof, K_CSCAN, s);
     hipLaunchKernelGGL(k_cscan, dim3(pl.n_large), dim3(1024), 0, s, segs, pl.lsegs, sc.lstate, sc.chunk_cnt,
-                       pl.slot, sc.chunk_off, sc.counters, sc.items);
+                       pl.slot, sc.chunk_off, counters, sc.items);
   }
   if (pl.n_chunks > 0) {
     ProfScope ps(prof, K_CGATHER, s);
@@ -1407,26 +1423,23 @@ hipError_t launch_large(const LargePlan& pl, const Scratch& sc, const SegDesc* s
   // candidate tiles first, then the workgroups of the fallback work list
   const int nct = pl.n_ctiles;
   const dim3 grid(nct + kDenseGrid), b(256);
+  // the digit chosen from each level's histogram is computed by the workgroups of the next launch
   for (int level = 0; level < 3; ++level) {
-    {
-      ProfScope ps(prof, K_HIST, s);
-      if (level == 0)
-        hipLaunchKernelGGL((k_hist<0>), grid, b, 0, s, nct, pl.ctiles, pl.tiles, sc.items, sc.counters, pl.n_tiles,
-                           res, sc.cand, sc.lstate, sc.ghist);
-      else if (level == 1)
-        hipLaunchKernelGGL((k_hist<1>), grid, b, 0, s, nct, pl.ctiles, pl.tiles, sc.items, sc.counters, pl.n_tiles,
-                           res, sc.cand, sc.lstate, sc.ghist);
-      else
-        hipLaunchKernelGGL((k_hist<2>), grid, b, 0, s, nct, pl.ctiles, pl.tiles, sc.items, sc.counters, pl.n_tiles,
-                           res, sc.cand, sc.lstate, sc.ghist);
-    }
-    ProfScope ps(prof, K_CHOOSE, s);
-    hipLaunchKernelGGL(k_choose, dim3(pl.n_large), b, 0, s, level, pl.lsegs, segs, sc.ghist, sc.lstate);
+    ProfScope ps(prof, K_HIST, s);
+    if (level == 0)
+      hipLaunchKernelGGL((k_hist<0>), grid, b, 0, s, nct, pl.ctiles, pl.tiles, sc.items, counters, pl.n_tiles,
+                         pl.lsegs, segs, res, sc.cand, sc.lstate, sc.ghist);
+    else if (level == 1)
+      hipLaunchKernelGGL((k_hist<1>), grid, b, 0, s, nct, pl.ctiles, pl.tiles, sc.items, counters, pl.n_tiles,
+                         pl.lsegs, segs, res, sc.cand, sc.lstate, sc.ghist);
+    else
+      hipLaunchKernelGGL((k_hist<2>), grid, b, 0, s, nct, pl.ctiles, pl.tiles, sc.items, counters, pl.n_tiles,
+                         pl.lsegs, segs, res, sc.cand, sc.lstate, sc.ghist);
   }
   {
     ProfScope ps(prof, K_COUNT, s);
-    hipLaunchKernelGGL(k_count, grid, b, 0, s, nct, pl.ctiles, pl.tiles, sc.items, sc.counters, pl.n_tiles, res,
-                       sc.cand, sc.lstate, sc.tile_gt, sc.tile_eq);
+    hipLaunchKernelGGL(k_count, grid, b, 0, s, nct, pl.ctiles, pl.tiles, sc.items, counters, pl.n_tiles, res,
+                       sc.cand, sc.lstate, sc.ghist, sc.tile_gt, sc.tile_eq);
   }
   {
     ProfScope ps(prof, K_SCAN, s);
@@ -1435,7 +1448,7 @@ hipError_t launch_large(const LargePlan& pl, const Scratch& sc, const SegDesc* s
   }
   {
     ProfScope ps(prof, K_EMIT, s);
-    hipLaunchKernelGGL(k_emit, grid, b, 0, s, nct, pl.ctiles, pl.tiles, sc.items, sc.counters, pl.n_tiles, pl.lsegs,
+    hipLaunchKernelGGL(k_emit, grid, b, 0, s, nct, pl.ctiles, pl.tiles, sc.items, counters, pl.n_tiles, pl.lsegs,
                        segs, res, sc.cand, sc.lstate, sc.tile_gt, sc.tile_eq, out_idx, out_val);
   }
   return hipGetLastError();
