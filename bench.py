@@ -187,7 +187,11 @@ def main():
 
     # dominant kernel = largest total time; its algorithmic bytes per launch
     rho_mean = float(K) / float(total)
-    kel = dict((table_1 if args.per_worker else table_b).kernel_elements())
+    # elements each kernel covers in one step (per-worker mode: P calls over one worker's table)
+    if args.per_worker:
+        kel = {k: v * P for k, v in table_1.kernel_elements().items()}
+    else:
+        kel = dict(table_b.kernel_elements())
     kel.update({k: v for k, v in table_1.kernel_elements().items() if k == "k_merge"})
     dom_ms = prof[dom][0] / prof[dom][1]                 # average duration of one launch
     launches_per_step = prof[dom][1] / args.steps
@@ -201,7 +205,8 @@ def main():
     achieved = bpe * kel.get(dom, elements) / (dom_ms_per_step * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": (lambda t: None if t is None else t / launches_per_step)(measured_traffic(dom, wl.name, P)),
+                "traffic": (lambda t: None if t is None else t / launches_per_step)(
+                    None if args.per_worker else measured_traffic(dom, wl.name, P)),
                 "avg_kernel_ms": round(dom_ms, 4), "launches_per_step": launches_per_step,
                 "bytes_per_element": round(bpe, 4),
                 "elements_per_launch": kel.get(dom, elements) / launches_per_step}
