@@ -181,6 +181,18 @@ def main():
     for (off, d, r), code in zip(batched, routes):
         route_elems[route_names[code]] = route_elems.get(route_names[code], 0) + d
 
+    # Eq. 9 (Section 5) on a SYNTHETIC timing table: backpropagation time proportional to the layer
+    # size (2.8 ns per parameter, the paper's 0.391 s for its VGG-16), the sparsification overhead
+    # from this run's own rate, a 10 Gb/s network with 50 us start-up, P workers, c_u = 1000
+    ds = [d for (_, d, _) in layers]
+    per_elem_s = (t1 - t0) / args.steps / float(P * total)
+    t_comp = [2.8e-9 * d for d in ds]
+    t_spar = [per_elem_s * d for d in ds]
+    ta = time.perf_counter()
+    ada_k, _ = lags.lags_adaptive_ratios(50e-6, 0.8e-9, P, ds, t_comp, t_spar, 1000.0)
+    ada_us = (time.perf_counter() - ta) * 1e6
+    ada_c = [d / k for d, k in zip(ds, ada_k)]
+
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     elements = P * total
     value = elements / (ms_per_step * 1e-3)
@@ -242,6 +254,10 @@ def main():
                                        + prof2["k_merge_bounds"][0] / 2) / reps, 4),
             "delta_monitor_gbs": round(4.0 * P * total / (prof2["k_delta_tiles"][0] / reps * 1e-3) / 1e9, 1),
             "delta_max": float(np.nanmax(delta_host[:, 2])),
+            "adaptive_ratio": {"timing_table": "synthetic", "solver_us": round(ada_us, 1),
+                               "layers_at_cap": sum(1 for c in ada_c if c >= 999.0),
+                               "layers_below_cap": sum(1 for c in ada_c if c < 999.0),
+                               "min_ratio": round(min(ada_c), 2)},
         },
     }
     if not args.no_cpu_baseline:

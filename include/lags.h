@@ -133,6 +133,45 @@ int lags_delta_monitor(lags_ctx *ctx, const lags_table *t, const float *residual
                        int64_t res_stride, const int32_t *idx, const float *val, int32_t P,
                        int64_t stride_k, double *out3, void *hip_stream);
 
+/* Section 5, Eq. 9: the layer-wise adaptive choice of the compression ratio c^(l) = d^(l)/k^(l).
+ * Host only: no GPU work, no context.
+ *
+ * Layer l's sparse exchange is issued when its gradient is ready and overlaps the
+ * backpropagation of the layer computed next, layer l-1 (Section 3, pipelining).  Eq. 9 picks
+ * the smallest ratio whose exchange is hidden,
+ *     c^(l) = min{ c_u, min{ c : t_comm^(l)(c) + t_spar^(l) <= t_comp^(l-1) } }
+ * (the printed outer "max" with an upper bound c_u is read as "min"; an empty inner set gives
+ * c_u).  With c = d/k for an integer k this is the LARGEST k in [1, d] whose exchange fits,
+ * raised to at least ceil(d / c_u).
+ *
+ * The paper takes t_comm from "the communication model of the AllGather"; this library's model
+ * is a ring all-gather of one message per worker holding k (int32 index, float value) pairs:
+ *     t_comm(k) = (P - 1) * (alpha + 8 * k * beta)      seconds. */
+typedef struct {
+  double alpha; /* start-up time of one message, seconds, >= 0 */
+  double beta;  /* transfer time per byte, seconds, >= 0       */
+  int32_t P;    /* workers, >= 1                                */
+} lags_allgather_model;
+
+/* t_comm(k) of the model above, evaluated in double in exactly this order:
+ * ((double)(P-1)) * (alpha + (8.0 * (double)k) * beta).  NaN if net is NULL, P < 1 or k < 0. */
+double lags_allgather_seconds(const lags_allgather_model *net, int64_t k);
+
+/* Eq. 9 for n layers listed in forward order (layer 0 is computed last in backpropagation).
+ *   d[l]       elements of layer l, 1 <= d[l] < 2^31
+ *   t_comp[l]  backpropagation time of layer l, seconds, >= 0
+ *   t_spar[l]  sparsification overhead of layer l (compression + de-compression), seconds, >= 0
+ *   c_u        upper bound of the ratio, >= 1
+ * The budget of layer l is t_comp[l-1]; layer 0 has nothing left to hide behind (budget 0).
+ *   k_out[l]   the chosen k^(l)
+ *   rho_out[l] a density for which lags_topk_count(d[l], rho_out[l]) == k_out[l] exactly
+ *              (k/d, moved down by an ulp where the rounded product would give k+1);
+ *              may be NULL
+ * All arrays are host memory.  LAGS_EINVAL on a NULL pointer, a size out of range, a negative
+ * or NaN time, or c_u < 1 (nothing is written then). */
+int lags_adaptive_ratios(const lags_allgather_model *net, const int64_t *d, const double *t_comp,
+                         const double *t_spar, int32_t n, double c_u, int64_t *k_out, double *rho_out);
+
 /* Diagnostic: which route each layer took in the LAST lags_sparsify_model call made with
  * this table on this context (host-synchronous: waits for the device).  route[l], l in
  * [0, n): 0 = one-workgroup route (small layer); 1 = sampled threshold accepted, selection

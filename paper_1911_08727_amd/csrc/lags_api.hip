@@ -585,6 +585,51 @@ int lags_delta_monitor(lags_ctx* ctx, const lags_table* t, const float* residual
   return run_merge(MERGE_DELTA, ctx, t, idx, val, P, stride_k, nullptr, residual_flat, res_stride, out3, hip_stream);
 }
 
+double lags_allgather_seconds(const lags_allgather_model* net, int64_t k) {
+  if (!net || net->P < 1 || k < 0) return std::nan("");
+  return ((double)(net->P - 1)) * (net->alpha + (8.0 * (double)k) * net->beta);
+}
+
+int lags_adaptive_ratios(const lags_allgather_model* net, const int64_t* d, const double* t_comp,
+                         const double* t_spar, int32_t n, double c_u, int64_t* k_out, double* rho_out) {
+  if (!net || !d || !t_comp || !t_spar || !k_out || n < 1) return LAGS_EINVAL;
+  if (net->P < 1 || !(net->alpha >= 0.0) || !(net->beta >= 0.0) || !(c_u >= 1.0)) return LAGS_EINVAL;
+  for (int32_t l = 0; l < n; ++l)
+    if (d[l] < 1 || d[l] > 0x7FFFFFFFLL || !(t_comp[l] >= 0.0) || !(t_spar[l] >= 0.0)) return LAGS_EINVAL;
+  for (int32_t l = 0; l < n; ++l) {
+    const double budget = l == 0 ? 0.0 : t_comp[l - 1];
+    // t_comm is non-decreasing in k (products and sums of non-negative doubles are monotone), so
+    // the largest k that fits is found by bisection on the very predicate of Eq. 9
+    auto fits = [&](int64_t k) { return lags_allgather_seconds(net, k) + t_spar[l] <= budget; };
+    int64_t k_fit = 0;
+    if (fits(1)) {
+      if (fits(d[l])) {
+        k_fit = d[l];
+      } else {
+        int64_t lo = 1, hi = d[l];   // fits(lo), !fits(hi)
+        while (hi - lo > 1) {
+          const int64_t mid = lo + (hi - lo) / 2;
+          if (fits(mid)) lo = mid; else hi = mid;
+        }
+        k_fit = lo;
+      }
+    }
+    int64_t k_min = (int64_t)std::ceil((double)d[l] / c_u);   // c = d/k <= c_u
+    if (k_min < 1) k_min = 1;
+    if (k_min > d[l]) k_min = d[l];
+    const int64_t k = std::max(k_fit, k_min);
+    k_out[l] = k;
+    if (rho_out) {
+      double rho = (double)k / (double)d[l];
+      if (rho > 1.0) rho = 1.0;
+      for (int guard = 0; guard < 64 && lags_topk_count(d[l], rho) > k; ++guard) rho = std::nextafter(rho, 0.0);
+      for (int guard = 0; guard < 64 && lags_topk_count(d[l], rho) < k; ++guard) rho = std::nextafter(rho, 1.0);
+      rho_out[l] = rho;
+    }
+  }
+  return LAGS_OK;
+}
+
 int lags_last_routes(lags_ctx* ctx, const lags_table* t, int32_t* route, int32_t n) {
   if (!ctx || !t || t->ctx != ctx || !route || n != t->n) return LAGS_EINVAL;
   DeviceGuard g(ctx->device);

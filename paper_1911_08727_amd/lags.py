@@ -16,6 +16,10 @@ class LayerDesc(ctypes.Structure):
     _fields_ = [("offset", ctypes.c_int64), ("d", ctypes.c_int64), ("rho", ctypes.c_double)]
 
 
+class AllgatherModel(ctypes.Structure):
+    _fields_ = [("alpha", ctypes.c_double), ("beta", ctypes.c_double), ("P", ctypes.c_int32)]
+
+
 _lib = None
 
 
@@ -64,6 +68,12 @@ def lib():
         L.lags_profile_reset.restype, L.lags_profile_reset.argtypes = ctypes.c_int, [vp]
         L.lags_profile_kernel_elements.restype = i64
         L.lags_profile_kernel_elements.argtypes = [vp, ctypes.c_int]
+        L.lags_allgather_seconds.restype = dbl
+        L.lags_allgather_seconds.argtypes = [ctypes.POINTER(AllgatherModel), i64]
+        L.lags_adaptive_ratios.restype = ctypes.c_int
+        L.lags_adaptive_ratios.argtypes = [ctypes.POINTER(AllgatherModel), ctypes.POINTER(i64),
+                                           ctypes.POINTER(dbl), ctypes.POINTER(dbl), i32, dbl,
+                                           ctypes.POINTER(i64), ctypes.POINTER(dbl)]
         _lib = L
     return _lib
 
@@ -92,6 +102,24 @@ def _stream(stream):
 
 def lags_topk_count(d, rho):
     return int(lib().lags_topk_count(int(d), float(rho)))
+
+
+def lags_allgather_seconds(alpha, beta, P, k):
+    net = AllgatherModel(float(alpha), float(beta), int(P))
+    return float(lib().lags_allgather_seconds(ctypes.byref(net), int(k)))
+
+
+def lags_adaptive_ratios(alpha, beta, P, d, t_comp, t_spar, c_u):
+    """Host lists in, (k list, rho list) out."""
+    n = len(d)
+    net = AllgatherModel(float(alpha), float(beta), int(P))
+    dd = (ctypes.c_int64 * n)(*[int(x) for x in d])
+    tc = (ctypes.c_double * n)(*[float(x) for x in t_comp])
+    ts = (ctypes.c_double * n)(*[float(x) for x in t_spar])
+    k = (ctypes.c_int64 * n)()
+    rho = (ctypes.c_double * n)()
+    _check(lib().lags_adaptive_ratios(ctypes.byref(net), dd, tc, ts, n, float(c_u), k, rho), "lags_adaptive_ratios")
+    return list(k), list(rho)
 
 
 class Table:
