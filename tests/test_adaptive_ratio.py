@@ -136,3 +136,43 @@ def test_library_rejects_bad_arguments(lags):
                      ("d", [1 << 31]), ("t_comp", [-1.0]), ("t_spar", [float("nan")])):
         with pytest.raises(LagsError):
             lags.lags_adaptive_ratios(**dict(good, **{key: bad}))
+
+
+# ---------------------------------------------------------------- the pins have teeth
+ORACLE_PINS = [test_hand_worked_example, test_closed_form_inversion_on_exact_numbers,
+               test_limits_and_monotonicity, test_layer_pipeline_order]
+
+ORACLE_MUTANTS = {
+    "all_P_workers_send": ("return float(P - 1) *", "return float(P) *"),
+    "four_bytes_per_pair": ("(8.0 * float(k))", "(4.0 * float(k))"),
+    "no_startup_cost": ("(alpha + (8.0 * float(k)) * beta)", "((8.0 * float(k)) * beta)"),
+    "overhead_ignored": ("+ t_spar <= budget", "<= budget"),
+    "strict_inequality": ("+ t_spar <= budget", "+ t_spar < budget"),
+    "smallest_k_that_fits": ("for k in range(d, 0, -1):", "for k in range(1, d + 1):"),
+    "cap_is_a_lower_bound_of_the_ratio": ("return max(k_fit, k_cap)", "return min(k_fit, k_cap) if k_fit else k_cap"),
+    "cap_rounded_down": ("int(math.ceil(float(d) / c_u))", "int(math.floor(float(d) / c_u))"),
+    "hides_behind_its_own_backprop": ("budget = 0.0 if l == 0 else t_comp[l - 1]", "budget = t_comp[l]"),
+    "hides_behind_the_layer_above": ("budget = 0.0 if l == 0 else t_comp[l - 1]",
+                                     "budget = 0.0 if l == len(d) - 1 else t_comp[l + 1]"),
+}
+
+
+@pytest.mark.parametrize("name", sorted(ORACLE_MUTANTS))
+def test_oracle_mutant_is_caught(name, monkeypatch):
+    """Each plausible mistake, planted in a copy of the oracle's source, fails some pin above."""
+    import sys
+    import types
+    old, new = ORACLE_MUTANTS[name]
+    src = open(ora.__file__).read()
+    assert src.count(old) == 1, "mutation site not found: %s" % name
+    mutant = types.ModuleType("adaptive_ratio_mutant")
+    exec(compile(src.replace(old, new), "mutant_" + name, "exec"), mutant.__dict__)
+    monkeypatch.setattr(sys.modules[__name__], "ora", mutant)
+    caught = False
+    for pin in ORACLE_PINS:
+        try:
+            pin()
+        except (AssertionError, ZeroDivisionError):
+            caught = True
+            break
+    assert caught, "no pin notices mutant %s" % name
