@@ -33,6 +33,12 @@ constexpr int kSmall2 = 16 * 10 * 256;   // <= 40960 : 16 waves, 10 rounds
 constexpr int kSamplePiece = 64;
 constexpr int kSamplePieces = 256;
 constexpr int kSampleMax = kSamplePiece * kSamplePieces;   // 16384 sampled elements
+// Layers that keep many entries (k >= kBigSampleK) of many elements take four times the sample:
+// the threshold is then tighter (about 1.6 k candidates instead of 2.5 k at rho = 0.001), which
+// saves more candidate traffic than the larger sample costs.
+constexpr int kSamplePiecesBig = 1024;                     // 65536 sampled elements
+constexpr int kBigSampleK = 8192;
+constexpr int64_t kBigSampleD = 1 << 20;
 constexpr int kSlotMin = 256;            // candidate slots per tile of a sampled layer: the table uses the
 constexpr int kSlotMax = 2048;           // smallest power of two >= 8x the expected count of any layer
 constexpr int kDenseGrid = 1024;         // workgroups of the fallback kernels (grid-stride)
@@ -115,6 +121,7 @@ struct LState {         // per call, per large layer
 struct LargePlan {      // everything launch_large needs (device pointers + counts)
   int n_large = 0, n_tiles = 0, n_sampled = 0, n_chunks = 0, n_ctiles = 0;
   int slot = kSlotMin;                  // candidate slots per sampled tile
+  bool big_sample = false;              // some layer uses the large sample
   int n_cand_small[3] = {0, 0, 0};
   const LargeSeg* lsegs = nullptr;
   const TileDesc* tiles = nullptr;      // dense tiles

@@ -118,6 +118,16 @@ __device__ __forceinline__ void block_find_bucket(const uint32_t* hist, int nb, 
   __syncthreads();
 }
 
+// Histogram update where many lanes may hit the same bin: lanes that share lane 0's bin
+// are counted with one ballot and a single LDS add; the others add individually.
+// b = 0xFFFFFFFF: the lane has nothing to add.  Must be called by all 64 lanes.
+__device__ __forceinline__ void hist_add_peeled(uint32_t* s_hist, uint32_t b, int lane) {
+  const uint32_t f = (uint32_t)__builtin_amdgcn_readfirstlane((int)b);
+  const uint64_t same = __ballot(b == f);
+  if (lane == 0 && f != 0xFFFFFFFFu) atomicAdd(&s_hist[f], (uint32_t)__popcll(same));
+  if (b != f && b != 0xFFFFFFFFu) atomicAdd(&s_hist[b], 1u);
+}
+
 // Exact radix select over keys held in registers by a whole workgroup: finds the k-th
 // largest key T and the number of entries equal to T that belong to the top k.
 // s_hist: kBins0 words, s_wt: NT/64 words, s_sel: 2 words.
@@ -318,16 +328,6 @@ __device__ __forceinline__ bool aligned16(const void* a, const void* b) {
   return ((reinterpret_cast<uintptr_t>(a) | reinterpret_cast<uintptr_t>(b)) & 15u) == 0;
 }
 
-// Histogram update where many lanes may hit the same bin: lanes that share lane 0's bin
-// are counted with one ballot and a single LDS add; the others add individually.
-// b = 0xFFFFFFFF: the lane has nothing to add.  Must be called by all 64 lanes.
-__device__ __forceinline__ void hist_add_peeled(uint32_t* s_hist, uint32_t b, int lane) {
-  const uint32_t f = (uint32_t)__builtin_amdgcn_readfirstlane((int)b);
-  const uint64_t same = __ballot(b == f);
-  if (lane == 0 && f != 0xFFFFFFFFu) atomicAdd(&s_hist[f], (uint32_t)__popcll(same));
-  if (b != f && b != 0xFFFFFFFFu) atomicAdd(&s_hist[b], 1u);
-}
-
 __device__ __forceinline__ uint32_t mix32(uint32_t x) {
   x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
   return x;
@@ -411,23 +411,17 @@ __global__ __launch_bounds__(NW * 64) void k_small(const SegDesc* __restrict__ s
 }
 
 // ------------------------------------------------------------------ sample ---
-// Threshold guess for one large layer: form acc on up to 256 pieces of 64 consecutive
+// Threshold guess for one large layer: form acc on up to 64*V pieces of 64 consecutive
 // elements spread over the layer (with a hashed offset inside each stride), and take the
 // sample's `sample_rank`-th largest key as tau and its `sample_rank_hi`-th largest (the
-// sample's estimate of the layer's k-th largest) as tau_hi.  Missing sample slots count as key 0.
-__global__ __launch_bounds__(1024) void k_sample(const SegDesc* __restrict__ segs,
-                                                 const int32_t* __restrict__ sampled,
-                                                 const LargeSeg* __restrict__ lsegs,
-                                                 const float* __restrict__ grad,
-                                                 const float* __restrict__ res, float lr,
-                                                 LState* __restrict__ lstate) {
-  constexpr int NW = 16, V = kSamplePieces / 64, NT = 1024;  // a wave takes 4 pieces per round
-  __shared__ uint32_t s_hist[kBins0];
-  __shared__ uint32_t s_wt[NW];
-  __shared__ uint32_t s_sel[2];
-  const int li = sampled[blockIdx.x];
-  const LargeSeg ls = lsegs[li];
-  const SegDesc sd = segs[ls.seg];
+// sample's estimate of the layer's k-th largest) as tau_hi.  Missing sample slots count as
+// key 0.
+template <int V>
+__device__ __forceinline__ void sample_layer(const LargeSeg& ls, int li, const SegDesc& sd,
+                                             const float* __restrict__ grad, const float* __restrict__ res,
+                                             float lr, LState* __restrict__ lstate, uint32_t* s_hist,
+                                             uint32_t* s_wt, uint32_t* s_sel) {
+  constexpr int NT = 1024;  // 16 waves; a wave takes 4 pieces per round
   const int tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
   const float* g = grad + sd.offset;
   const float* r = res + sd.offset;
@@ -466,6 +460,27 @@ __global__ __launch_bounds__(1024) void k_sample(const SegDesc* __restrict__ seg
     lstate[li].tau = T;
     lstate[li].tau_hi = Thi;  // >= T because sample_rank_hi <= sample_rank
   }
+}
+
+// One workgroup per sampled layer.  BIG: the table holds layers with the large sample
+// (more than kSamplePieces pieces); those workgroups take the V = 16 path.
+template <bool BIG>
+__global__ __launch_bounds__(1024) void k_sample(const SegDesc* __restrict__ segs,
+                                                 const int32_t* __restrict__ sampled,
+                                                 const LargeSeg* __restrict__ lsegs,
+                                                 const float* __restrict__ grad,
+                                                 const float* __restrict__ res, float lr,
+                                                 LState* __restrict__ lstate) {
+  __shared__ uint32_t s_hist[kBins0];
+  __shared__ uint32_t s_wt[16];
+  __shared__ uint32_t s_sel[2];
+  const int li = sampled[blockIdx.x];
+  const LargeSeg ls = lsegs[li];
+  const SegDesc sd = segs[ls.seg];
+  if (BIG && ls.sample_pieces > kSamplePieces)  // uniform over the workgroup
+    sample_layer<kSamplePiecesBig / 64>(ls, li, sd, grad, res, lr, lstate, s_hist, s_wt, s_sel);
+  else
+    sample_layer<kSamplePieces / 64>(ls, li, sd, grad, res, lr, lstate, s_hist, s_wt, s_sel);
 }
 
 // ------------------------------------------------------------------ stream ---
@@ -1382,8 +1397,12 @@ hipError_t launch_large(const LargePlan& pl, const Scratch& sc, const SegDesc* s
   if (e != hipSuccess) return e;
   if (pl.n_sampled > 0) {
     ProfScope ps(prof, K_SAMPLE, s);
-    hipLaunchKernelGGL(k_sample, dim3(pl.n_sampled), dim3(1024), 0, s, segs, pl.sampled, pl.lsegs, grad, res, lr,
-                       sc.lstate);
+    if (pl.big_sample)
+      hipLaunchKernelGGL((k_sample<true>), dim3(pl.n_sampled), dim3(1024), 0, s, segs, pl.sampled, pl.lsegs, grad,
+                         res, lr, sc.lstate);
+    else
+      hipLaunchKernelGGL((k_sample<false>), dim3(pl.n_sampled), dim3(1024), 0, s, segs, pl.sampled, pl.lsegs, grad,
+                         res, lr, sc.lstate);
   }
   {
     const int nl = (pl.n_tiles + kStreamLaunchTiles - 1) / kStreamLaunchTiles;
