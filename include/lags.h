@@ -22,6 +22,11 @@
  *     `hip_stream` before the call and before everything enqueued on it after the call.
  *   - Argument validation happens before anything is enqueued: on an error return
  *     no output buffer has been touched.
+ *   - The sparsify, merge, apply and delta calls may be recorded into a HIP graph by stream
+ *     capture (they enqueue kernels and event waits only, no memset and no copy), provided a
+ *     call with the same table (and, for the merge-type calls, a P at least as large) has run
+ *     outside capture before: that first call sizes the context's scratch with synchronous
+ *     allocations.  Timing (lags_profile_*) must be off while capturing.
  *   - A context owns scratch memory only (histograms, counters, candidate lists);
  *     nothing in it influences results.  One context serves one stream at a time:
  *     calls on the same context must be ordered on one stream (or externally).

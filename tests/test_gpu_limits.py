@@ -166,3 +166,62 @@ def test_merge_worker_limit_and_rejected_arguments(gpu, oracle):
     with pytest.raises(lags.LagsError):
         gpu.ctx.table([(0, 2 ** 31, 0.5)])                                        # beyond int32 indices
     table.destroy()
+
+
+def test_hip_graph_replay_matches_eager_and_oracle(gpu, oracle):
+    """One step (batched sparsify of P workers + merge) captured into a HIP graph after a warm-up
+    call has sized the scratch; every replay, with eager work and synchronisations of the program
+    between the replays, equals the eager calls and the oracle bit for bit.  The capture includes
+    the fork to and join from the context's side stream and uses clearing kernels, no memset."""
+    torch = gpu.torch
+    rng = np.random.default_rng(77)
+    sizes = [(100, 0.01), (300_000, 0.002), (60_000, 0.6), (9000, 0.001), (2_200_000, 0.01), (1 << 20, 0.001)]
+    layers, off = [], 0
+    for d, rho in sizes:
+        layers.append((off, d, rho))
+        off += d
+    total, P, lr = off, 2, 0.1
+    batched = [(p * total + o, d, r) for p in range(P) for (o, d, r) in layers]
+    tb, t1 = gpu.ctx.table(batched), gpu.ctx.table(layers)
+    K = t1.total_k
+    g_host = rng.standard_normal(P * total).astype(np.float32)
+    r_host = (0.1 * rng.standard_normal(P * total)).astype(np.float32)
+    grad, res0 = gpu.to_dev(g_host), gpu.to_dev(r_host)
+    res = res0.clone()
+    idx = torch.empty(P * K, dtype=torch.int32, device=gpu.dev)
+    val = torch.empty(P * K, dtype=torch.float32, device=gpu.dev)
+    upd = torch.empty(total, dtype=torch.float32, device=gpu.dev)
+    note("graph test: warm-up call outside capture")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        gpu.ctx.lags_sparsify_model(tb, grad, res, lr, idx, val, side)
+        gpu.ctx.lags_merge_sparse(t1, idx, val, P, K, upd, side)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    res.copy_(res0)
+    note("graph test: capture")
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        st = torch.cuda.current_stream()
+        gpu.ctx.lags_sparsify_model(tb, grad, res, lr, idx, val, st)
+        gpu.ctx.lags_merge_sparse(t1, idx, val, P, K, upd, st)
+    res_cpu = [r_host[p * total:(p + 1) * total].copy() for p in range(P)]
+    for it in range(3):
+        note("graph test: replay %d" % it)
+        graph.replay()
+        torch.cuda.synchronize()
+        _ = float((grad * 2.0).sum().item())          # eager work between the replays
+        want_i, want_v = np.empty(P * K, np.int32), np.empty(P * K, np.float32)
+        for p in range(P):
+            wi, wv = oracle_model_parallel(oracle, layers, g_host[p * total:(p + 1) * total], res_cpu[p], lr)
+            want_i[p * K:(p + 1) * K], want_v[p * K:(p + 1) * K] = wi, wv
+        want_u = np.zeros(total, np.float32)
+        oracle.merge_sparse(layers, want_i, want_v, P, K, want_u)
+        assert_same("idx replay %d" % it, idx.cpu().numpy(), want_i)
+        assert_same("val replay %d" % it, val.cpu().numpy(), want_v)
+        assert_same("res replay %d" % it, res.cpu().numpy(), np.concatenate(res_cpu))
+        assert_same("update replay %d" % it, upd.cpu().numpy(), want_u)
+    del graph
+    tb.destroy()
+    t1.destroy()
