@@ -138,9 +138,13 @@ void free_table_device(lags_table* t) {
 // get.  Returns false if the layer is not worth sampling (k too large for the slots).
 bool plan_sample(int64_t d, int64_t k, LargeSeg* ls, double* per_tile) {
   int64_t pieces, stride;
+  int64_t piece_len = kSamplePiece;
+  ls->sample_big = 0;
   if (d >= kBigSampleD && k >= kBigSampleK) {
-    pieces = kSamplePiecesBig;
-    stride = d / kSamplePiecesBig;
+    pieces = kSamplePieces;
+    stride = d / kSamplePieces;
+    piece_len = kSamplePieceBig;
+    ls->sample_big = 1;
   } else if (d >= kSampleMax) {
     pieces = kSamplePieces;
     stride = d / kSamplePieces;
@@ -148,7 +152,7 @@ bool plan_sample(int64_t d, int64_t k, LargeSeg* ls, double* per_tile) {
     pieces = (d + kSamplePiece - 1) / kSamplePiece;
     stride = kSamplePiece;
   }
-  const double m = (double)std::min<int64_t>(d, pieces * kSamplePiece);
+  const double m = (double)std::min<int64_t>(d, pieces * piece_len);
   const double fk = (double)k * m / (double)d;
   // the sample's rank-j key admits about j/m of the layer; j is fk plus four standard
   // deviations of the sampled count plus a constant: fewer than k candidates (which only
@@ -225,7 +229,7 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
         double per_tile = 0.0;
         const bool sampled_layer = plan_sample(d[l], k[l], &ls, &per_tile);
         if (sampled_layer) max_per_tile = std::max(max_per_tile, per_tile);
-        if (sampled_layer && ls.sample_pieces > kSamplePieces) t->plan.big_sample = true;
+        if (sampled_layer && ls.sample_big) t->plan.big_sample = true;
         if (sampled_layer && any_cand_large) ls.cand_class = CAND_LARGE;
         ls.tile_begin = (int32_t)tiles.size();
         const int64_t nt = (d[l] + kTile - 1) / kTile;

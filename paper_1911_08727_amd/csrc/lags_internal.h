@@ -36,7 +36,7 @@ constexpr int kSampleMax = kSamplePiece * kSamplePieces;   // 16384 sampled elem
 // Layers that keep many entries (k >= kBigSampleK) of many elements take four times the sample:
 // the threshold is then tighter (about 1.6 k candidates instead of 2.5 k at rho = 0.001), which
 // saves more candidate traffic than the larger sample costs.
-constexpr int kSamplePiecesBig = 1024;                     // 65536 sampled elements
+constexpr int kSamplePieceBig = 256;                       // 256 pieces x 256 = 65536 sampled elements
 constexpr int kBigSampleK = 8192;
 constexpr int64_t kBigSampleD = 1 << 20;
 constexpr int kSlotMin = 256;            // candidate slots per tile of a sampled layer: the table uses the
@@ -102,6 +102,7 @@ struct LargeSeg {       // static plan of one large layer
   int32_t sample_rank_hi;  // rank of the sample key used as tau_hi (0: none): about k's share of the sample
   int32_t sample_pieces;
   int32_t sample_stride;
+  int32_t sample_big;   // 1: pieces of kSamplePieceBig elements (the large sample), 0: of kSamplePiece
 };
 
 enum : uint32_t { MODE_DENSE = 0, MODE_SPARSE = 1 };
