@@ -55,11 +55,12 @@ def _check_properties(torch, wl, layers, ks, pos, P, total, K, acc, res, idx, va
                     assert int(ties_kept.max()) < int(ties_dropped.min()), "tie rule violated"
 
 
-def _run_full(name, big_once=()):
+def _run_full(name, big_once=(), rho_override=None, iters=None):
     import torch
     import oracle
     from paper_1911_08727_amd import lags
-    wl = workloads.make(name)
+    wl = workloads.make(name, rho_override=rho_override)
+    n_iters = iters or wl.iters
     dev = torch.device("cuda:0")
     P, total, layers = wl.P, wl.total_d, wl.layers()
     batched = [(p * total + off, d, r) for p in range(P) for (off, d, r) in layers]
@@ -77,7 +78,7 @@ def _run_full(name, big_once=()):
     param = torch.randn(total, dtype=torch.float32, device=dev, generator=torch.Generator(device=dev).manual_seed(7))
     delta = torch.empty(3 * len(layers), dtype=torch.float64, device=dev)
     fell_back = 0
-    for it in range(wl.iters):
+    for it in range(n_iters):
         note("%s iteration %d: generate" % (name, it))
         for p in range(P):
             workloads.grad_torch(wl, it, p, dev, out=grad[p * total:(p + 1) * total])
@@ -102,7 +103,7 @@ def _run_full(name, big_once=()):
         torch.cuda.synchronize()
         assert_same("param it=%d" % it, param.cpu().numpy(), want_v)
 
-        if it == wl.iters - 1:
+        if it == n_iters - 1:
             note("%s iteration %d: delta metric vs oracle" % (name, it))
             ctx.lags_delta_monitor(t1, res, total, idx, val, P, K, delta)
             torch.cuda.synchronize()
@@ -119,7 +120,7 @@ def _run_full(name, big_once=()):
 
         # the oracle on one worker's layers (the largest ones only where listed in big_once)
         p = (it * 5 + 3) % P
-        sub = [l for l, (_, d, _) in enumerate(layers) if d <= 20_000_000 or (l in big_once and it == wl.iters - 1)]
+        sub = [l for l, (_, d, _) in enumerate(layers) if d <= 20_000_000 or (l in big_once and it == n_iters - 1)]
         note("%s iteration %d: oracle on worker %d, %d layers" % (name, it, p, len(sub)))
         sub_layers = [layers[l] for l in sub]
         g_h = grad[p * total:(p + 1) * total].cpu().numpy()
@@ -145,6 +146,13 @@ def test_vgg16_full():
     [0.001, 0.01], P = 16, 5 iterations.  fc1 (102.8M elements) goes through the oracle once."""
     fell_back = _run_full("vgg16", big_once=(26,))
     assert fell_back == 0, "a sampled layer fell back to the multi-pass route on smooth data"
+
+
+def test_vgg16_at_the_benchmarked_density():
+    """The workload bench.py times by default: the VGG-16-shaped table with rho = 0.001 for every
+    layer, P = 16 in one batched table (nine streaming launches, large samples for the two
+    biggest layers of every worker), two iterations."""
+    assert _run_full("vgg16", rho_override=0.001, iters=2) == 0
 
 
 def test_resnet50_full():
