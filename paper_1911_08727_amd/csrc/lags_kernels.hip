@@ -1245,10 +1245,12 @@ __global__ __launch_bounds__(256) void k_merge(const TileDesc* __restrict__ mtil
   __shared__ uint32_t s_start[257];
   __shared__ int32_t s_lo[256];
   __shared__ uint32_t s_wt[4];
+  __shared__ uint32_t s_claim[APPLY ? kMergeTile / 32 : 1];
   const TileDesc td = mtiles[blockIdx.x];
   const SegDesc sd = segs[td.seg];
   const int tid = threadIdx.x;
   const int slot = (int)blockIdx.x + td.seg;  // every earlier layer owns one extra (end) slot
+  if (APPLY) s_claim[tid] = 0u;  // kMergeTile / 32 = 256 words; the accumulation's barriers order this
   const uint32_t entries =
       merge_accumulate<float>(s_acc, s_start, s_lo, s_wt, td, sd, slot, idx, val, P, stride_k, nb, bounds);
   // sum / P: for P a power of two the product with 1/P is the same binary32 value as the
@@ -1260,6 +1262,33 @@ __global__ __launch_bounds__(256) void k_merge(const TileDesc* __restrict__ mtil
   float* u = out + td.start;
   if (APPLY) {
     if (entries == 0) return;  // uniform over the workgroup
+    if (P <= 256) {
+      // One pass of the accumulation covered all workers, so its entry table (s_start, s_lo) is
+      // still valid: walk the entries again and let the first thread that claims an element's
+      // bit apply the element's sum.  Touches the selected elements only, in one round trip.
+      const uint32_t total = s_start[256];
+      for (uint32_t base = 0; base < total; base += 256) {
+        const uint32_t e = base + (uint32_t)tid;
+        if (e < total) {
+          int a = 0, z = P;  // last worker q with s_start[q] <= e
+          while (a < z) {
+            const int mid = (a + z) >> 1;
+            if (s_start[mid] <= e) a = mid + 1; else z = mid;
+          }
+          const int q = a - 1;
+          const int64_t gi = (int64_t)q * stride_k + sd.out_offset + s_lo[q] + (int)(e - s_start[q]);
+          const uint32_t off = (uint32_t)(idx[gi] - td.local0);
+          if (off < (uint32_t)td.n) {
+            const uint32_t bit = 1u << (off & 31u);
+            if (!(atomicOr(&s_claim[off >> 5], bit) & bit)) {
+              const float sacc = s_acc[off];
+              if (sacc != 0.0f) u[off] = __fsub_rn(u[off], pow2 ? __fmul_rn(sacc, inv) : __fdiv_rn(sacc, fp));
+            }
+          }
+        }
+      }
+      return;
+    }
     for (int e = tid; e < td.n; e += 256) {
       const float sacc = s_acc[e];
       if (sacc != 0.0f) u[e] = __fsub_rn(u[e], pow2 ? __fmul_rn(sacc, inv) : __fdiv_rn(sacc, fp));
