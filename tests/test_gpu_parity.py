@@ -346,6 +346,59 @@ def test_random_tables(gpu, oracle):
         table.destroy()
 
 
+def _large_values(kind, d, rng):
+    if kind == "laplace":
+        return rng.laplace(size=d).astype(np.float32)
+    if kind == "sparse":                      # 3 % non-zero
+        x = rng.standard_normal(d).astype(np.float32)
+        x[rng.random(d) < 0.97] = 0.0
+        return x
+    if kind == "clustered":                   # 50000 consecutive entries 80 times larger
+        x = rng.standard_normal(d).astype(np.float32)
+        s = int(rng.integers(0, max(1, d - 50000)))
+        x[s:s + 50000] *= 80.0
+        return x
+    if kind == "rows":                        # four of five rows of 1500 are zero (an embedding gradient)
+        x = rng.standard_normal(d).astype(np.float32)
+        x[(np.arange(d) // 1500) % 5 != 0] = 0.0
+        return x
+    return _values(kind, d, rng)
+
+
+def test_random_tables_of_large_layers(gpu, oracle):
+    """Seeded random tables of layers between 41,000 and 9 million elements (the large sample for
+    k >= 8192, candidate lists of every size class, rejected guesses, layers that are not sampled),
+    unaligned offsets, eight value distributions, two iterations with error feedback."""
+    kinds = ["normal", "laplace", "ties", "sparse", "narrow", "zeros", "clustered", "rows"]
+    seen = set()
+    for case in range(8):
+        rng = np.random.default_rng(9100 + case)
+        n = int(rng.integers(1, 4))
+        layers, off = [], int(rng.integers(0, 3)) * 4
+        for _ in range(n):
+            d = int(rng.choice([rng.integers(41000, 300000), rng.integers(1 << 20, 3 << 20),
+                                rng.integers(3 << 20, 9 << 20)]))
+            rho = float(rng.choice([1e-4, 1e-3, 2e-3, 5e-3, 0.01, 0.03, 0.1, 0.3]))
+            layers.append((off, d, rho))
+            off += d + int(rng.integers(0, 3)) * 4
+        total = off
+        table = gpu.ctx.table(layers)
+        res_g, res_c = np.zeros(total, np.float32), np.zeros(total, np.float32)
+        for it in range(2):
+            g = np.zeros(total, np.float32)
+            for (o, d, _) in layers:
+                g[o:o + d] = _large_values(str(rng.choice(kinds)), d, rng)
+            note("large random table %d iteration %d: %r" % (case, it, layers))
+            wi, wv = oracle_model_parallel(oracle, layers, g, res_c, 0.5)
+            gi, gv, res_g = gpu.sparsify_model(layers, g, res_g, 0.5, table=table)
+            assert_same("idx case=%d it=%d" % (case, it), gi, wi)
+            assert_same("val case=%d it=%d" % (case, it), gv, wv)
+            assert_same("res case=%d it=%d" % (case, it), res_g, res_c)
+            seen.update(gpu.ctx.lags_last_routes(table))
+        table.destroy()
+    assert {1, 2, 3} <= seen, seen       # every route of the large path was taken
+
+
 def test_merge_closed_forms(gpu, oracle):
     """P = 1 is a scatter; many workers on one index sum in worker order; division is a
     true division (P = 3, 7); indices spread over several merge tiles; P beyond one batch of 256."""
