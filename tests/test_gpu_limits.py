@@ -225,3 +225,50 @@ def test_hip_graph_replay_matches_eager_and_oracle(gpu, oracle):
     del graph
     tb.destroy()
     t1.destroy()
+
+
+def test_two_contexts_on_two_streams(gpu, oracle):
+    """Two contexts, each on a stream of its own, enqueue their steps without waiting for each
+    other (a context holds all scratch; nothing is shared between contexts): both results equal
+    the oracle."""
+    torch = gpu.torch
+    from paper_1911_08727_amd import lags
+    rng = np.random.default_rng(78)
+    sizes = [(500, 0.01), (700_000, 0.002), (50_000, 0.5), (1_500_000, 0.01), (45_000, 0.001)]
+    layers, off = [], 0
+    for d, rho in sizes:
+        layers.append((off, d, rho))
+        off += d
+    total = off
+    ctxs = [gpu.ctx, lags.Context(0)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    tables = [c.table(layers) for c in ctxs]
+    K = tables[0].total_k
+    g_host = [rng.standard_normal(total).astype(np.float32) for _ in ctxs]
+    r_host = [(0.2 * rng.standard_normal(total)).astype(np.float32) for _ in ctxs]
+    grad = [gpu.to_dev(g) for g in g_host]
+    res = [gpu.to_dev(r) for r in r_host]
+    idx = [torch.empty(K, dtype=torch.int32, device=gpu.dev) for _ in ctxs]
+    val = [torch.empty(K, dtype=torch.float32, device=gpu.dev) for _ in ctxs]
+    upd = [torch.empty(total, dtype=torch.float32, device=gpu.dev) for _ in ctxs]
+    torch.cuda.synchronize()
+    note("two contexts: enqueue three steps each, interleaved")
+    for it in range(3):
+        for i in (0, 1):
+            with torch.cuda.stream(streams[i]):
+                ctxs[i].lags_sparsify_model(tables[i], grad[i], res[i], 0.3, idx[i], val[i], streams[i])
+                ctxs[i].lags_merge_sparse(tables[i], idx[i], val[i], 1, K, upd[i], streams[i])
+    torch.cuda.synchronize()
+    for i in (0, 1):
+        rc = r_host[i].copy()
+        for it in range(3):
+            wi, wv = oracle_model_parallel(oracle, layers, g_host[i], rc, 0.3)
+        want_u = np.zeros(total, np.float32)
+        oracle.merge_sparse(layers, wi, wv, 1, K, want_u)
+        assert_same("idx ctx %d" % i, idx[i].cpu().numpy(), wi)
+        assert_same("val ctx %d" % i, val[i].cpu().numpy(), wv)
+        assert_same("res ctx %d" % i, res[i].cpu().numpy(), rc)
+        assert_same("update ctx %d" % i, upd[i].cpu().numpy(), want_u)
+    for t in tables:
+        t.destroy()
+    ctxs[1].destroy()
