@@ -58,6 +58,29 @@ def cpu_baseline(wl, grad0_host, threads):
     return wl.total_d / dt, dt
 
 
+def cpu_baseline_extras(wl, grad0_host, idx_host, val_host, P, K):
+    """Two more oracle timings for context: the sparsifier on one host thread (the second largest
+    layer of worker 0 only, to bound the time) and the merge of the P workers' pairs (one thread)."""
+    import numpy as np
+    import oracle
+    layers = wl.layers()
+    order = sorted(range(len(layers)), key=lambda l: -layers[l][1])
+    l = order[1] if len(order) > 1 else order[0]
+    off, d, rho = layers[l]
+    g = np.ascontiguousarray(grad0_host[off:off + d])
+    r = np.zeros(d, np.float32)
+    t0 = time.perf_counter()
+    oracle.sparsify_layer(g, r, wl.lr, oracle.topk_count(d, rho))
+    t_one = time.perf_counter() - t0
+    upd = np.empty(wl.total_d, np.float32)
+    t0 = time.perf_counter()
+    oracle.merge_sparse(layers, idx_host, val_host, P, K, upd)
+    t_merge = time.perf_counter() - t0
+    return {"single_thread_value": d / t_one, "single_thread_sample": "layer %d of worker 0 (%d elements), %.1f s" % (l, d, t_one),
+            "merge_value": wl.total_d / t_merge, "merge_unit": "update elements/s",
+            "merge_sample": "all %d layers, P = %d, one thread, %.2f s" % (len(layers), P, t_merge)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -228,6 +251,23 @@ def main():
     sparsify_ms = call_ms
     merge_ms = sum(prof_all.get(k, (0.0, 0))[0] for k in merge_names) / n_table
 
+    # the practical ceiling beside the spec-sheet peak: a plain device copy of one worker's array
+    ca = torch.empty(total, dtype=torch.float32, device=dev).normal_()
+    cb = torch.empty_like(ca)
+    for _ in range(2):
+        cb.copy_(ca)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(10):
+        cb.copy_(ca)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 10 * 8.0 * total / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del ca, cb
+    traffic = roofline["traffic"]
+    measured_gbs = None if traffic is None else traffic / (dom_ms * 1e-3) / 1e9
+
     out = {
         "metric": "sparsified elements/s, per-layer top-k + error feedback (P workers) + merge",
         "value": value, "unit": "elements/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -245,6 +285,17 @@ def main():
                                                            (sparsify_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
                             if sparsify_ms > 0 else None},
         "sparsify_call_ms": round(call_ms, 4),
+        "sparsify_elements_per_s": round(elements / (call_ms * 1e-3), 1) if call_ms > 0 else None,
+        "merge": {"ms": round(merge_ms, 4),
+                  "update_elements_per_s": round(total / (merge_ms * 1e-3), 1) if merge_ms > 0 else None,
+                  "algorithmic_gbs": round((4.0 + 8.0 * P * rho_mean) * total / (merge_ms * 1e-3) / 1e9, 1)
+                  if merge_ms > 0 else None},
+        "hbm": {"peak_gbs": HBM_PEAK_GBS, "plain_copy_gbs": round(copy_gbs, 1),
+                "dominant_kernel_algorithmic_gbs": roofline["achieved"],
+                "dominant_kernel_measured_gbs": None if measured_gbs is None else round(measured_gbs, 1),
+                "dominant_kernel_measured_frac_of_peak": None if measured_gbs is None
+                else round(measured_gbs / HBM_PEAK_GBS, 4),
+                "dominant_kernel_frac_of_plain_copy": round(roofline["achieved"] / copy_gbs, 4)},
         "kernels": kernels,
         "elements_by_route": route_elems,
         "roofline": roofline,
@@ -263,7 +314,8 @@ def main():
     if not args.no_cpu_baseline:
         threads = min(16, os.cpu_count() or 1)
         v, dt = cpu_baseline(wl, grad0_host, threads)
-        out["cpu_baseline"] = {"value": v, "unit": "elements/s", "cores": threads, "kind": "oracle",
+        extras = cpu_baseline_extras(wl, grad0_host, idx.cpu().numpy(), val.cpu().numpy(), P, K)
+        out["cpu_baseline"] = {**extras, "value": v, "unit": "elements/s", "cores": threads, "kind": "oracle",
                                "sample": "worker 0 of %d, one iteration, all %d layers (%d elements), "
                                          "%.1f s wall" % (P, len(layers), total, dt)}
     print(json.dumps(out))
