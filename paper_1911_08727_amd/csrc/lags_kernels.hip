@@ -418,10 +418,9 @@ __global__ __launch_bounds__(NW * 64) void k_small(const SegDesc* __restrict__ s
 // ------------------------------------------------------------------ sample ---
 // Threshold guess for one large layer: form acc on up to 256 pieces of 64 (V = 4) or 256
 // (V = 16) consecutive elements spread over the layer (with a hashed offset inside each
-// stride), and take the
-// sample's `sample_rank`-th largest key as tau and its `sample_rank_hi`-th largest (the
-// sample's estimate of the layer's k-th largest) as tau_hi.  Missing sample slots count as
-// key 0.
+// stride), and take the sample's `sample_rank`-th largest key as tau and its
+// `sample_rank_hi`-th largest (the sample's estimate of the layer's k-th largest) as tau_hi.
+// Missing sample slots count as key 0.
 template <int V>
 __device__ __forceinline__ void sample_layer(const LargeSeg& ls, int li, const SegDesc& sd,
                                              const float* __restrict__ grad, const float* __restrict__ res,
@@ -593,8 +592,9 @@ __device__ __forceinline__ void stream_collect(uint32_t (&a)[V][4], int n_w, int
 // key >= tau into the tile's slots, and write zero instead of acc for the collected entries
 // with key >= tau_hi (the sample's estimate of the k-th largest key: most of them are kept, so
 // most kept entries get their zero in this pass instead of a scattered write later); tiles of
-// the other layers add to the layer's histogram of key bits 30..20.  Both arrays are touched exactly once, so full aligned tiles use
-// non-temporal 16-byte loads and stores.
+// the other layers add to the layer's histogram of key bits 30..20.  Both arrays are touched
+// exactly once, so full aligned tiles use non-temporal 16-byte loads and stores.  The launch
+// adds kStreamLdsPad bytes of unused dynamic LDS per workgroup to cap the workgroups per CU.
 template <int NW, int V>
 __global__ __launch_bounds__(NW * 64) void k_stream(const TileDesc* __restrict__ tiles,
                                                 const float* __restrict__ grad,
