@@ -39,7 +39,7 @@ constexpr int kSampleMax = kSamplePiece * kSamplePieces;   // 16384 sampled elem
 constexpr int kSamplePieceBig = 256;                       // 256 pieces x 256 = 65536 sampled elements
 constexpr int kBigSampleK = 8192;
 constexpr int64_t kBigSampleD = 1 << 20;
-constexpr int kSlotMin = 256;            // candidate slots per tile of a sampled layer: the table uses the
+constexpr int kSlotMin = 128;            // candidate slots per tile of a sampled layer: the table uses the
 constexpr int kSlotMax = 2048;           // smallest power of two >= 8x the expected count of any layer
 constexpr int kDenseGrid = 1024;         // workgroups of the fallback kernels (grid-stride)
 // The streaming pass is HBM-bound and runs best when each CU holds only three of its
