@@ -26,8 +26,12 @@
  *     capture (they enqueue kernels and event waits only, no memset and no copy), provided a
  *     call with the same table (and, for the merge-type calls, a P at least as large) has run
  *     outside capture before: that first call sizes the context's scratch with synchronous
- *     allocations.  Timing (lags_profile_*) must be off while capturing.
- *   - A context owns scratch memory only (histograms, counters, candidate lists);
+ *     allocations.  Timing (lags_profile_*) must be off while capturing.  A recorded graph
+ *     holds the addresses of the scratch it was recorded with: from the first recorded call on,
+ *     scratch that a larger table (or a larger P) outgrows is kept allocated until lags_destroy
+ *     instead of being freed, so graphs recorded earlier stay valid for as long as the context,
+ *     their table and the caller's buffers live.
+ *   - A context owns scratch memory only (histograms, counters, candidate slots);
  *     nothing in it influences results.  One context serves one stream at a time:
  *     calls on the same context must be ordered on one stream (or externally).
  *   - Indices are 0-based, local to their layer, int32.
@@ -66,7 +70,8 @@ enum {
 int64_t lags_topk_count(int64_t d, double rho);
 
 /* Create / destroy a context on HIP device `device`.  Scratch grows when a table is
- * created and is released by lags_destroy. */
+ * created and is released by lags_destroy (which waits for the device first).  If an allocation
+ * for a larger table fails, the context and the tables created before stay usable. */
 int lags_create(lags_ctx **out, int device);
 int lags_destroy(lags_ctx *ctx);
 
@@ -149,8 +154,8 @@ int lags_delta_monitor(lags_ctx *ctx, const lags_table *t, const float *residual
  * c_u).  With c = d/k for an integer k this is the LARGEST k in [1, d] whose exchange fits,
  * raised to at least ceil(d / c_u).
  *
- * The paper takes t_comm from "the communication model of the AllGather"; this library's model
- * is a ring all-gather of one message per worker holding k (int32 index, float value) pairs:
+ * Section 5 leaves the cost model of the collective open; this library's model is a ring
+ * all-gather of one message per worker holding k (int32 index, float value) pairs:
  *     t_comm(k) = (P - 1) * (alpha + 8 * k * beta)      seconds. */
 typedef struct {
   double alpha; /* start-up time of one message, seconds, >= 0 */
@@ -177,13 +182,32 @@ double lags_allgather_seconds(const lags_allgather_model *net, int64_t k);
 int lags_adaptive_ratios(const lags_allgather_model *net, const int64_t *d, const double *t_comp,
                          const double *t_spar, int32_t n, double c_u, int64_t *k_out, double *rho_out);
 
-/* Diagnostic: which route each layer took in the LAST lags_sparsify_model call made with
- * this table on this context (host-synchronous: waits for the device).  route[l], l in
- * [0, n): 0 = one-workgroup route (small layer); 1 = sampled threshold accepted, selection
- * ran on the candidate list; 2 = sampled threshold rejected (too few candidates or a list
- * overflowed), exact multi-pass fallback; 3 = layer not sampled, exact multi-pass route.
+/* Diagnostic: which route each layer took in the LAST sparsify call made on this context,
+ * which must have been a lags_sparsify_model call with this table (the record lives in the
+ * context's scratch, which every table and every lags_sparsify_layer call of the context
+ * shares).  Host-synchronous: waits for the device.  route[l], l in [0, n):
+ * 0 = one-workgroup route (small layer); 1 = sampled threshold accepted, the kept set was
+ * read off the candidates collected by the streaming pass; 2 = sampled threshold rejected (too
+ * few candidates, a tile's slots overflowed, too many entries tied around the k-th largest),
+ * exact selection over the whole layer; 3 = layer not sampled, exact multi-pass route.
  * Results never depend on the route. */
 int lags_last_routes(lags_ctx *ctx, const lags_table *t, int32_t *route, int32_t n);
+
+/* Diagnostic: how a rejected threshold guess (route 2) is served.  mode 0 (default): by one
+ * workgroup per rejected layer inside the same launches (nothing extra is enqueued while guesses
+ * hold; a rejection is reported to the host through a pinned word, and the next 64 sparsify
+ * calls of the context also enqueue the six multi-pass kernels, which then serve rejections);
+ * mode 1: the multi-pass kernels are always enqueued; mode 2: never for rejections.
+ * Results are the same in every mode. */
+int lags_debug_fallback_chain(lags_ctx *ctx, int mode);
+
+/* Diagnostic: address and size of the context's scratch buffer number `which` (0 <= which < 14),
+ * and how many outgrown buffers the context keeps alive for recorded graphs. */
+int lags_debug_scratch_info(lags_ctx *ctx, int which, const void **ptr, int64_t *bytes, int64_t *retired);
+
+/* Diagnostic: overwrite every scratch buffer of the context with 0xFF bytes (enqueued on
+ * `hip_stream`).  Results of later calls must not change: scratch carries nothing between calls. */
+int lags_debug_poison_scratch(lags_ctx *ctx, void *hip_stream);
 
 /* Optional per-kernel timing with HIP events recorded on the caller's stream (measurement
  * aid; off by default; no effect on results).  While enabled every kernel launch of this

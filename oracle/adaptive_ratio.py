@@ -8,7 +8,7 @@ Eq. 9 picks, per layer l, the smallest compression ratio c = d/k whose sparse ex
 (time t_comm(c)) plus the sparsification overhead t_spar fits into the backpropagation time of
 the layer computed next, t_comp^(l-1), capped by an upper bound c_u.  The printed outer "max"
 with an UPPER bound is read as "min"; an empty set gives c_u.  The communication model
-(the paper only names "the communication model of the AllGather") is a ring all-gather of one
+(Section 5 leaves the collective's cost model open) is a ring all-gather of one
 message of k (index, value) pairs of 8 bytes per worker: (P-1) * (alpha + 8*k*beta).
 """
 import math

@@ -13,16 +13,34 @@
 
 using namespace lags;
 
-// A device buffer that only ever grows.
+// A device buffer that only ever grows.  The larger buffer is allocated before the old one is
+// given up, so a failed allocation leaves the buffer (and every table that uses it) intact.
+// `retired`: if not null the old allocation is kept there instead of being freed (a captured
+// HIP graph may still hold its address).
 struct DevBuf {
   void* p = nullptr;
   size_t bytes = 0;
-  int grow(size_t need) {
+  int grow(size_t need, std::vector<void*>* retired) {
     if (need <= bytes) return LAGS_OK;
-    if (p) (void)hipFree(p);
-    p = nullptr;
-    bytes = 0;
-    if (hipMalloc(&p, need) != hipSuccess) { p = nullptr; return LAGS_ENOMEM; }
+    void* q = nullptr;
+    if (hipMalloc(&q, need) != hipSuccess) return LAGS_ENOMEM;
+    if (p) {
+      bool kept = false;
+      if (retired) {
+        try {
+          retired->push_back(p);
+          kept = true;
+        } catch (const std::bad_alloc&) {
+        }
+        if (!kept) {  // cannot keep the old buffer alive: refuse to move it
+          (void)hipFree(q);
+          return LAGS_ENOMEM;
+        }
+      } else {
+        (void)hipFree(p);
+      }
+    }
+    p = q;
     bytes = need;
     return LAGS_OK;
   }
@@ -35,27 +53,43 @@ struct DevBuf {
 
 struct lags_ctx {
   int device = 0;
-  // scratch of the multi-block path, sized for the largest table created so far
-  DevBuf ghist, lstate, tile_gt, tile_eq, items, chunk_cnt, chunk_off, slots, cand;
+  // scratch of the large layers' path, sized for the largest table created so far
+  DevBuf bh, lstate, chunk_cnt, slots, wgt, band, band_cnt, ghist, dstate, tile_gt, tile_eq, items;
   DevBuf bounds;   // merge: P rows of tile start positions, sized at the first merge call that needs it
   DevBuf partials; // delta metric: two doubles per merge tile
+  // Once a call of this context has been recorded by stream capture, scratch that has to grow is
+  // not freed but kept until lags_destroy: the recorded graph holds its address.
+  bool captured = false;
+  std::vector<void*> retired;
+  // A pinned host word that a kernel sets when a sampled layer's guess is rejected.  The next
+  // calls then also enqueue the multi-pass kernels, so that rejected layers are selected by many
+  // workgroups instead of one (results are the same either way).
+  uint32_t* fail_host = nullptr;
+  uint32_t* fail_dev = nullptr;
+  int armed_calls = 0;   // calls left that enqueue the multi-pass kernels
+  int chain_mode = 0;    // 0: as above; 1: always enqueue them; 2: never (diagnostic setting)
   std::map<std::pair<int64_t, int64_t>, lags_table*> layer_tables;  // (d, k) -> one-layer table
   Prof prof;
   // side stream (default priority) on which the small layers' kernels run beside the large
   // layers' pipeline; forked from and joined to the caller's stream with events in every call
   hipStream_t aux = nullptr;
   hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+  std::vector<void*>* retire_list() { return captured ? &retired : nullptr; }
   Scratch scratch() const {
     Scratch sc;
-    sc.ghist = static_cast<uint32_t*>(ghist.p);
+    sc.bh = static_cast<uint32_t*>(bh.p);
     sc.lstate = static_cast<LState*>(lstate.p);
+    sc.chunk_cnt = static_cast<uint32_t*>(chunk_cnt.p);
+    sc.slots = static_cast<uint2*>(slots.p);
+    sc.wgt = static_cast<uint32_t*>(wgt.p);
+    sc.band = static_cast<uint2*>(band.p);
+    sc.band_cnt = static_cast<uint32_t*>(band_cnt.p);
+    sc.ghist = static_cast<uint32_t*>(ghist.p);
+    sc.dstate = static_cast<DState*>(dstate.p);
     sc.tile_gt = static_cast<uint32_t*>(tile_gt.p);
     sc.tile_eq = static_cast<uint32_t*>(tile_eq.p);
     sc.items = static_cast<int32_t*>(items.p);
-    sc.chunk_cnt = static_cast<uint32_t*>(chunk_cnt.p);
-    sc.chunk_off = static_cast<uint32_t*>(chunk_off.p);
-    sc.slots = static_cast<uint2*>(slots.p);
-    sc.cand = static_cast<uint2*>(cand.p);
+    sc.fail_flag = fail_dev;
     return sc;
   }
 };
@@ -74,13 +108,11 @@ struct lags_table {
   int32_t* d_small[3] = {nullptr, nullptr, nullptr};
   LargeSeg* d_lsegs = nullptr;
   TileDesc* d_tiles = nullptr;
-  TileDesc* d_ctiles = nullptr;
+  GroupDesc* d_groups = nullptr;
+  int32_t* d_multi = nullptr;
   TileDesc* d_mtiles = nullptr;
   BChunk* d_bchunks = nullptr;
   int32_t* d_seg_mtile0 = nullptr;
-  int32_t* d_sampled = nullptr;
-  int32_t* d_cand_small[3] = {nullptr, nullptr, nullptr};
-  int32_t* d_chunk_lseg = nullptr;
 };
 
 namespace {
@@ -117,25 +149,27 @@ bool ranges_overlap(const void* a, int64_t abytes, const void* b, int64_t bbytes
   return a0 < b0 + (uintptr_t)bbytes && b0 < a0 + (uintptr_t)abytes;
 }
 
+std::vector<DevBuf*> all_bufs(lags_ctx* ctx) {
+  return {&ctx->bh, &ctx->lstate, &ctx->chunk_cnt, &ctx->slots, &ctx->wgt, &ctx->band, &ctx->band_cnt, &ctx->ghist,
+          &ctx->dstate, &ctx->tile_gt, &ctx->tile_eq, &ctx->items, &ctx->bounds, &ctx->partials};
+}
+
 void free_table_device(lags_table* t) {
   if (t->d_segs) (void)hipFree(t->d_segs);
-  for (int c = 0; c < 3; ++c) {
+  for (int c = 0; c < 3; ++c)
     if (t->d_small[c]) (void)hipFree(t->d_small[c]);
-    if (t->d_cand_small[c]) (void)hipFree(t->d_cand_small[c]);
-  }
   if (t->d_lsegs) (void)hipFree(t->d_lsegs);
   if (t->d_tiles) (void)hipFree(t->d_tiles);
-  if (t->d_ctiles) (void)hipFree(t->d_ctiles);
+  if (t->d_groups) (void)hipFree(t->d_groups);
+  if (t->d_multi) (void)hipFree(t->d_multi);
   if (t->d_mtiles) (void)hipFree(t->d_mtiles);
   if (t->d_bchunks) (void)hipFree(t->d_bchunks);
   if (t->d_seg_mtile0) (void)hipFree(t->d_seg_mtile0);
-  if (t->d_sampled) (void)hipFree(t->d_sampled);
-  if (t->d_chunk_lseg) (void)hipFree(t->d_chunk_lseg);
 }
 
 // Plan of the threshold guess for a large layer of d elements keeping k: how many sample
-// pieces, which rank of the sample becomes the threshold, how long the candidate list may
-// get.  Returns false if the layer is not worth sampling (k too large for the slots).
+// pieces and which ranks of the sample become the threshold and the estimate of the k-th
+// largest key.  Returns false if the layer is not worth sampling (k too large for the slots).
 bool plan_sample(int64_t d, int64_t k, LargeSeg* ls, double* per_tile) {
   int64_t pieces, stride;
   int64_t piece_len = kSamplePiece;
@@ -154,28 +188,19 @@ bool plan_sample(int64_t d, int64_t k, LargeSeg* ls, double* per_tile) {
   }
   const double m = (double)std::min<int64_t>(d, pieces * piece_len);
   const double fk = (double)k * m / (double)d;
-  // the sample's rank-j key admits about j/m of the layer; j is fk plus four standard
-  // deviations of the sampled count plus a constant: fewer than k candidates (which only
-  // costs the fallback for that layer in that call) then has a probability of a few 1e-5
-  const double jd = std::ceil(fk + 4.0 * std::sqrt(fk) + 8.0);
+  // the sample's rank-j key admits about j/m of the layer; j is fk plus five standard
+  // deviations of the sampled count plus a constant: fewer than k candidates (which costs the
+  // slow selection of that layer in that call) then has a probability below 1e-6
+  const double jd = std::ceil(fk + 5.0 * std::sqrt(fk) + 8.0);
   if (jd > m) return false;
   // expected candidates per tile must stay well inside the largest slot size
   *per_tile = jd / m * (double)kTile;
   if (*per_tile > (double)kSlotMax * 0.5) return false;
-  const double expect = jd / m * (double)d;
-  const int64_t cap = std::min<int64_t>(d, (int64_t)(2.0 * expect) + 1024);
   ls->sample_rank = (int32_t)jd;
-  // the sample's best estimate of the k-th largest key: entries above it are zeroed in the
-  // streaming pass, the final pass fixes the difference (about k / sqrt(fk) entries either way)
-  // (not worth a second selection over the sample where k is small)
-  ls->sample_rank_hi = k >= 8192 ? (int32_t)std::floor(fk) : 0;
+  // the sample's best estimate of the k-th largest key: it sets the width of the candidate buckets
+  ls->sample_rank_hi = (int32_t)std::max(1.0, std::floor(fk));
   ls->sample_pieces = (int32_t)pieces;
   ls->sample_stride = (int32_t)stride;
-  ls->cap = (int32_t)cap;
-  if (cap <= kSmall0) ls->cand_class = CAND_SMALL0;
-  else if (cap <= kSmall1) ls->cand_class = CAND_SMALL1;
-  else if (cap <= kSmall2) ls->cand_class = CAND_SMALL2;
-  else ls->cand_class = CAND_LARGE;
   return true;
 }
 
@@ -187,28 +212,20 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
   if (!t) return LAGS_ENOMEM;
   t->ctx = ctx;
   t->n = n;
-  std::vector<int32_t> small[3], cand_small[3], sampled, chunk_lseg;
-  std::vector<TileDesc> tiles, ctiles, mtiles;
+  std::vector<int32_t> small[3], multi;
+  std::vector<TileDesc> tiles, mtiles;
+  std::vector<GroupDesc> groups;
   std::vector<BChunk> bchunks;
   std::vector<int32_t> seg_mtile0;
-  int64_t n_ctile_dense = 0;   // tiles of sampled layers: each owns `slot` candidate slots
+  int64_t n_chunks = 0;        // tiles of sampled layers: each owns `slot` candidate slots
+  int64_t n_wchunks = 0;       // runs of kWaveTiles such tiles
   double max_per_tile = 0.0;   // largest expected candidate count per tile over the sampled layers
-  int64_t cand_total = 0;
   constexpr int64_t kMaxTiles = 1 << 28;
   try {
     t->segs.resize(n);
     int64_t outpos = 0;
     t->span_lo = off[0];
     t->span_hi = off[0] + d[0];
-    // If some layer's candidate list needs the multi-block selection, those launches happen
-    // anyway: then every sampled layer uses them and the one-workgroup launches are saved.
-    bool any_cand_large = false;
-    for (int32_t l = 0; l < n && !any_cand_large; ++l) {
-      LargeSeg probe = {};
-      double per_tile = 0.0;
-      if (d[l] > kSmall2 && plan_sample(d[l], k[l], &probe, &per_tile) && probe.cand_class == CAND_LARGE)
-        any_cand_large = true;
-    }
     for (int32_t l = 0; l < n; ++l) {
       SegDesc& s = t->segs[l];
       s.offset = off[l];
@@ -225,36 +242,34 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
         LargeSeg ls = {};
         const int32_t li = (int32_t)t->lsegs.size();
         ls.seg = l;
-        ls.cand_class = CAND_NONE;
         double per_tile = 0.0;
-        const bool sampled_layer = plan_sample(d[l], k[l], &ls, &per_tile);
-        if (sampled_layer) max_per_tile = std::max(max_per_tile, per_tile);
-        if (sampled_layer && ls.sample_big) t->plan.big_sample = true;
-        if (sampled_layer && any_cand_large) ls.cand_class = CAND_LARGE;
+        ls.sampled = plan_sample(d[l], k[l], &ls, &per_tile) ? 1 : 0;
         ls.tile_begin = (int32_t)tiles.size();
         const int64_t nt = (d[l] + kTile - 1) / kTile;
         if ((int64_t)tiles.size() + nt > kMaxTiles) { delete t; return LAGS_ECAPACITY; }
-        if (sampled_layer) {
-          ls.chunk_begin = (int32_t)n_ctile_dense;
-          ls.cand_base = cand_total;
-          cand_total += ls.cap;
-          sampled.push_back(li);
-          if (ls.cand_class == CAND_LARGE) {
-            ls.ctile_begin = (int32_t)ctiles.size();
-            const int64_t nct = ((int64_t)ls.cap + kTile - 1) / kTile;
-            for (int64_t i = 0; i < nct; ++i) {
-              TileDesc td;
-              td.start = ls.cand_base + i * kTile;
-              td.n = (int32_t)std::min<int64_t>(kTile, (int64_t)ls.cap - i * kTile);
-              td.seg = li;
-              td.local0 = (int32_t)(i * kTile);
-              td.ctile = -1;
-              ctiles.push_back(td);
+        if (ls.sampled) {
+          max_per_tile = std::max(max_per_tile, per_tile);
+          if (ls.sample_big) t->plan.big_sample = true;
+          ls.chunk_begin = (int32_t)n_chunks;
+          ls.chunk_end = (int32_t)(n_chunks + nt);
+          ls.wchunk_begin = (int32_t)n_wchunks;
+          const int64_t nwc = (nt + kWaveTiles - 1) / kWaveTiles;
+          n_wchunks += nwc;
+          ls.fused = nt <= kFusedTiles ? 1 : 0;
+          if (!ls.fused) {
+            ls.group_begin = (int32_t)groups.size();
+            const int64_t ng = (nwc + kGroupWaves - 1) / kGroupWaves;
+            for (int64_t g = 0; g < ng; ++g) {
+              GroupDesc gd;
+              gd.lseg = li;
+              gd.first = (int32_t)g;
+              groups.push_back(gd);
             }
-            ls.ctile_end = (int32_t)ctiles.size();
-          } else {
-            cand_small[ls.cand_class - CAND_SMALL0].push_back(li);
+            ls.group_end = (int32_t)groups.size();
+            multi.push_back(li);
           }
+        } else {
+          t->plan.has_dense = true;
         }
         for (int64_t i = 0; i < nt; ++i) {
           TileDesc td;
@@ -262,15 +277,11 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
           td.n = (int32_t)std::min<int64_t>(kTile, d[l] - i * kTile);
           td.seg = li;
           td.local0 = (int32_t)(i * kTile);
-          td.ctile = sampled_layer ? (int32_t)n_ctile_dense : -1;
-          if (sampled_layer) {
-            ++n_ctile_dense;
-            chunk_lseg.push_back(li);
-          }
+          td.ctile = ls.sampled ? (int32_t)(n_chunks + i) : -1;
           tiles.push_back(td);
         }
+        if (ls.sampled) n_chunks += nt;
         ls.tile_end = (int32_t)tiles.size();
-        if (sampled_layer) ls.chunk_end = (int32_t)n_ctile_dense;
         t->lsegs.push_back(ls);
       }
       const int64_t nmt = (d[l] + kMergeTile - 1) / kMergeTile;
@@ -308,46 +319,47 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
   LargePlan& pl = t->plan;
   pl.n_large = (int)t->lsegs.size();
   pl.n_tiles = (int)tiles.size();
-  pl.n_sampled = (int)sampled.size();
-  pl.n_chunks = (int)chunk_lseg.size();
-  pl.n_ctiles = (int)ctiles.size();
+  pl.n_chunks = (int)n_chunks;
+  pl.n_wchunks = (int)n_wchunks;
+  pl.n_groups = (int)groups.size();
+  pl.n_multi = (int)multi.size();
+  for (const LargeSeg& ls : t->lsegs) pl.n_sampled += ls.sampled;
   // candidates cluster (e.g. the few non-zero rows of an embedding gradient), so a tile may
   // hold several times the layer's average: the slots leave a factor 8 where they can
   pl.slot = kSlotMin;
   while ((double)pl.slot < 8.0 * max_per_tile && pl.slot < kSlotMax) pl.slot *= 2;
-  for (int c = 0; c < 3; ++c) pl.n_cand_small[c] = (int)cand_small[c].size();
 
   int rc = upload(&t->d_segs, t->segs);
   for (int c = 0; c < 3 && rc == LAGS_OK; ++c) rc = upload(&t->d_small[c], small[c]);
-  for (int c = 0; c < 3 && rc == LAGS_OK; ++c) rc = upload(&t->d_cand_small[c], cand_small[c]);
   if (rc == LAGS_OK) rc = upload(&t->d_lsegs, t->lsegs);
   if (rc == LAGS_OK) rc = upload(&t->d_tiles, tiles);
-  if (rc == LAGS_OK) rc = upload(&t->d_ctiles, ctiles);
+  if (rc == LAGS_OK) rc = upload(&t->d_groups, groups);
+  if (rc == LAGS_OK) rc = upload(&t->d_multi, multi);
   if (rc == LAGS_OK) rc = upload(&t->d_mtiles, mtiles);
   if (rc == LAGS_OK) rc = upload(&t->d_bchunks, bchunks);
   if (rc == LAGS_OK) rc = upload(&t->d_seg_mtile0, seg_mtile0);
   t->mplan.mtiles = t->d_mtiles;
   t->mplan.bchunks = t->d_bchunks;
   t->mplan.seg_mtile0 = t->d_seg_mtile0;
-  if (rc == LAGS_OK) rc = upload(&t->d_sampled, sampled);
-  if (rc == LAGS_OK) rc = upload(&t->d_chunk_lseg, chunk_lseg);
   pl.lsegs = t->d_lsegs;
   pl.tiles = t->d_tiles;
-  pl.ctiles = t->d_ctiles;
-  pl.sampled = t->d_sampled;
-  pl.chunk_lseg = t->d_chunk_lseg;
-  for (int c = 0; c < 3; ++c) pl.cand_small[c] = t->d_cand_small[c];
+  pl.groups = t->d_groups;
+  pl.multi = t->d_multi;
   if (pl.n_large > 0) {
-    const size_t nt = (size_t)pl.n_tiles + (size_t)pl.n_ctiles;
-    if (rc == LAGS_OK) rc = ctx->ghist.grow(((size_t)pl.n_large * kHistStride + 16) * sizeof(uint32_t));
-    if (rc == LAGS_OK) rc = ctx->lstate.grow((size_t)pl.n_large * sizeof(LState));
-    if (rc == LAGS_OK) rc = ctx->tile_gt.grow(nt * sizeof(uint32_t));
-    if (rc == LAGS_OK) rc = ctx->tile_eq.grow(nt * sizeof(uint32_t));
-    if (rc == LAGS_OK) rc = ctx->items.grow((size_t)pl.n_tiles * sizeof(int32_t));
-    if (rc == LAGS_OK) rc = ctx->chunk_cnt.grow((size_t)pl.n_chunks * sizeof(uint32_t));
-    if (rc == LAGS_OK) rc = ctx->chunk_off.grow((size_t)pl.n_chunks * sizeof(uint32_t));
-    if (rc == LAGS_OK) rc = ctx->slots.grow((size_t)pl.n_chunks * (size_t)pl.slot * sizeof(uint2));
-    if (rc == LAGS_OK) rc = ctx->cand.grow((size_t)cand_total * sizeof(uint2));
+    std::vector<void*>* rl = ctx->retire_list();
+    const size_t nl = (size_t)pl.n_large;
+    if (rc == LAGS_OK) rc = ctx->bh.grow(nl * kFineBins * sizeof(uint32_t), rl);
+    if (rc == LAGS_OK) rc = ctx->lstate.grow(nl * sizeof(LState), rl);
+    if (rc == LAGS_OK) rc = ctx->chunk_cnt.grow((size_t)pl.n_chunks * sizeof(uint32_t), rl);
+    if (rc == LAGS_OK) rc = ctx->slots.grow((size_t)pl.n_chunks * (size_t)pl.slot * sizeof(uint2), rl);
+    if (rc == LAGS_OK) rc = ctx->wgt.grow((size_t)pl.n_wchunks * sizeof(uint32_t), rl);
+    if (rc == LAGS_OK) rc = ctx->band.grow((size_t)pl.n_groups * kGroupBand * sizeof(uint2), rl);
+    if (rc == LAGS_OK) rc = ctx->band_cnt.grow((size_t)pl.n_groups * sizeof(uint32_t), rl);
+    if (rc == LAGS_OK) rc = ctx->ghist.grow((nl * kHistStride + 16) * sizeof(uint32_t), rl);
+    if (rc == LAGS_OK) rc = ctx->dstate.grow(nl * sizeof(DState), rl);
+    if (rc == LAGS_OK) rc = ctx->tile_gt.grow((size_t)pl.n_tiles * sizeof(uint32_t), rl);
+    if (rc == LAGS_OK) rc = ctx->tile_eq.grow((size_t)pl.n_tiles * sizeof(uint32_t), rl);
+    if (rc == LAGS_OK) rc = ctx->items.grow((size_t)pl.n_tiles * sizeof(int32_t), rl);
   }
   if (rc != LAGS_OK) {
     free_table_device(t);
@@ -360,6 +372,24 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
 
 int run_sparsify(lags_ctx* ctx, const lags_table* t, const float* grad, float* res, float lr,
                  int32_t* out_idx, float* out_val, hipStream_t s) {
+  // a call that is being recorded into a graph pins the scratch it uses (see DevBuf::grow)
+  hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(s, &cap) == hipSuccess && cap != hipStreamCaptureStatusNone) ctx->captured = true;
+  // Do the multi-pass kernels run in this call?  Always for tables with layers that are not
+  // sampled; otherwise for a number of calls after a kernel reported a rejected guess.
+  bool chain = t->plan.has_dense;
+  if (t->plan.n_large > 0) {
+    if (ctx->fail_host && *static_cast<volatile uint32_t*>(ctx->fail_host)) {
+      *static_cast<volatile uint32_t*>(ctx->fail_host) = 0u;
+      ctx->armed_calls = 64;
+    }
+    if (ctx->armed_calls > 0) {
+      chain = true;
+      --ctx->armed_calls;
+    }
+    if (ctx->chain_mode == 1) chain = true;
+    if (ctx->chain_mode == 2) chain = t->plan.has_dense;
+  }
   ProfScope whole(&ctx->prof, K_SPARSIFY_CALL, s);
   // small and large layers touch disjoint parts of every buffer, so the small layers' kernels
   // can run on the side stream while the large layers' pipeline occupies the caller's stream
@@ -376,7 +406,7 @@ int run_sparsify(lags_ctx* ctx, const lags_table* t, const float* grad, float* r
   }
   if (fork && hipEventRecord(ctx->ev_join, ctx->aux) != hipSuccess) rc = LAGS_EHIP;
   if (rc == LAGS_OK &&
-      launch_large(t->plan, ctx->scratch(), t->d_segs, grad, res, lr, out_idx, out_val, s, &ctx->prof) != hipSuccess)
+      launch_large(t->plan, ctx->scratch(), t->d_segs, grad, res, lr, out_idx, out_val, chain, s, &ctx->prof) != hipSuccess)
     rc = LAGS_EHIP;
   // always join what was forked, also on an error path, so the caller's stream stays ordered
   if (fork && hipStreamWaitEvent(s, ctx->ev_join, 0) != hipSuccess) rc = LAGS_EHIP;
@@ -418,6 +448,23 @@ int lags_create(lags_ctx** out, int device) {
     } else {
       c->aux = nullptr;
     }
+    // the word through which kernels report a rejected guess: pinned, mapped host memory
+    void* hp = nullptr;
+    void* dp = nullptr;
+    if (!g.ok || hipHostMalloc(&hp, sizeof(uint32_t), hipHostMallocMapped) != hipSuccess ||
+        hipHostGetDevicePointer(&dp, hp, 0) != hipSuccess) {
+      if (hp) (void)hipHostFree(hp);
+      if (c->aux) {
+        (void)hipStreamDestroy(c->aux);
+        (void)hipEventDestroy(c->ev_fork);
+        (void)hipEventDestroy(c->ev_join);
+      }
+      delete c;
+      return g.ok ? LAGS_ENOMEM : LAGS_EHIP;
+    }
+    c->fail_host = static_cast<uint32_t*>(hp);
+    c->fail_dev = static_cast<uint32_t*>(dp);
+    *c->fail_host = 0u;
   }
   *out = c;
   return LAGS_OK;
@@ -437,9 +484,10 @@ int lags_destroy(lags_ctx* ctx) {
     free_table_device(kv.second);
     delete kv.second;
   }
-  DevBuf* bufs[] = {&ctx->ghist, &ctx->lstate, &ctx->tile_gt, &ctx->tile_eq, &ctx->items,
-                    &ctx->chunk_cnt, &ctx->chunk_off, &ctx->slots, &ctx->cand, &ctx->bounds, &ctx->partials};
-  for (DevBuf* b : bufs) b->release();
+  (void)hipDeviceSynchronize();  // no kernel may still write the pinned word or the scratch
+  for (DevBuf* b : all_bufs(ctx)) b->release();
+  for (void* p : ctx->retired) (void)hipFree(p);
+  if (ctx->fail_host) (void)hipHostFree(ctx->fail_host);
   delete ctx;
   return LAGS_OK;
 }
@@ -566,8 +614,15 @@ int run_merge(int mode, lags_ctx* ctx, const lags_table* t, const int32_t* idx, 
   if (!g.ok) return LAGS_EHIP;
   // P rows of tile bounds (and the delta partial sums): these grow, with a synchronous
   // allocation, the first time a larger P or table is used
-  if (ctx->bounds.grow((size_t)P * (size_t)t->mplan.nb * sizeof(int32_t)) != LAGS_OK) return LAGS_ENOMEM;
-  if (mode == MERGE_DELTA && ctx->partials.grow((size_t)t->mplan.n_mtiles * 2 * sizeof(double)) != LAGS_OK)
+  {
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing((hipStream_t)hip_stream, &cap) == hipSuccess && cap != hipStreamCaptureStatusNone)
+      ctx->captured = true;
+  }
+  if (ctx->bounds.grow((size_t)P * (size_t)t->mplan.nb * sizeof(int32_t), ctx->retire_list()) != LAGS_OK)
+    return LAGS_ENOMEM;
+  if (mode == MERGE_DELTA &&
+      ctx->partials.grow((size_t)t->mplan.n_mtiles * 2 * sizeof(double), ctx->retire_list()) != LAGS_OK)
     return LAGS_ENOMEM;
   if (launch_merge(mode, t->mplan, static_cast<int32_t*>(ctx->bounds.p), t->d_segs, idx, val, P, stride_k, out, res,
                    res_stride, static_cast<double*>(ctx->partials.p), out3, (hipStream_t)hip_stream,
@@ -654,10 +709,35 @@ int lags_last_routes(lags_ctx* ctx, const lags_table* t, int32_t* route, int32_t
   if (hipDeviceSynchronize() != hipSuccess) return LAGS_EHIP;
   if (hipMemcpy(st.data(), ctx->lstate.p, (size_t)nl * sizeof(LState), hipMemcpyDeviceToHost) != hipSuccess)
     return LAGS_EHIP;
-  for (int i = 0; i < nl; ++i) {
-    const LargeSeg& ls = t->lsegs[i];
-    route[ls.seg] = ls.cand_class == CAND_NONE ? 3 : (st[i].mode == MODE_SPARSE ? 1 : 2);
-  }
+  for (int i = 0; i < nl; ++i) route[t->lsegs[i].seg] = (int32_t)st[i].route;
+  return LAGS_OK;
+}
+
+int lags_debug_fallback_chain(lags_ctx* ctx, int mode) {
+  if (!ctx || mode < 0 || mode > 2) return LAGS_EINVAL;
+  ctx->chain_mode = mode;
+  ctx->armed_calls = 0;
+  return LAGS_OK;
+}
+
+int lags_debug_scratch_info(lags_ctx* ctx, int which, const void** ptr, int64_t* bytes, int64_t* retired) {
+  if (!ctx || !ptr || !bytes || !retired) return LAGS_EINVAL;
+  const std::vector<DevBuf*> bufs = all_bufs(ctx);
+  if (which < 0 || which >= (int)bufs.size()) return LAGS_EINVAL;
+  *ptr = bufs[which]->p;
+  *bytes = (int64_t)bufs[which]->bytes;
+  *retired = (int64_t)ctx->retired.size();
+  return LAGS_OK;
+}
+
+int lags_debug_poison_scratch(lags_ctx* ctx, void* hip_stream) {
+  if (!ctx) return LAGS_EINVAL;
+  DeviceGuard g(ctx->device);
+  if (!g.ok) return LAGS_EHIP;
+  for (DevBuf* b : all_bufs(ctx))
+    if (b->p && launch_fill_u32(static_cast<uint32_t*>(b->p), (int64_t)(b->bytes / 4), 0xFFFFFFFFu,
+                                (hipStream_t)hip_stream) != hipSuccess)
+      return LAGS_EHIP;
   return LAGS_OK;
 }
 

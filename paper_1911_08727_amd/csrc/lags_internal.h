@@ -28,20 +28,32 @@ constexpr int kSmall2 = 16 * 10 * 256;   // <= 40960 : 16 waves, 10 rounds
 
 // Threshold guess from a sample (large layers): 256 pieces of 64 consecutive elements.
 // The sample only has to rank the top k roughly: a smaller sample admits more candidates
-// (the threshold sits four standard deviations of the sample count below the top k), which
-// costs 8 bytes each and nothing else.
+// (the threshold sits five standard deviations of the sample count below the top k), which
+// costs 8 bytes each and little else.
 constexpr int kSamplePiece = 64;
 constexpr int kSamplePieces = 256;
 constexpr int kSampleMax = kSamplePiece * kSamplePieces;   // 16384 sampled elements
 // Layers that keep many entries (k >= kBigSampleK) of many elements take four times the sample:
-// the threshold is then tighter (about 1.6 k candidates instead of 2.5 k at rho = 0.001), which
-// saves more candidate traffic than the larger sample costs.
+// the threshold is then tighter (about 1.7 k candidates instead of 2.7 k at rho = 0.001).
 constexpr int kSamplePieceBig = 256;                       // 256 pieces x 256 = 65536 sampled elements
 constexpr int kBigSampleK = 8192;
 constexpr int64_t kBigSampleD = 1 << 20;
 constexpr int kSlotMin = 128;            // candidate slots per tile of a sampled layer: the table uses the
 constexpr int kSlotMax = 2048;           // smallest power of two >= 8x the expected count of any layer
-constexpr int kDenseGrid = 1024;         // workgroups of the fallback kernels (grid-stride)
+constexpr int kDenseGrid = 1024;         // workgroups of the multi-pass kernels (grid-stride)
+// Finish of a sampled layer.  The streaming pass counts its candidates in kFineBins buckets of
+// 2^shift key steps above the threshold tau (one global atomic each; same-address atomics cost
+// about 0.1-0.2 us on this chip, so the buckets are many and cover only the part of the key range
+// where the k-th largest key is expected: candidates above it are counted per tile instead).
+// The bucket that holds the k-th largest key is then resolved exactly among its own entries
+// ("band"), which must number at most kBandCap.
+constexpr int kFineBins = 4096;
+constexpr int kBandCap = 2048;
+constexpr int kWaveTiles = 32;           // a wave flattens the slots of 32 consecutive tiles ("wave chunk")
+constexpr int kGroupWaves = 4;           // a workgroup of the multi-workgroup finish: 4 wave chunks
+constexpr int kGroupTiles = kWaveTiles * kGroupWaves;
+constexpr int kGroupBand = 64;           // band entries one group may contribute
+constexpr int kFusedTiles = 1024;        // sampled layers of up to this many tiles are finished by one workgroup
 // The streaming pass is HBM-bound and runs best when each CU holds only three of its
 // workgroups (12 waves, about 96 KB of loads in flight per CU): measured on MI355X, 26.6 GB in
 // 4.05 ms, against 4.36 ms at the eight workgroups that registers and static LDS would allow
@@ -77,42 +89,54 @@ struct SegDesc {        // one layer
   int32_t k;
 };
 
-struct TileDesc {       // one tile of a layer (dense tiles, candidate tiles, merge tiles)
-  int64_t start;        // dense/merge: absolute element offset; candidate tile: offset in the candidate array
-  int32_t n;            // elements in the tile (<= tile size); candidate tiles: capacity
+struct TileDesc {       // one tile of a layer (dense tiles, merge tiles)
+  int64_t start;        // absolute element offset
+  int32_t n;            // elements in the tile (<= tile size)
   int32_t seg;          // large path: index among the large layers; merge: layer index
-  int32_t local0;       // layer-local index (candidate tiles: list position) of the first element
+  int32_t local0;       // layer-local index of the first element
   int32_t ctile;        // dense tiles of sampled layers: index among those tiles ("chunk"); else -1
 };
 
-enum : int32_t { CAND_NONE = 0, CAND_SMALL0 = 1, CAND_SMALL1 = 2, CAND_SMALL2 = 3, CAND_LARGE = 4 };
-
 struct LargeSeg {       // static plan of one large layer
-  int64_t cand_base;    // start of the layer's candidate list in the candidate array
   int32_t seg;          // layer index
   int32_t tile_begin;   // dense tiles [tile_begin, tile_end)
   int32_t tile_end;
+  int32_t sampled;      // 1: threshold guess from a sample, candidates collected in slots
   int32_t chunk_begin;  // sampled layers: their tiles' ctile numbers [chunk_begin, chunk_end), else 0,0
   int32_t chunk_end;
-  int32_t cand_class;   // CAND_NONE: not sampled
-  int32_t cap;          // capacity of the candidate list
-  int32_t ctile_begin;  // candidate tiles (CAND_LARGE) [ctile_begin, ctile_end)
-  int32_t ctile_end;
+  int32_t fused;        // sampled layers: 1 = finished by one workgroup, 0 = by groups of tiles
+  int32_t wchunk_begin; // sampled layers: first of the layer's wave chunks in the per-wave-chunk array
+  int32_t group_begin;  // multi-workgroup finish: the layer's groups [group_begin, group_end)
+  int32_t group_end;
   int32_t sample_rank;  // rank (1-based, from the top) of the sample key used as threshold tau
-  int32_t sample_rank_hi;  // rank of the sample key used as tau_hi (0: none): about k's share of the sample
+  int32_t sample_rank_hi;  // rank of the sample key that estimates the layer's k-th largest key
   int32_t sample_pieces;
   int32_t sample_stride;
   int32_t sample_big;   // 1: pieces of kSamplePieceBig elements (the large sample), 0: of kSamplePiece
+};
+
+struct GroupDesc {      // one workgroup of the multi-workgroup finish
+  int32_t lseg;         // large-layer index
+  int32_t first;        // index of the group inside its layer
 };
 
 enum : uint32_t { MODE_DENSE = 0, MODE_SPARSE = 1 };
 
 struct LState {         // per call, per large layer
   uint32_t tau;         // candidates are the entries with key >= tau
-  uint32_t tau_hi;      // candidates with key >= tau_hi had their residual zeroed by the streaming pass
-  uint32_t ncand;       // number of candidates found
-  uint32_t mode;        // MODE_SPARSE: the candidate list holds the top k; MODE_DENSE: fall back
-  uint32_t p0, k0;      // radix select after digit 0: key bits decided, entries still to take below them
+  uint32_t tau_top;     // candidates with key >= tau_top are counted per tile, the others per bucket
+  uint32_t shift;       // bucket of a candidate below tau_top: (key - tau) >> shift
+  uint32_t mode;        // MODE_SPARSE: the guess held, the slots contain the top k
+  uint32_t bstar;       // the bucket that holds the k-th largest key
+  uint32_t k_rem;       // how many of that bucket's entries belong to the top k
+  uint32_t n_band;      // entries in that bucket
+  uint32_t band_over;   // a group collected more band entries than it can hold
+  uint32_t route;       // for lags_last_routes: 1 accepted, 2 rejected, 3 not sampled
+  uint32_t pad[3];
+};
+
+struct DState {         // per call, per large layer on the multi-pass route: the radix select's progress
+  uint32_t p0, k0;      // after digit 0: key bits decided, entries still to take below them
   uint32_t p1, k1;      // ... after digit 1
   uint32_t prefix;      // ... after digit 2: the k-th largest key T
   uint32_t k_rem;       //     and how many entries equal to T belong to the top k
@@ -120,35 +144,37 @@ struct LState {         // per call, per large layer
 };
 
 struct LargePlan {      // everything launch_large needs (device pointers + counts)
-  int n_large = 0, n_tiles = 0, n_sampled = 0, n_chunks = 0, n_ctiles = 0;
+  int n_large = 0, n_tiles = 0, n_sampled = 0, n_chunks = 0, n_wchunks = 0, n_groups = 0, n_multi = 0;
   int slot = kSlotMin;                  // candidate slots per sampled tile
   bool big_sample = false;              // some layer uses the large sample
-  int n_cand_small[3] = {0, 0, 0};
+  bool has_dense = false;               // some large layer is not sampled: the multi-pass kernels always run
   const LargeSeg* lsegs = nullptr;
   const TileDesc* tiles = nullptr;      // dense tiles
-  const TileDesc* ctiles = nullptr;     // candidate tiles of CAND_LARGE layers
-  const int32_t* sampled = nullptr;     // large-layer indices that are sampled
-  const int32_t* cand_small[3] = {nullptr, nullptr, nullptr};  // large-layer indices per class
-  const int32_t* chunk_lseg = nullptr;  // chunk (sampled tile) -> large-layer index
+  const GroupDesc* groups = nullptr;    // groups of the layers with fused == 0
+  const int32_t* multi = nullptr;       // large-layer indices of those layers
 };
 
 struct Scratch {        // context-owned device memory, contents meaningless between calls
-  uint32_t* ghist = nullptr;      // n_large * kHistStride, then 16 counters ([0] = number of dense
-                                  // work items); zeroed each call
+  uint32_t* bh = nullptr;         // n_large * kFineBins: candidate buckets; zeroed each call
   LState* lstate = nullptr;       // n_large
-  uint32_t* tile_gt = nullptr;    // n_tiles + n_ctiles
-  uint32_t* tile_eq = nullptr;
-  int32_t* items = nullptr;       // n_tiles: dense tiles to process in fallback mode
-  uint32_t* chunk_cnt = nullptr;  // n_chunks
-  uint32_t* chunk_off = nullptr;  // n_chunks
+  uint32_t* chunk_cnt = nullptr;  // n_chunks: candidates of the tile | those at or above tau_top << 16
   uint2* slots = nullptr;         // n_chunks * slot
-  uint2* cand = nullptr;          // sum of cap over sampled layers
+  uint32_t* wgt = nullptr;        // n_wchunks: entries above the decisive bucket per wave chunk
+  uint2* band = nullptr;          // n_groups * kGroupBand
+  uint32_t* band_cnt = nullptr;   // n_groups
+  // multi-pass route (layers that are not sampled, rejected guesses)
+  uint32_t* ghist = nullptr;      // n_large * kHistStride, then 16 counters ([0] = number of work items)
+  DState* dstate = nullptr;       // n_large
+  uint32_t* tile_gt = nullptr;    // n_tiles
+  uint32_t* tile_eq = nullptr;
+  int32_t* items = nullptr;       // n_tiles: dense tiles to process
+  uint32_t* fail_flag = nullptr;  // device address of the context's pinned host word
 };
 
 // Kernel ids for the optional event timing.
 enum KernelId {
-  K_ZERO = 0, K_SMALL0, K_SMALL1, K_SMALL2, K_SAMPLE, K_STREAM, K_CSCAN, K_CGATHER,
-  K_CSMALL0, K_CSMALL1, K_CSMALL2, K_HIST, K_COUNT, K_SCAN, K_EMIT,
+  K_PREP = 0, K_SMALL0, K_SMALL1, K_SMALL2, K_STREAM, K_FINISH, K_GROUP_A, K_GROUP_B,
+  K_HIST, K_COUNT, K_SCAN, K_EMIT,
   K_MERGE_BOUNDS, K_MERGE, K_MERGE_APPLY, K_DELTA_TILES, K_DELTA_FINISH,
   K_SPARSIFY_CALL,      // not a kernel: the whole sparsify call on the caller's stream, fork to join
   K_NUM
@@ -178,11 +204,14 @@ struct ProfScope {
 };
 
 // Launch wrappers (lags_kernels.hip).  All enqueue on `s` and return the launch status.
-hipError_t launch_zero_u32(uint32_t* p, int64_t n, hipStream_t s, Prof* prof);
+hipError_t launch_fill_u32(uint32_t* p, int64_t n, uint32_t value, hipStream_t s);
 hipError_t launch_small(int cls, int nseg, const SegDesc* segs, const int32_t* list, const float* grad,
                         float* res, float lr, int32_t* out_idx, float* out_val, hipStream_t s, Prof* prof);
+// chain: also enqueue the multi-pass kernels (rejected guesses then use them instead of the
+// one-workgroup rescue); always true for plans with has_dense.
 hipError_t launch_large(const LargePlan& pl, const Scratch& sc, const SegDesc* segs, const float* grad,
-                        float* res, float lr, int32_t* out_idx, float* out_val, hipStream_t s, Prof* prof);
+                        float* res, float lr, int32_t* out_idx, float* out_val, bool chain, hipStream_t s,
+                        Prof* prof);
 enum { MERGE_UPDATE = 0, MERGE_APPLY = 1, MERGE_DELTA = 2 };
 
 struct MergePlan {      // device pointers + counts of the merge-type launches

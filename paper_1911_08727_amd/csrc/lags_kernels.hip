@@ -19,13 +19,16 @@
 // Three routes, chosen per layer by size:
 //   small  (d <= 40960): one workgroup, acc stays in registers between the single read of
 //          grad/residual and the single write of the residual.
-//   large, sampled: a sample of 16384 elements gives a threshold tau that, with high
+//   large, sampled: a sample of 16384 (65536) elements gives a threshold tau that, with high
 //          probability, admits slightly more than k entries.  One streaming pass writes acc
-//          into the residual buffer and collects every entry with key >= tau (in index
-//          order).  If at least k were collected (and the lists did not overflow) the exact
-//          top k are among them and the selection runs on the short candidate list only.
-//          The guess never changes the result: it is verified by the count.
-//   large, fallback: radix select over the acc values in the residual buffer, multi-block.
+//          into the residual buffer, collects every entry with key >= tau (in index order)
+//          into per-tile slots and counts them in buckets of the key range just above tau.
+//          If at least k were collected and no tile overflowed, the exact top k are among
+//          them: the bucket counts name the bucket that holds the k-th largest key, its few
+//          entries are ranked exactly, and one more pass over the slots emits the kept pairs.
+//          The guess never changes the result: it is verified by the counts.
+//   large, multi-pass: radix select over the acc values in the residual buffer, multi-block
+//          (layers too dense to sample; rejected guesses).
 #include "lags_internal.h"
 
 namespace lags {
@@ -215,18 +218,6 @@ __device__ __forceinline__ void load_bits(const float* __restrict__ r, int n_w, 
   }
 }
 
-// Load the value bits of a wave's chunk of a candidate list ((index, bits) pairs).
-template <int V>
-__device__ __forceinline__ void load_cand_bits(const uint2* __restrict__ cw, int n_w, int lane,
-                                               uint32_t (&a)[V][4]) {
-#pragma unroll
-  for (int j = 0; j < V; ++j) {
-    const int e = j * 256 + lane * 4;
-#pragma unroll
-    for (int c = 0; c < 4; ++c) a[j][c] = (e + c < n_w) ? cw[e + c].y : 0u;
-  }
-}
-
 template <int V>
 __device__ __forceinline__ void store_bits(float* __restrict__ r, int n_w, bool vec, int lane,
                                            const uint32_t (&a)[V][4]) {
@@ -259,7 +250,7 @@ __device__ __forceinline__ void lane_count(const uint32_t (&a)[V][4], int n_w, i
   }
 }
 
-enum { EMIT_FULL = 0, EMIT_ZERO = 1, EMIT_CAND = 2 };
+enum { EMIT_FULL = 0, EMIT_ZERO = 1 };
 
 // Ordered emission of a wave's chunk.  gt_before / eq_before: numbers of keys > T and
 // == T that precede the chunk in the layer.  An element is kept if key > T, or key == T
@@ -269,16 +260,11 @@ enum { EMIT_FULL = 0, EMIT_ZERO = 1, EMIT_CAND = 2 };
 //            zeroed).  r = the chunk's residual.
 // EMIT_ZERO: the residual already holds acc; only the kept entries are zeroed.  r = the
 //            chunk's residual.
-// EMIT_CAND: the chunk is part of a candidate list cw ((index, bits) pairs).  The streaming
-//            pass already wrote zero for the entries with key >= tau_hi and acc for the others,
-//            so r[index] is written only where that differs from the outcome: zero for kept
-//            entries below tau_hi, acc for dropped entries at or above it.  r = the layer's residual.
 template <int V, int MODE>
 __device__ __forceinline__ void wave_emit(uint32_t (&a)[V][4], int n_w, int lane, uint32_t T,
                                           uint32_t rtake, uint32_t gt_before, uint32_t eq_before,
                                           uint32_t k, int32_t idx_base, int32_t* __restrict__ oi,
-                                          float* __restrict__ ov, float* __restrict__ r, bool vec,
-                                          const uint2* __restrict__ cw, uint32_t tau_hi) {
+                                          float* __restrict__ ov, float* __restrict__ r, bool vec) {
 #pragma unroll
   for (int j = 0; j < V; ++j) {
     if (j * 256 >= n_w) break;  // wave-uniform
@@ -304,18 +290,7 @@ __device__ __forceinline__ void wave_emit(uint32_t (&a)[V][4], int n_w, int lane
     for (int c = 0; c < 4; ++c) {
       const bool sel = fg[c] || (fe[c] && eb < rtake);
       const uint32_t pos = gb + (eb < rtake ? eb : rtake);
-      if (MODE == EMIT_CAND) {
-        const bool zeroed = (a[j][c] & 0x7FFFFFFFu) >= tau_hi;  // what the streaming pass assumed
-        if (e + c < n_w && (sel || zeroed)) {
-          const int32_t index = (int32_t)cw[e + c].x;
-          if (sel && pos < k) {  // pos < k always holds; the check keeps a wrong T from writing out of bounds
-            ov[pos] = __uint_as_float(a[j][c]);
-            oi[pos] = index;
-          }
-          if (sel && !zeroed) r[index] = 0.0f;
-          if (!sel && zeroed) r[index] = __uint_as_float(a[j][c]);
-        }
-      } else if (sel && pos < k) {
+      if (sel && pos < k) {  // pos < k always holds; the check keeps a wrong T from writing out of bounds
         ov[pos] = __uint_as_float(a[j][c]);
         oi[pos] = idx_base + e + c;
         if (MODE == EMIT_FULL) a[j][c] = 0u; else r[e + c] = 0.0f;
@@ -338,22 +313,11 @@ __device__ __forceinline__ uint32_t mix32(uint32_t x) {
   return x;
 }
 
-// ------------------------------------------------------------------ zero -----
-__global__ void k_zero_u32(uint32_t* __restrict__ p, int64_t n) {
-  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const int64_t step = (int64_t)gridDim.x * blockDim.x;
-  for (; i < n; i += step) p[i] = 0u;
-}
-
 // ------------------------------------------------------------------ small ----
-// One workgroup per layer (CAND = false) or per candidate list of a large layer
-// (CAND = true); the values live in registers between the single read and the write.
-template <int NW, int V, bool CAND>
+// One workgroup per layer; the values live in registers between the single read and the write.
+template <int NW, int V>
 __global__ __launch_bounds__(NW * 64) void k_small(const SegDesc* __restrict__ segs,
                                                    const int32_t* __restrict__ list,
-                                                   const LargeSeg* __restrict__ lsegs,
-                                                   const LState* __restrict__ lstate,
-                                                   const uint2* __restrict__ cand,
                                                    const float* __restrict__ grad,
                                                    float* __restrict__ res, float lr,
                                                    int32_t* __restrict__ out_idx,
@@ -366,35 +330,14 @@ __global__ __launch_bounds__(NW * 64) void k_small(const SegDesc* __restrict__ s
   __shared__ uint32_t s_wg[NW], s_we[NW];
 
   const int tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
-  SegDesc sd;
-  int n;
-  const uint2* cw = nullptr;
-  uint32_t tau_hi = 0xFFFFFFFFu;
-  if (CAND) {
-    const int li = list[blockIdx.x];
-    const LargeSeg ls = lsegs[li];
-    const LState st = lstate[li];
-    if (st.mode != MODE_SPARSE) return;  // uniform over the workgroup
-    tau_hi = st.tau_hi;
-    sd = segs[ls.seg];
-    n = (int)st.ncand;
-    cw = cand + ls.cand_base + (int64_t)w * CH;
-  } else {
-    sd = segs[list[blockIdx.x]];
-    n = sd.d;
-  }
-  const int n_w = n - w * CH;
+  const SegDesc sd = segs[list[blockIdx.x]];
+  const int n_w = sd.d - w * CH;
   float* r = res + sd.offset + (int64_t)w * CH;
-  bool vec = false;
+  const float* g = grad + sd.offset + (int64_t)w * CH;
+  const bool vec = aligned16(g, r);
 
   uint32_t a[V][4];
-  if (CAND) {
-    load_cand_bits<V>(cw, n_w, lane, a);
-  } else {
-    const float* g = grad + sd.offset + (int64_t)w * CH;
-    vec = aligned16(g, r);
-    load_acc<V>(g, r, n_w, lr, vec, lane, a);
-  }
+  load_acc<V>(g, r, n_w, lr, vec, lane, a);
 
   uint32_t T, rtake;
   block_radix_select<NT, V>(a, n_w, lane, (uint32_t)sd.k, s_hist, s_wt, s_sel, T, rtake);
@@ -407,41 +350,93 @@ __global__ __launch_bounds__(NW * 64) void k_small(const SegDesc* __restrict__ s
   __syncthreads();
   uint32_t gb = 0, eb = 0;
   for (int i = 0; i < w; ++i) { gb += s_wg[i]; eb += s_we[i]; }
-  if (CAND)
-    wave_emit<V, EMIT_CAND>(a, n_w, lane, T, rtake, gb, eb, (uint32_t)sd.k, 0, out_idx + sd.out_offset,
-                            out_val + sd.out_offset, res + sd.offset, false, cw, tau_hi);
-  else
-    wave_emit<V, EMIT_FULL>(a, n_w, lane, T, rtake, gb, eb, (uint32_t)sd.k, w * CH, out_idx + sd.out_offset,
-                            out_val + sd.out_offset, r, vec, nullptr, 0u);
+  wave_emit<V, EMIT_FULL>(a, n_w, lane, T, rtake, gb, eb, (uint32_t)sd.k, w * CH, out_idx + sd.out_offset,
+                          out_val + sd.out_offset, r, vec);
 }
 
-// ------------------------------------------------------------------ sample ---
+// ------------------------------------------------------------------ prep -----
+// Finds, in a histogram whose bins are ordered by key, the bin that holds the entry of rank
+// `rank` (1-based, counted from the top bin downwards) and that entry's rank inside the bin.
+// Returns false if the histogram holds fewer than `rank` entries.  Contains barriers; every
+// thread gets the result.
+template <int NT>
+__device__ __forceinline__ bool find_rank(const uint32_t* hist, int nb, uint32_t rank, uint32_t* s_wt,
+                                          uint32_t* s_sel, uint32_t& bin, uint32_t& rank_in_bin) {
+  __syncthreads();
+  if (threadIdx.x == 0) { s_sel[0] = 0u; s_sel[1] = 0u; }
+  __syncthreads();
+  block_find_bucket<NT>(hist, nb, rank, s_wt, s_sel);
+  bin = s_sel[0];
+  rank_in_bin = s_sel[1];
+  return rank_in_bin != 0u;
+}
+
+template <int NT>
+__device__ __forceinline__ uint32_t block_max(uint32_t v, uint32_t* s_wt) {
+  const int lane = lane_id(), w = threadIdx.x >> 6;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const uint32_t t = __shfl_xor(v, o, 64);
+    v = t > v ? t : v;
+  }
+  __syncthreads();
+  if (lane == 0) s_wt[w] = v;
+  __syncthreads();
+  uint32_t m = 0;
+#pragma unroll
+  for (int i = 0; i < NT / 64; ++i) m = s_wt[i] > m ? s_wt[i] : m;
+  return m;
+}
+
+// Sum of a and of b over the workgroup (two barriers; s_tmp holds 2 * NT / 64 words).
+template <int NT>
+__device__ __forceinline__ void block_sum2(uint32_t& a, uint32_t& b, uint32_t* s_tmp) {
+  constexpr int NW = NT / 64;
+  const int lane = lane_id(), w = threadIdx.x >> 6;
+  a = wave_sum(a);
+  b = wave_sum(b);
+  __syncthreads();
+  if (lane == 0) { s_tmp[w] = a; s_tmp[NW + w] = b; }
+  __syncthreads();
+  uint32_t ta = 0, tb = 0;
+#pragma unroll
+  for (int i = 0; i < NW; ++i) { ta += s_tmp[i]; tb += s_tmp[NW + i]; }
+  a = ta;
+  b = tb;
+}
+
 // Threshold guess for one large layer: form acc on up to 256 pieces of 64 (V = 4) or 256
 // (V = 16) consecutive elements spread over the layer (with a hashed offset inside each
-// stride), and take the sample's `sample_rank`-th largest key as tau and its
-// `sample_rank_hi`-th largest (the sample's estimate of the layer's k-th largest) as tau_hi.
-// Missing sample slots count as key 0.
-template <int V>
-__device__ __forceinline__ void sample_layer(const LargeSeg& ls, int li, const SegDesc& sd,
-                                             const float* __restrict__ grad, const float* __restrict__ res,
-                                             float lr, LState* __restrict__ lstate, uint32_t* s_hist,
-                                             uint32_t* s_wt, uint32_t* s_sel) {
-  constexpr int NT = 1024;  // 16 waves; a wave takes 4 pieces per round
-  const int tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
-  const float* g = grad + sd.offset;
-  const float* r = res + sd.offset;
-  const bool vec = aligned16(g, r);
-  // V = 4: a round of a wave covers 4 pieces of 64 elements (16 lanes each); the large sample
-  // (V = 16) takes the same number of pieces, each 256 elements long (one wave round), so that
-  // it touches no more pages than the small one
-  constexpr int PL = V == 4 ? kSamplePiece : 256;       // piece length
-  constexpr int LP = PL / 4;                            // lanes per piece
-  constexpr int PR = 64 / LP;                           // pieces per wave round
-  uint32_t a[V][4];
+// stride); tau is a key that at least `sample_rank` sample keys reach (and few more), t_est one
+// that at least `sample_rank_hi` reach: the sample's estimate of the layer's k-th largest key.
+// Any value would be correct (the guess is verified by counting); a good one keeps the
+// candidates few.  Missing sample slots count as key 0.
+//
+// The two keys come from two histograms over 1024 linear bins, which spread the top of the
+// sample evenly (bins of exponent bits would put it all into a handful of LDS words):
+// first the per-thread maxima over the 2^26 key steps below the largest sample key M, which
+// gives a floor F that at least `sample_rank` thread maxima reach; then the sample entries at
+// or above F over [F, M].  The lower edge of the bin that holds a rank is returned, so the
+// threshold may admit the few sample entries that share that bin.  Ranks above 1024 (very
+// dense layers) and samples whose top spans more than 2^26 key steps take an exact radix
+// select instead.
+// Keys of one batch of the sample: 4 wave rounds (16 keys per thread).  BATCHES = 1: a round of a
+// wave covers 4 pieces of 64 elements (16 lanes each); BATCHES = 4 (the large sample): the same
+// number of pieces, each 256 elements long (one wave round), so that it touches no more pages
+// than the small one.
+template <int BATCHES>
+__device__ __forceinline__ void sample_batch(int batch, const LargeSeg& ls, int li, const SegDesc& sd,
+                                             const float* __restrict__ g, const float* __restrict__ r, bool vec,
+                                             float lr, int lane, int w, uint32_t (&a)[4][4]) {
+  constexpr int V = 4 * BATCHES;
+  constexpr int PL = BATCHES == 1 ? kSamplePiece : kSamplePieceBig;  // piece length
+  constexpr int LP = PL / 4;                                         // lanes per piece
+  constexpr int PR = 64 / LP;                                        // pieces per wave round
 #pragma unroll
-  for (int j = 0; j < V; ++j) {
+  for (int jj = 0; jj < 4; ++jj) {
+    const int j = batch * 4 + jj;
     const int piece = w * (V * PR) + j * PR + (lane / LP);
-    a[j][0] = a[j][1] = a[j][2] = a[j][3] = 0u;
+    a[jj][0] = a[jj][1] = a[jj][2] = a[jj][3] = 0u;
     if (piece < ls.sample_pieces) {
       int start = piece * ls.sample_stride;
       if (ls.sample_stride > PL)
@@ -451,66 +446,173 @@ __device__ __forceinline__ void sample_layer(const LargeSeg& ls, int li, const S
       if (vec && e + 3 < sd.d) {
         const float4 gv = *reinterpret_cast<const float4*>(g + e);
         const float4 rv = *reinterpret_cast<const float4*>(r + e);
-        a[j][0] = acc_bits(gv.x, rv.x, lr);
-        a[j][1] = acc_bits(gv.y, rv.y, lr);
-        a[j][2] = acc_bits(gv.z, rv.z, lr);
-        a[j][3] = acc_bits(gv.w, rv.w, lr);
+        a[jj][0] = acc_bits(gv.x, rv.x, lr);
+        a[jj][1] = acc_bits(gv.y, rv.y, lr);
+        a[jj][2] = acc_bits(gv.z, rv.z, lr);
+        a[jj][3] = acc_bits(gv.w, rv.w, lr);
       } else {
 #pragma unroll
         for (int c = 0; c < 4; ++c)
-          if (e + c < sd.d) a[j][c] = acc_bits(g[e + c], r[e + c], lr);
+          if (e + c < sd.d) a[jj][c] = acc_bits(g[e + c], r[e + c], lr);
       }
     }
-  }
-  // The large sample first finds a lower bound of the rank-j key, so that the selections below
-  // add a few hundred entries to their histograms instead of 65536 whose exponents share a
-  // handful of LDS bins (measured 2.5x faster on normal data; not worth its own selection for
-  // the small sample): the j-th largest of the 1024 per-thread maxima is the j-th largest of a
-  // subset of the sample.
-  uint32_t floor_key = 0u, rtake;
-  if (V == 16 && ls.sample_rank <= NT) {  // uniform over the workgroup
-    uint32_t mx[1][4] = {{0u, 0u, 0u, 0u}};
 #pragma unroll
-    for (int j = 0; j < V; ++j) {
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const uint32_t key = a[j][c] & 0x7FFFFFFFu;
-        mx[0][0] = key > mx[0][0] ? key : mx[0][0];
-      }
-    }
-    // one value per thread in component 0; the empty components (key 0) stay below the floor 1
-    block_radix_select<NT, 1>(mx, 256, lane, (uint32_t)ls.sample_rank, s_hist, s_wt, s_sel, floor_key, rtake, 1u);
-  }
-  uint32_t T, Thi = 0xFFFFFFFFu;
-  block_radix_select<NT, V>(a, V * 256, lane, (uint32_t)ls.sample_rank, s_hist, s_wt, s_sel, T, rtake, floor_key);
-  if (ls.sample_rank_hi > 0)  // uniform over the workgroup
-    block_radix_select<NT, V>(a, V * 256, lane, (uint32_t)ls.sample_rank_hi, s_hist, s_wt, s_sel, Thi, rtake,
-                              floor_key);
-  if (tid == 0) {
-    lstate[li].tau = T;
-    lstate[li].tau_hi = Thi;  // >= T because sample_rank_hi <= sample_rank
+    for (int c = 0; c < 4; ++c) a[jj][c] &= 0x7FFFFFFFu;
   }
 }
 
-// One workgroup per sampled layer.  BIG: the table holds layers with the large sample; those
-// workgroups take the V = 16 path.
+// Threshold guess for one large layer: form acc on up to 256 pieces of 64 (BATCHES = 1) or 256
+// (BATCHES = 4) consecutive elements spread over the layer (with a hashed offset inside each
+// stride); tau is a key that at least `sample_rank` sample keys reach (and few more), t_est one
+// that at least `sample_rank_hi` reach: the sample's estimate of the layer's k-th largest key.
+// Any value would be correct (the guess is verified by counting); a good one keeps the
+// candidates few.  Missing sample slots count as key 0.
+//
+// The two keys come from two histograms over 1024 linear bins, which spread the top of the
+// sample evenly (bins of exponent bits would put it all into a handful of LDS words):
+// first the per-thread maxima over the 2^26 key steps below the largest sample key M, which
+// gives a floor F that at least `sample_rank` thread maxima reach; then the sample entries at
+// or above F over [F, M] (the sample is read a second time: it is in cache, and the large
+// sample would not fit the registers).  The lower edge of the bin that holds a rank is
+// returned, so the threshold may admit the few sample entries that share that bin.  Ranks
+// above 1024 (very dense layers) and samples whose top spans more than 2^26 key steps take an
+// exact radix select over the first batch instead, with the ranks scaled to it.
+template <int BATCHES>
+__device__ __forceinline__ void sample_layer(const LargeSeg& ls, int li, const SegDesc& sd,
+                                             const float* __restrict__ grad, const float* __restrict__ res,
+                                             float lr, uint32_t* s_hist, uint32_t* s_wt, uint32_t* s_sel,
+                                             uint32_t& tau, uint32_t& t_est) {
+  constexpr int NT = 1024;  // 16 waves; a wave takes 4 pieces per round
+  const int tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
+  const float* g = grad + sd.offset;
+  const float* r = res + sd.offset;
+  const bool vec = aligned16(g, r);
+  const uint32_t rank = (uint32_t)ls.sample_rank, rank_hi = (uint32_t)ls.sample_rank_hi;
+  uint32_t a[4][4];
+  uint32_t mx = 0u;
+  for (int batch = BATCHES - 1; batch >= 0; --batch) {  // batch 0 last: it stays in the registers
+    sample_batch<BATCHES>(batch, ls, li, sd, g, r, vec, lr, lane, w, a);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+#pragma unroll
+      for (int c = 0; c < 4; ++c) mx = a[j][c] > mx ? a[j][c] : mx;
+    }
+  }
+  const uint32_t M = block_max<NT>(mx, s_wt);
+  bool fast = rank <= (uint32_t)NT;  // uniform over the workgroup
+  uint32_t F = 0u, bin, rib;
+  if (fast) {
+    const uint32_t L1 = M > 0x03FFFFFFu ? M - 0x03FFFFFFu : 0u;
+    s_hist[tid] = 0u;
+    __syncthreads();
+    if (mx >= L1) atomicAdd(&s_hist[(mx - L1) >> 16], 1u);
+    fast = find_rank<NT>(s_hist, 1024, rank, s_wt, s_sel, bin, rib);
+    F = L1 + (bin << 16);
+  }
+  if (fast) {
+    int s2 = 0;
+    while (((M - F) >> s2) >= 1024u) ++s2;
+    __syncthreads();
+    s_hist[tid] = 0u;
+    __syncthreads();
+    for (int batch = 0; batch < BATCHES; ++batch) {
+      if (batch > 0) sample_batch<BATCHES>(batch, ls, li, sd, g, r, vec, lr, lane, w, a);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+          if (a[j][c] >= F) atomicAdd(&s_hist[(a[j][c] - F) >> s2], 1u);
+      }
+    }
+    // at least `rank` entries reach F, so both ranks are found
+    tau = F;
+    t_est = F;
+    if (find_rank<NT>(s_hist, 1024, rank_hi, s_wt, s_sel, bin, rib)) t_est = F + (bin << s2);
+    if (find_rank<NT>(s_hist, 1024, rank, s_wt, s_sel, bin, rib)) tau = F + (bin << s2);
+    // If the bin of tau holds clearly more sample entries than the rank needs (keys that lie
+    // closer together than the bins are wide: quantised or narrow data), its lower edge would
+    // admit them all: resolve the rank inside the bin, 1024 finer bins at a time.
+    uint32_t extra = rib != 0u ? s_hist[bin] - rib : 0u;
+    while (s2 > 0 && extra > 4u) {  // uniform over the workgroup
+      const uint32_t lo = tau, width = 1u << s2, want = rib;
+      s2 = s2 > 10 ? s2 - 10 : 0;
+      __syncthreads();
+      s_hist[tid] = 0u;
+      __syncthreads();
+      for (int batch = 0; batch < BATCHES; ++batch) {
+        if (BATCHES > 1) sample_batch<BATCHES>(batch, ls, li, sd, g, r, vec, lr, lane, w, a);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+#pragma unroll
+          for (int c = 0; c < 4; ++c)
+            if (a[j][c] >= lo && a[j][c] - lo < width) atomicAdd(&s_hist[(a[j][c] - lo) >> s2], 1u);
+        }
+      }
+      if (!find_rank<NT>(s_hist, 1024, want, s_wt, s_sel, bin, rib)) break;  // cannot happen: the bin held `want`
+      tau = lo + (bin << s2);
+      extra = s_hist[bin] - rib;
+    }
+  } else {
+    uint32_t rtake;
+    const uint32_t r1 = rank / BATCHES > 0 ? rank / BATCHES : 1u, r2 = rank_hi / BATCHES > 0 ? rank_hi / BATCHES : 1u;
+    block_radix_select<NT, 4>(a, 4 * 256, lane, r1, s_hist, s_wt, s_sel, tau, rtake);
+    block_radix_select<NT, 4>(a, 4 * 256, lane, r2, s_hist, s_wt, s_sel, t_est, rtake);
+  }
+  if (t_est < tau) t_est = tau;
+}
+
+// One workgroup per large layer: clears the layer's per-call scratch (candidate buckets, flags,
+// and, when the multi-pass kernels will run, their histograms and work counter) and guesses
+// the threshold of a sampled layer.  BIG: the table holds layers with the large sample; those
+// workgroups take the four-batch path.
 template <bool BIG>
-__global__ __launch_bounds__(1024) void k_sample(const SegDesc* __restrict__ segs,
-                                                 const int32_t* __restrict__ sampled,
-                                                 const LargeSeg* __restrict__ lsegs,
-                                                 const float* __restrict__ grad,
-                                                 const float* __restrict__ res, float lr,
-                                                 LState* __restrict__ lstate) {
+__global__ __launch_bounds__(1024) void k_prep(const SegDesc* __restrict__ segs,
+                                               const LargeSeg* __restrict__ lsegs,
+                                               const float* __restrict__ grad,
+                                               const float* __restrict__ res, float lr,
+                                               LState* __restrict__ lstate, uint32_t* __restrict__ bh,
+                                               uint32_t* __restrict__ ghist, uint32_t* __restrict__ counters,
+                                               int chain) {
   __shared__ uint32_t s_hist[kBins0];
   __shared__ uint32_t s_wt[16];
   __shared__ uint32_t s_sel[2];
-  const int li = sampled[blockIdx.x];
+  const int li = blockIdx.x, tid = threadIdx.x;
   const LargeSeg ls = lsegs[li];
+  static_assert(kFineBins == 4096 && kHistStride == 4096, "one 16-byte store per thread clears either");
+  reinterpret_cast<uint4*>(bh + (int64_t)li * kFineBins)[tid] = make_uint4(0u, 0u, 0u, 0u);
+  if (chain) {
+    reinterpret_cast<uint4*>(ghist + (int64_t)li * kHistStride)[tid] = make_uint4(0u, 0u, 0u, 0u);
+    if (li == 0 && tid < 16) counters[tid] = 0u;
+  }
+  if (!ls.sampled) {  // uniform over the workgroup
+    if (tid == 0) {
+      LState st = {};
+      st.mode = MODE_DENSE;
+      st.route = 3u;
+      lstate[li] = st;
+    }
+    return;
+  }
   const SegDesc sd = segs[ls.seg];
+  uint32_t tau, t_est;
   if (BIG && ls.sample_big)  // uniform over the workgroup
-    sample_layer<16>(ls, li, sd, grad, res, lr, lstate, s_hist, s_wt, s_sel);
+    sample_layer<4>(ls, li, sd, grad, res, lr, s_hist, s_wt, s_sel, tau, t_est);
   else
-    sample_layer<4>(ls, li, sd, grad, res, lr, lstate, s_hist, s_wt, s_sel);
+    sample_layer<1>(ls, li, sd, grad, res, lr, s_hist, s_wt, s_sel, tau, t_est);
+  if (tid == 0) {
+    // bucket width: the distance from tau to the estimate of the k-th largest key spans 512 to
+    // 1023 buckets, so the 4096 buckets reach four to eight times that distance above tau
+    const uint32_t delta = t_est - tau;
+    uint32_t shift = 0;
+    while ((delta >> shift) >= 1024u) ++shift;
+    const uint64_t top = (uint64_t)tau + ((uint64_t)kFineBins << shift);
+    LState st = {};
+    st.tau = tau;
+    st.tau_top = top > 0x80000000ull ? 0x80000000u : (uint32_t)top;  // keys are below 2^31
+    st.shift = shift;
+    st.mode = MODE_DENSE;
+    lstate[li] = st;
+  }
 }
 
 // ------------------------------------------------------------------ stream ---
@@ -528,73 +630,85 @@ __device__ __forceinline__ void store_bits_nt(float* __restrict__ r, int lane, c
 // Candidate collection of one tile inside the streaming pass (all waves of the workgroup call
 // it; contains one barrier).  Every entry with key >= tau goes, in index order, into the
 // tile's slots (entries beyond nslot are dropped; the count written to *cnt then exceeds nslot
-// and marks the tile as overflowed), and collected entries with key >= tau_hi are replaced by
-// zero in `a`.  FULL: the wave's chunk is complete, no bounds checks.
+// and marks the tile as overflowed).  A candidate below tau_top adds one to its bucket of the
+// layer's histogram; those at or above tau_top are counted in the upper half of *cnt.
+// FULL: the wave's chunk is complete, no bounds checks.
 template <int NW, int V, bool FULL>
-__device__ __forceinline__ void stream_collect(uint32_t (&a)[V][4], int n_w, int lane, int w, uint32_t tau,
-                                               uint32_t tau_hi, int32_t idx0, uint2* __restrict__ slot,
-                                               int nslot, uint32_t* __restrict__ cnt, uint32_t* s_cnt) {
+__device__ __forceinline__ void stream_collect(const uint32_t (&a)[V][4], int n_w, int lane, int w, uint32_t tau,
+                                               uint32_t tau_top, uint32_t shift, int32_t idx0,
+                                               uint2* __restrict__ slot, int nslot, uint32_t* __restrict__ cnt,
+                                               uint32_t* __restrict__ bh, uint32_t* s_cnt) {
   // one ballot per element slot of the wave; bitwise & keeps the code free of branches
   uint64_t m[V][4];
+  uint32_t wtop = 0;
 #pragma unroll
   for (int j = 0; j < V; ++j) {
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
-      const bool ge = (a[j][c] & 0x7FFFFFFFu) >= tau;
-      if (FULL) m[j][c] = __builtin_amdgcn_ballot_w64(ge);
-      else m[j][c] = __builtin_amdgcn_ballot_w64(ge & (j * 256 + lane * 4 + c < n_w));
+      const uint32_t key = a[j][c] & 0x7FFFFFFFu;
+      const bool valid = FULL ? true : (j * 256 + lane * 4 + c < n_w);
+      m[j][c] = __builtin_amdgcn_ballot_w64((key >= tau) & valid);
+      wtop += (uint32_t)__popcll(__builtin_amdgcn_ballot_w64((key >= tau_top) & valid));
     }
   }
   uint32_t wtot = 0;
 #pragma unroll
   for (int j = 0; j < V; ++j)
     wtot += (uint32_t)(__popcll(m[j][0]) + __popcll(m[j][1]) + __popcll(m[j][2]) + __popcll(m[j][3]));
-  if (lane == 0) s_cnt[w] = wtot;
+  if (lane == 0) s_cnt[w] = wtot | (wtop << 16);  // each at most 1024 per wave, 4096 per tile
   __syncthreads();
   uint32_t base = 0, total = 0;
 #pragma unroll
   for (int i = 0; i < NW; ++i) {
     const uint32_t t = s_cnt[i];
-    if (i < w) base += t;
+    if (i < w) base += t & 0xFFFFu;
     total += t;
   }
   if (threadIdx.x == 0) *cnt = total;
   if (wtot == 0) return;  // wave-uniform
+  // A tile that overflows its slots rejects the layer's guess: its bucket counts are not needed
+  // (and a tile full of equal keys would send thousands of atomics to one address).
+  const bool counted = (total & 0xFFFFu) <= (uint32_t)nslot;  // uniform over the workgroup
+  // The first bucket the wave meets is counted in a scalar and added once at the end, so that
+  // many candidates with one key (quantised values) cost one atomic per wave.
+  uint32_t hot = 0xFFFFFFFFu, hot_n = 0;
 #pragma unroll
   for (int j = 0; j < V; ++j) {
     const uint32_t tot =
         (uint32_t)(__popcll(m[j][0]) + __popcll(m[j][1]) + __popcll(m[j][2]) + __popcll(m[j][3]));
     if (tot) {  // wave-uniform
       const int e = j * 256 + lane * 4;
-      // slot of the lane's first candidate of this round, then one predicated store and one
-      // select per component
+      // slot of the lane's first candidate of this round, then one predicated store per component
       uint32_t pos = base + mbcnt64(m[j][0]) + mbcnt64(m[j][1]) + mbcnt64(m[j][2]) + mbcnt64(m[j][3]);
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
         const uint32_t key = a[j][c] & 0x7FFFFFFFu;
         const bool f = FULL ? key >= tau : ((key >= tau) & (e + c < n_w));
-        const bool put = f & (pos < (uint32_t)nslot);
-        if (put) slot[pos] = make_uint2((uint32_t)(idx0 + e + c), a[j][c]);
-        // an entry at or above tau_hi is expected to be kept: its residual is written as zero
-        // right here (its value is safe in the slot); the final pass corrects the few entries
-        // for which that expectation turns out wrong
-        a[j][c] = (put & (key >= tau_hi)) ? 0u : a[j][c];
+        if (f & (pos < (uint32_t)nslot)) slot[pos] = make_uint2((uint32_t)(idx0 + e + c), a[j][c]);
         pos += f ? 1u : 0u;
+        if (counted && m[j][c]) {  // wave-uniform
+          const uint32_t b = (f & (key < tau_top)) ? (key - tau) >> shift : 0xFFFFFFFFu;
+          const uint64_t act = __ballot(b != 0xFFFFFFFFu);
+          if (act) {  // wave-uniform
+            if (hot == 0xFFFFFFFFu) hot = (uint32_t)__builtin_amdgcn_readlane((int)b, __builtin_ctzll(act));
+            hot_n += (uint32_t)__popcll(__ballot(b == hot));
+            if (b != hot && b != 0xFFFFFFFFu) atomicAdd(&bh[b], 1u);
+          }
+        }
       }
       base += tot;
     }
   }
+  if (lane == 0 && hot_n) atomicAdd(&bh[hot], hot_n);
 }
 
 // The one pass over grad and residual of every large layer: acc = residual + lr*grad is
 // written into the residual buffer (it is the final residual everywhere but at the k kept
 // entries).  Tiles of sampled layers also collect, in index order, the entries with
-// key >= tau into the tile's slots, and write zero instead of acc for the collected entries
-// with key >= tau_hi (the sample's estimate of the k-th largest key: most of them are kept, so
-// most kept entries get their zero in this pass instead of a scattered write later); tiles of
-// the other layers add to the layer's histogram of key bits 30..20.  Both arrays are touched
-// exactly once, so full aligned tiles use non-temporal 16-byte loads and stores.  The launch
-// adds kStreamLdsPad bytes of unused dynamic LDS per workgroup to cap the workgroups per CU.
+// key >= tau into the tile's slots and count them by bucket; tiles of the other layers add to
+// the layer's histogram of key bits 30..20.  Both arrays are touched exactly once, so full
+// aligned tiles use non-temporal 16-byte loads and stores.  The launch adds kStreamLdsPad bytes
+// of unused dynamic LDS per workgroup to cap the workgroups per CU.
 template <int NW, int V>
 __global__ __launch_bounds__(NW * 64) void k_stream(const TileDesc* __restrict__ tiles,
                                                 const float* __restrict__ grad,
@@ -602,6 +716,7 @@ __global__ __launch_bounds__(NW * 64) void k_stream(const TileDesc* __restrict__
                                                 const LState* __restrict__ lstate,
                                                 uint32_t* __restrict__ chunk_cnt,
                                                 uint2* __restrict__ slots, int nslot,
+                                                uint32_t* __restrict__ bh,
                                                 uint32_t* __restrict__ ghist) {
   __shared__ uint32_t s_hist[kBins0];
   __shared__ uint32_t s_cnt[NW];
@@ -610,10 +725,11 @@ __global__ __launch_bounds__(NW * 64) void k_stream(const TileDesc* __restrict__
   const TileDesc td = tiles[blockIdx.x];
   const int tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
   const bool collect = td.ctile >= 0;  // uniform over the workgroup
-  uint32_t tau = 0, tau_hi = 0xFFFFFFFFu;
+  uint32_t tau = 0, tau_top = 0, shift = 0;
   if (collect) {
     tau = lstate[td.seg].tau;
-    tau_hi = lstate[td.seg].tau_hi;
+    tau_top = lstate[td.seg].tau_top;
+    shift = lstate[td.seg].shift;
   } else {
     for (int i = tid; i < kBins0; i += NT) s_hist[i] = 0u;
   }
@@ -644,9 +760,10 @@ __global__ __launch_bounds__(NW * 64) void k_stream(const TileDesc* __restrict__
   if (collect) {
     uint2* slot = slots + (int64_t)td.ctile * nslot;
     uint32_t* cnt = chunk_cnt + td.ctile;
+    uint32_t* bhl = bh + (int64_t)td.seg * kFineBins;
     const int32_t idx0 = td.local0 + w * WC;
-    if (fast) stream_collect<NW, V, true>(a, n_w, lane, w, tau, tau_hi, idx0, slot, nslot, cnt, s_cnt);
-    else stream_collect<NW, V, false>(a, n_w, lane, w, tau, tau_hi, idx0, slot, nslot, cnt, s_cnt);
+    if (fast) stream_collect<NW, V, true>(a, n_w, lane, w, tau, tau_top, shift, idx0, slot, nslot, cnt, bhl, s_cnt);
+    else stream_collect<NW, V, false>(a, n_w, lane, w, tau, tau_top, shift, idx0, slot, nslot, cnt, bhl, s_cnt);
     if (fast) store_bits_nt<V>(r, lane, a);
     else store_bits<V>(r, n_w, vec, lane, a);
   } else {
@@ -670,188 +787,460 @@ __global__ __launch_bounds__(NW * 64) void k_stream(const TileDesc* __restrict__
   }
 }
 
-// Per large layer: exclusive scan of the chunks' candidate counts, the verdict on the
-// guess (MODE_SPARSE iff no chunk overflowed, at least k candidates, list fits), and, for
-// layers in MODE_DENSE, their tiles appended to the work list of the fallback kernels.
-__global__ __launch_bounds__(1024) void k_cscan(const SegDesc* __restrict__ segs,
-                                                const LargeSeg* __restrict__ lsegs,
-                                                LState* __restrict__ lstate,
-                                                const uint32_t* __restrict__ chunk_cnt, int nslot,
-                                                uint32_t* __restrict__ chunk_off,
-                                                uint32_t* __restrict__ counter,
-                                                int32_t* __restrict__ items) {
-  __shared__ uint32_t s_wt[16];
-  __shared__ uint32_t s_base;
-  const int li = blockIdx.x;
-  const LargeSeg ls = lsegs[li];
-  const int tid = threadIdx.x;
-  uint32_t mode = MODE_DENSE;
-  if (ls.cand_class != CAND_NONE) {  // uniform over the workgroup
-    uint32_t carry = 0;
-    int over = 0;
-    for (int base = ls.chunk_begin; base < ls.chunk_end; base += 8192) {
-      const int i0 = base + tid * 8;
-      uint32_t v[8], s = 0;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        v[e] = (i0 + e < ls.chunk_end) ? chunk_cnt[i0 + e] : 0u;
-        over |= v[e] > (uint32_t)nslot;
-        s += v[e];
-      }
-      uint32_t tot;
-      const uint32_t incl = block_incl_scan<1024>(s, s_wt, tot);
-      uint32_t run = carry + incl - s;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        if (i0 + e < ls.chunk_end) chunk_off[i0 + e] = run;
-        run += v[e];
-      }
-      carry += tot;
-    }
-    over = __syncthreads_or(over);
-    const uint32_t k = (uint32_t)segs[ls.seg].k;
-    if (!over && carry >= k && carry <= (uint32_t)ls.cap) mode = MODE_SPARSE;
-    if (tid == 0) lstate[li].ncand = carry;
-  }
-  if (tid == 0) lstate[li].mode = mode;
-  if (mode == MODE_DENSE) {
-    const int nt = ls.tile_end - ls.tile_begin;
-    if (tid == 0) s_base = atomicAdd(counter, (uint32_t)nt);
-    __syncthreads();
-    const uint32_t b = s_base;
-    for (int j = tid; j < nt; j += 1024) items[b + j] = ls.tile_begin + j;
-  }
-}
+// ------------------------------------------------------------------ finish ---
+// After the streaming pass a sampled layer's candidates sit in its tiles' slots (index order
+// inside a tile, tiles in index order) and are counted per bucket.  The finish
+//   decides   whether the guess held (at least k candidates, no tile overflowed) and which
+//             bucket b* holds the k-th largest key, so that every candidate above b* is kept
+//             and k_rem of the entries in b* (the "band", at most kBandCap) are;
+//   phase A   counts per wave chunk (32 tiles) the candidates above b* and collects the band;
+//   selects   among the band the entry of rank k_rem in the order (key descending, index
+//             ascending): its key T and index I fix the kept set, key > T or key == T and index <= I;
+//   phase B   writes the kept pairs in index order (position = kept entries of the earlier wave
+//             chunks + kept band entries with a smaller index + rank inside the wave chunk) and
+//             zeroes their residual.
+// Small layers do all of it in one workgroup (k_finish); large ones decide in k_finish and run
+// the phases as one launch each over groups of 128 tiles, every workgroup of phase B selecting
+// T and I for itself from the band.  No workgroup ever waits for another one.
 
-// Copy the tiles' slots into the layer's contiguous candidate list (index order is kept
-// because tiles are laid out in index order); for layers whose guess was rejected, undo the
-// streaming pass's early zeros instead.  A wave takes 64 consecutive tiles; lane l
-// learns tile l's count and destination, then the wave copies all their entries 64 at a
-// time: for the e-th entry the owning tile is found by a binary search over the lanes'
-// exclusive counts (shuffles), so neighbouring lanes read neighbouring slots of one tile
-// and write neighbouring list positions.
-__global__ __launch_bounds__(256) void k_cgather(int n_chunks, const int32_t* __restrict__ chunk_lseg,
-                                                 const LargeSeg* __restrict__ lsegs,
-                                                 const LState* __restrict__ lstate,
-                                                 const uint32_t* __restrict__ chunk_cnt,
-                                                 const uint32_t* __restrict__ chunk_off,
-                                                 const uint2* __restrict__ slots, int nslot,
-                                                 uint2* __restrict__ cand,
-                                                 const SegDesc* __restrict__ segs,
-                                                 float* __restrict__ res) {
-  const int lane = lane_id();
-  const int c0 = (int)((blockIdx.x * 256u + threadIdx.x) >> 6) * 64;  // first tile of the wave
-  if (c0 >= n_chunks) return;  // wave-uniform
-  const int c = c0 + lane;
-  uint32_t cnt = 0;
-  int64_t dst = 0;
-  if (c < n_chunks) {
-    const int li = chunk_lseg[c];
-    const LState st = lstate[li];
-    if (st.mode == MODE_SPARSE) {
-      cnt = chunk_cnt[c];
-      dst = lsegs[li].cand_base + chunk_off[c];
-    } else {
-      // the layer falls back to the multi-pass route, which reads acc from the residual
-      // buffer: give the entries that the streaming pass zeroed (slotted, key >= tau_hi)
-      // their acc back.  Rare path, one lane per tile.
-      const uint32_t stored = chunk_cnt[c] < (uint32_t)nslot ? chunk_cnt[c] : (uint32_t)nslot;
-      float* rl = res + segs[lsegs[li].seg].offset;
-      const uint2* src = slots + (int64_t)c * nslot;
-      for (uint32_t q = 0; q < stored; ++q) {
-        const uint2 en = src[q];
-        if ((en.y & 0x7FFFFFFFu) >= st.tau_hi) rl[en.x] = __uint_as_float(en.y);
-      }
-    }
-  }
-  const uint32_t incl = wave_incl_scan(cnt, lane);
-  const uint32_t pre = incl - cnt;
-  const uint32_t total = __shfl(incl, 63, 64);
-  const uint32_t dst_lo = (uint32_t)dst, dst_hi = (uint32_t)(dst >> 32);
-  for (uint32_t base = 0; base < total; base += 64) {  // wave-uniform trip count
-    const bool live = base + lane < total;
-    const uint32_t e = live ? base + lane : total - 1;  // idle lanes search along, then skip the copy
-    int lo = 0, hi = 63;  // last lane whose exclusive count is <= e: the tile that owns entry e
-#pragma unroll
-    for (int step = 0; step < 6; ++step) {
-      const int mid = (lo + hi + 1) >> 1;
-      const uint32_t v = __shfl(pre, mid, 64);
-      if (v <= e) lo = mid; else hi = mid - 1;
-    }
-    const uint32_t p0 = __shfl(pre, lo, 64);
-    const uint32_t d_lo = __shfl(dst_lo, lo, 64), d_hi = __shfl(dst_hi, lo, 64);
-    if (live) {
-      const uint32_t q = e - p0;
-      const int64_t d = (int64_t)(((uint64_t)d_hi << 32) | d_lo) + q;
-      cand[d] = slots[(int64_t)(c0 + lo) * nslot + q];
-    }
-  }
-}
-
-// ------------------------------------------------------------------ multi-block select
-// The same radix-select passes serve two sources: CAND = false walks the acc values in
-// the residual buffer (fallback; tiles come from the device-built work list `items`),
-// CAND = true walks a layer's candidate list (tiles of kTile list entries).
-struct TileWork {
-  float* res;          // dense: the tile's residual data
-  const uint2* cand;   // candidate source: the tile's list entries
-  int n;               // valid entries
-  int lseg;
-  int local0;          // dense: layer-local index of the first element
-  int slot;            // index into tile_gt / tile_eq
-  bool active;         // candidate source: the layer is in MODE_SPARSE
-  bool skip_level0;    // dense: level-0 histogram already made by the streaming pass
+// A wave's view of the slots of up to 32 consecutive tiles as one flat, index-ordered list.
+struct WaveChunk {
+  int c0;           // first tile (chunk number)
+  uint32_t pre;     // lane l < 32: entries of the tiles before tile c0 + l
+  uint32_t total;   // entries of all its tiles
 };
 
-// Returns true if the tile has entries to process.
-template <bool CAND>
-__device__ __forceinline__ bool get_tile(int item, const TileDesc* __restrict__ tiles,
-                                         const int32_t* __restrict__ items, float* res,
-                                         const uint2* cand, const LState* __restrict__ lstate, int n_tiles,
-                                         TileWork& tw) {
-  if (CAND) {
-    const TileDesc td = tiles[item];
-    const LState st = lstate[td.seg];
-    tw.lseg = td.seg;
-    tw.slot = n_tiles + item;
-    tw.local0 = td.local0;
-    tw.res = nullptr;
-    tw.cand = cand + td.start;
-    tw.skip_level0 = false;
-    tw.active = st.mode == MODE_SPARSE;
-    const int left = (int)st.ncand - td.local0;
-    tw.n = left < td.n ? left : td.n;
-    return tw.active && tw.n > 0;
-  } else {
-    const int t = items[item];
-    const TileDesc td = tiles[t];
-    tw.lseg = td.seg;
-    tw.slot = t;
-    tw.local0 = td.local0;
-    tw.res = res + td.start;
-    tw.cand = nullptr;
-    tw.n = td.n;
-    tw.active = true;
-    tw.skip_level0 = td.ctile < 0;
-    return true;
+__device__ __forceinline__ WaveChunk wc_open(int c0, int c_end, const uint32_t* __restrict__ chunk_cnt, int nslot,
+                                             int lane) {
+  uint32_t cnt = 0;
+  if (lane < kWaveTiles && c0 + lane < c_end) {
+    cnt = chunk_cnt[c0 + lane] & 0xFFFFu;
+    cnt = cnt < (uint32_t)nslot ? cnt : (uint32_t)nslot;  // an overflowed tile never gets here; stay in bounds anyway
+  }
+  const uint32_t incl = wave_incl_scan(cnt, lane);
+  WaveChunk wc;
+  wc.c0 = c0;
+  wc.pre = incl - cnt;
+  wc.total = __shfl(incl, 63, 64);
+  return wc;
+}
+
+// Entry e < total of the flat list (all 64 lanes call it; e may differ per lane).
+__device__ __forceinline__ uint2 wc_entry(const WaveChunk& wc, uint32_t e, const uint2* __restrict__ slots,
+                                          int nslot) {
+  int lo = 0, hi = kWaveTiles - 1;  // last tile whose exclusive count is <= e
+#pragma unroll
+  for (int step = 0; step < 5; ++step) {
+    const int mid = (lo + hi + 1) >> 1;
+    const uint32_t v = __shfl(wc.pre, mid, 64);
+    if (v <= e) lo = mid; else hi = mid - 1;
+  }
+  const uint32_t p0 = __shfl(wc.pre, lo, 64);
+  return slots[(int64_t)(wc.c0 + lo) * nslot + (e - p0)];
+}
+
+// Phase A over one wave chunk: returns the number of candidates above bucket b* (wave-uniform)
+// and appends the entries of bucket b* to band[0 .. cap) through the LDS counter *s_nband.
+__device__ __forceinline__ uint32_t wc_phase_a(const WaveChunk& wc, const uint2* __restrict__ slots, int nslot,
+                                               uint32_t tau, uint32_t tau_top, uint32_t shift, uint32_t bstar,
+                                               uint2* band, uint32_t cap, uint32_t* s_nband, int lane) {
+  uint32_t n_gt = 0;
+  for (uint32_t base = 0; base < wc.total; base += 64) {  // wave-uniform trip count
+    const bool live = base + lane < wc.total;
+    const uint2 en = wc_entry(wc, live ? base + lane : wc.total - 1, slots, nslot);
+    const uint32_t key = en.y & 0x7FFFFFFFu;
+    const bool top = key >= tau_top;
+    const uint32_t b = (key - tau) >> shift;
+    n_gt += (uint32_t)__popcll(__ballot(live && (top || b > bstar)));
+    if (live && !top && b == bstar) {
+      const uint32_t pos = atomicAdd(s_nband, 1u);
+      if (pos < cap) band[pos] = en;
+    }
+  }
+  return n_gt;
+}
+
+// The band entry of rank k_rem (1-based) in the order (key descending, index ascending), by
+// counting for every entry how many precede it.  s_ti[0] = its key T, s_ti[1] = its index I.
+// The band has m <= kBandCap entries in LDS; 1 <= k_rem <= m.  Ends with a barrier.
+template <int NT>
+__device__ __forceinline__ void band_select(const uint2* s_band, uint32_t m, uint32_t k_rem, uint32_t* s_ti) {
+  for (uint32_t i = threadIdx.x; i < m; i += NT) {
+    const uint2 en = s_band[i];
+    const uint32_t key = en.y & 0x7FFFFFFFu;
+    uint32_t before = 0;
+    for (uint32_t q = 0; q < m; ++q) {
+      const uint2 o = s_band[q];
+      const uint32_t ok = o.y & 0x7FFFFFFFu;
+      before += (ok > key) || (ok == key && o.x < en.x);
+    }
+    if (before + 1u == k_rem) { s_ti[0] = key; s_ti[1] = en.x; }
+  }
+  __syncthreads();
+}
+
+// Kept band entries whose index is below idx0 (wave-uniform result).
+__device__ __forceinline__ uint32_t band_kept_before(const uint2* s_band, uint32_t m, uint32_t T, uint32_t I,
+                                                     uint32_t idx0, int lane) {
+  uint32_t c = 0;
+  for (uint32_t i = lane; i < m; i += 64) {
+    const uint2 en = s_band[i];
+    const uint32_t key = en.y & 0x7FFFFFFFu;
+    c += (en.x < idx0) && (key > T || (key == T && en.x <= I));
+  }
+  return wave_sum(c);
+}
+
+// Phase B over one wave chunk: the kept entries go to out[pos0 ...] in index order and their
+// residual is zeroed.  Positions are checked against k so that no state can write out of bounds.
+__device__ __forceinline__ void wc_phase_b(const WaveChunk& wc, const uint2* __restrict__ slots, int nslot,
+                                           uint32_t T, uint32_t I, uint32_t pos0, uint32_t k, int32_t d,
+                                           int32_t* __restrict__ oi, float* __restrict__ ov, float* __restrict__ rl,
+                                           int lane) {
+  for (uint32_t base = 0; base < wc.total; base += 64) {  // wave-uniform trip count
+    const bool live = base + lane < wc.total;
+    const uint2 en = wc_entry(wc, live ? base + lane : wc.total - 1, slots, nslot);
+    const uint32_t key = en.y & 0x7FFFFFFFu;
+    const bool keep = live && (key > T || (key == T && en.x <= I));
+    const uint64_t mk = __ballot(keep);
+    const uint32_t pos = pos0 + mbcnt64(mk);
+    if (keep && pos < k && en.x < (uint32_t)d) {
+      oi[pos] = (int32_t)en.x;
+      ov[pos] = __uint_as_float(en.y);
+      rl[en.x] = 0.0f;
+    }
+    pos0 += (uint32_t)__popcll(mk);
   }
 }
 
-template <bool CAND>
+// Exact selection of one layer by one workgroup from the acc values in the residual buffer:
+// three histogram passes over the layer (digits of 11 + 10 + 10 key bits), then one ordered
+// emission pass.  Slow (one workgroup walks the whole layer four times); used only where a
+// guess was rejected and the multi-pass kernels are not enqueued.
+template <int NT>
+__device__ __forceinline__ void rescue_layer(const SegDesc& sd, float* __restrict__ res,
+                                             int32_t* __restrict__ out_idx, float* __restrict__ out_val,
+                                             uint32_t* s_hist, uint32_t* s_wt, uint32_t* s_sel) {
+  const int tid = threadIdx.x, lane = lane_id();
+  float* rl = res + sd.offset;
+  int32_t* oi = out_idx + sd.out_offset;
+  float* ov = out_val + sd.out_offset;
+  uint32_t prefix = 0, mask = 0, k_rem = (uint32_t)sd.k;
+  for (int level = 0; level < 3; ++level) {
+    const int shift = level == 0 ? 20 : (level == 1 ? 10 : 0);
+    const int nb = level == 0 ? kBins0 : kBins12;
+    __syncthreads();
+    for (int i = tid; i < nb; i += NT) s_hist[i] = 0u;
+    __syncthreads();
+    for (int base = 0; base < sd.d; base += NT) {  // uniform trip count: the peeled add needs whole waves
+      const int i = base + tid;
+      uint32_t b = 0xFFFFFFFFu;
+      if (i < sd.d) {
+        const uint32_t key = __float_as_uint(rl[i]) & 0x7FFFFFFFu;
+        if ((key & mask) == prefix) b = (key >> shift) & (uint32_t)(nb - 1);
+      }
+      hist_add_peeled(s_hist, b, lane);
+    }
+    uint32_t bin, rib;
+    (void)find_rank<NT>(s_hist, nb, k_rem, s_wt, s_sel, bin, rib);  // the passes keep at least k_rem entries
+    prefix |= bin << shift;
+    mask |= (uint32_t)(nb - 1) << shift;
+    k_rem = rib;
+  }
+  const uint32_t T = prefix, rtake = k_rem;
+  uint32_t gb = 0, eb = 0;  // keys above T and equal to T before the current block of NT elements
+  for (int base = 0; base < sd.d; base += NT) {
+    const int i = base + tid;
+    uint32_t bits = 0u, fg = 0u, fe = 0u;
+    if (i < sd.d) {
+      bits = __float_as_uint(rl[i]);
+      const uint32_t key = bits & 0x7FFFFFFFu;
+      fg = key > T;
+      fe = key == T;
+    }
+    const uint32_t packed = fg | (fe << 16);
+    uint32_t tot;
+    const uint32_t excl = block_incl_scan<NT>(packed, s_wt, tot) - packed;
+    const uint32_t g0 = gb + (excl & 0xFFFFu), e0 = eb + (excl >> 16);
+    const uint32_t pos = g0 + (e0 < rtake ? e0 : rtake);
+    if ((fg || (fe && e0 < rtake)) && pos < (uint32_t)sd.k) {
+      oi[pos] = i;
+      ov[pos] = __uint_as_float(bits);
+      rl[i] = 0.0f;
+    }
+    gb += tot & 0xFFFFu;
+    eb += tot >> 16;
+  }
+}
+
+// Appends a layer's dense tiles to the work list of the multi-pass kernels.
+template <int NT>
+__device__ __forceinline__ void append_tiles(const LargeSeg& ls, uint32_t* __restrict__ counter,
+                                             int32_t* __restrict__ items, uint32_t* s_base) {
+  const int nt = ls.tile_end - ls.tile_begin;
+  __syncthreads();
+  if (threadIdx.x == 0) *s_base = atomicAdd(counter, (uint32_t)nt);
+  __syncthreads();
+  const uint32_t b = *s_base;
+  for (int j = threadIdx.x; j < nt; j += NT) items[b + j] = ls.tile_begin + j;
+}
+
+// A rejected guess: the layer is selected from the acc values in the residual buffer, by the
+// multi-pass kernels if they are enqueued in this call (chain), else by this workgroup.  The
+// context's pinned host word is set so that later calls enqueue them.
+template <int NT>
+__device__ __forceinline__ void reject_layer(int li, const LargeSeg& ls, const SegDesc& sd, int chain,
+                                             LState* __restrict__ lstate, uint32_t* __restrict__ fail_flag,
+                                             uint32_t* __restrict__ counter, int32_t* __restrict__ items,
+                                             float* __restrict__ res, int32_t* __restrict__ out_idx,
+                                             float* __restrict__ out_val, uint32_t* s_hist, uint32_t* s_wt,
+                                             uint32_t* s_sel) {
+  if (threadIdx.x == 0) {
+    lstate[li].mode = MODE_DENSE;
+    lstate[li].route = 2u;
+    __hip_atomic_store(fail_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+  }
+  if (chain) append_tiles<NT>(ls, counter, items, s_sel);
+  else rescue_layer<NT>(sd, res, out_idx, out_val, s_hist, s_wt, s_sel);
+}
+
+// One workgroup per large layer.  Layers that are not sampled hand their tiles to the
+// multi-pass kernels.  Sampled layers get their verdict and decisive bucket; those of at most
+// kFusedTiles tiles are finished here, the others by k_group_a and k_group_b.
+__global__ __launch_bounds__(1024) void k_finish(const SegDesc* __restrict__ segs,
+                                                 const LargeSeg* __restrict__ lsegs,
+                                                 LState* __restrict__ lstate,
+                                                 const uint32_t* __restrict__ chunk_cnt,
+                                                 const uint2* __restrict__ slots, int nslot,
+                                                 const uint32_t* __restrict__ bh,
+                                                 float* __restrict__ res, int32_t* __restrict__ out_idx,
+                                                 float* __restrict__ out_val, uint32_t* __restrict__ counter,
+                                                 int32_t* __restrict__ items, int chain,
+                                                 uint32_t* __restrict__ fail_flag) {
+  constexpr int NT = 1024, NW = 16;
+  constexpr int kMaxWc = kFusedTiles / kWaveTiles;
+  __shared__ uint2 s_band[kBandCap];
+  __shared__ uint32_t s_hist[kBins0];
+  __shared__ uint32_t s_wt[2 * NW];
+  __shared__ uint32_t s_sel[2];
+  __shared__ uint32_t s_ti[2];
+  __shared__ uint32_t s_nband;
+  __shared__ uint32_t s_wgt[kMaxWc];
+  const int li = blockIdx.x, tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
+  const LargeSeg ls = lsegs[li];
+  const SegDesc sd = segs[ls.seg];
+  if (!ls.sampled) {  // uniform over the workgroup
+    append_tiles<NT>(ls, counter, items, s_sel);
+    return;
+  }
+  const LState st = lstate[li];
+  // totals of the tiles: candidates, candidates at or above tau_top, overflowed tiles
+  uint32_t n = 0, ntop = 0;
+  int over = 0;
+  for (int c = ls.chunk_begin + tid; c < ls.chunk_end; c += NT) {
+    const uint32_t word = chunk_cnt[c];
+    over |= (word & 0xFFFFu) > (uint32_t)nslot;
+    n += word & 0xFFFFu;
+    ntop += word >> 16;
+  }
+  block_sum2<NT>(n, ntop, s_wt);
+  over = __syncthreads_or(over);
+  const uint32_t k = (uint32_t)sd.k;
+  const uint32_t* bhl = bh + (int64_t)li * kFineBins;
+  uint32_t bstar = 0, k_rem = 0, n_band = 0;
+  bool ok = !over && n >= k && ntop < k;  // uniform over the workgroup
+  if (ok) {
+    ok = find_rank<NT>(bhl, kFineBins, k - ntop, s_wt, s_sel, bstar, k_rem);
+    if (ok) {
+      n_band = bhl[bstar];
+      ok = n_band <= (uint32_t)kBandCap;
+    }
+  }
+  if (!ok) {
+    reject_layer<NT>(li, ls, sd, chain, lstate, fail_flag, counter, items, res, out_idx, out_val, s_hist, s_wt, s_sel);
+    return;
+  }
+  if (!ls.fused) {
+    if (tid == 0) {
+      lstate[li].mode = MODE_SPARSE;
+      lstate[li].bstar = bstar;
+      lstate[li].k_rem = k_rem;
+      lstate[li].n_band = n_band;
+    }
+    return;
+  }
+  // one workgroup finishes the layer: a wave takes every 16th wave chunk
+  const int nwc = (ls.chunk_end - ls.chunk_begin + kWaveTiles - 1) / kWaveTiles;  // <= kMaxWc
+  if (tid == 0) s_nband = 0u;
+  __syncthreads();
+  for (int q = w; q < nwc; q += NW) {
+    const WaveChunk wc = wc_open(ls.chunk_begin + q * kWaveTiles, ls.chunk_end, chunk_cnt, nslot, lane);
+    const uint32_t n_gt =
+        wc_phase_a(wc, slots, nslot, st.tau, st.tau_top, st.shift, bstar, s_band, kBandCap, &s_nband, lane);
+    if (lane == 0) s_wgt[q] = n_gt;
+  }
+  __syncthreads();
+  const uint32_t m = s_nband < (uint32_t)kBandCap ? s_nband : (uint32_t)kBandCap;  // equals n_band
+  if (tid == 0) { s_ti[0] = 0xFFFFFFFFu; s_ti[1] = 0u; }
+  __syncthreads();
+  band_select<NT>(s_band, m, k_rem, s_ti);
+  const uint32_t T = s_ti[0], I = s_ti[1];
+  int32_t* oi = out_idx + sd.out_offset;
+  float* ov = out_val + sd.out_offset;
+  float* rl = res + sd.offset;
+  for (int q = w; q < nwc; q += NW) {
+    uint32_t pos0 = band_kept_before(s_band, m, T, I, (uint32_t)q * (uint32_t)(kWaveTiles * kTile), lane);
+    for (int p = 0; p < q; ++p) pos0 += s_wgt[p];
+    const WaveChunk wc = wc_open(ls.chunk_begin + q * kWaveTiles, ls.chunk_end, chunk_cnt, nslot, lane);
+    wc_phase_b(wc, slots, nslot, T, I, pos0, k, sd.d, oi, ov, rl, lane);
+  }
+  if (tid == 0) {
+    lstate[li].mode = MODE_SPARSE;
+    lstate[li].route = 1u;
+  }
+}
+
+// Phase A of the layers finished by groups: one workgroup per group of 128 tiles, one wave per
+// wave chunk.  Writes the wave chunks' counts of candidates above b* and the group's band entries.
+__global__ __launch_bounds__(256) void k_group_a(const GroupDesc* __restrict__ groups,
+                                                 const LargeSeg* __restrict__ lsegs,
+                                                 LState* __restrict__ lstate,
+                                                 const uint32_t* __restrict__ chunk_cnt,
+                                                 const uint2* __restrict__ slots, int nslot,
+                                                 uint32_t* __restrict__ wgt, uint2* __restrict__ band,
+                                                 uint32_t* __restrict__ band_cnt) {
+  __shared__ uint32_t s_nband;
+  const GroupDesc gd = groups[blockIdx.x];
+  const LState st = lstate[gd.lseg];
+  if (st.mode != MODE_SPARSE) return;  // uniform over the workgroup
+  const LargeSeg ls = lsegs[gd.lseg];
+  const int tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
+  if (tid == 0) s_nband = 0u;
+  __syncthreads();
+  const int q = gd.first * kGroupWaves + w;  // wave chunk inside the layer
+  const int c0 = ls.chunk_begin + q * kWaveTiles;
+  if (c0 < ls.chunk_end) {  // wave-uniform
+    const WaveChunk wc = wc_open(c0, ls.chunk_end, chunk_cnt, nslot, lane);
+    const uint32_t n_gt = wc_phase_a(wc, slots, nslot, st.tau, st.tau_top, st.shift, st.bstar,
+                                     band + (int64_t)blockIdx.x * kGroupBand, kGroupBand, &s_nband, lane);
+    if (lane == 0) wgt[ls.wchunk_begin + q] = n_gt;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    const uint32_t nb = s_nband;
+    band_cnt[blockIdx.x] = nb < (uint32_t)kGroupBand ? nb : (uint32_t)kGroupBand;
+    if (nb > (uint32_t)kGroupBand) lstate[gd.lseg].band_over = 1u;  // every writer stores the same value
+  }
+}
+
+// Phase B of the layers finished by groups.  Workgroups [0, n_groups): one group each; it
+// gathers the layer's band from all groups, selects T and I, sums the counts of the earlier
+// wave chunks and emits.  Workgroups behind them: one per such layer, which records the route
+// and, if some group's band overflowed, selects the layer from the residual buffer instead.
+__global__ __launch_bounds__(256) void k_group_b(int n_groups, const GroupDesc* __restrict__ groups,
+                                                 const int32_t* __restrict__ multi,
+                                                 const SegDesc* __restrict__ segs,
+                                                 const LargeSeg* __restrict__ lsegs,
+                                                 LState* __restrict__ lstate,
+                                                 const uint32_t* __restrict__ chunk_cnt,
+                                                 const uint2* __restrict__ slots, int nslot,
+                                                 const uint32_t* __restrict__ wgt,
+                                                 const uint2* __restrict__ band,
+                                                 const uint32_t* __restrict__ band_cnt,
+                                                 float* __restrict__ res, int32_t* __restrict__ out_idx,
+                                                 float* __restrict__ out_val, uint32_t* __restrict__ counter,
+                                                 int32_t* __restrict__ items, int chain,
+                                                 uint32_t* __restrict__ fail_flag) {
+  constexpr int NT = 256;
+  __shared__ uint2 s_band[kBandCap];
+  __shared__ uint32_t s_hist[kBins0];
+  __shared__ uint32_t s_wt[8];
+  __shared__ uint32_t s_sel[2];
+  __shared__ uint32_t s_ti[2];
+  __shared__ uint32_t s_own[kGroupWaves];
+  const int tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
+  if ((int)blockIdx.x >= n_groups) {  // uniform over the workgroup
+    const int li = multi[blockIdx.x - n_groups];
+    const LState st = lstate[li];
+    if (st.mode != MODE_SPARSE) return;  // rejected by k_finish, dealt with there
+    if (!st.band_over) {
+      if (tid == 0) lstate[li].route = 1u;
+      return;
+    }
+    const LargeSeg ls = lsegs[li];
+    reject_layer<NT>(li, ls, segs[ls.seg], chain, lstate, fail_flag, counter, items, res, out_idx, out_val, s_hist,
+                     s_wt, s_sel);
+    return;
+  }
+  const GroupDesc gd = groups[blockIdx.x];
+  const LState st = lstate[gd.lseg];
+  if (st.mode != MODE_SPARSE || st.band_over) return;  // uniform over the workgroup
+  const LargeSeg ls = lsegs[gd.lseg];
+  const SegDesc sd = segs[ls.seg];
+  // the layer's band: the groups' entries one after the other (any order serves the selection)
+  uint32_t m = 0;
+  for (int g0 = ls.group_begin; g0 < ls.group_end; g0 += NT) {  // uniform trip count
+    const int g = g0 + tid;
+    const uint32_t cnt = g < ls.group_end ? band_cnt[g] : 0u;
+    uint32_t tot;
+    uint32_t at = m + block_incl_scan<NT>(cnt, s_wt, tot) - cnt;
+    for (uint32_t i = 0; i < cnt; ++i, ++at)
+      if (at < (uint32_t)kBandCap) s_band[at] = band[(int64_t)g * kGroupBand + i];
+    m += tot;
+  }
+  m = m < (uint32_t)kBandCap ? m : (uint32_t)kBandCap;  // equals n_band
+  if (tid == 0) { s_ti[0] = 0xFFFFFFFFu; s_ti[1] = 0u; }
+  __syncthreads();
+  band_select<NT>(s_band, m, st.k_rem, s_ti);
+  const uint32_t T = s_ti[0], I = s_ti[1];
+  // kept candidates above b* in the wave chunks before this group, then inside it
+  const int q0 = gd.first * kGroupWaves;
+  uint32_t before = 0, unused = 0;
+  for (int p = tid; p < q0; p += NT) before += wgt[ls.wchunk_begin + p];
+  block_sum2<NT>(before, unused, s_wt);
+  const int q = q0 + w;
+  const int c0 = ls.chunk_begin + q * kWaveTiles;
+  const bool active = c0 < ls.chunk_end;  // wave-uniform
+  if (lane == 0) s_own[w] = active ? wgt[ls.wchunk_begin + q] : 0u;
+  __syncthreads();
+  if (!active) return;
+  uint32_t pos0 = before + band_kept_before(s_band, m, T, I, (uint32_t)q * (uint32_t)(kWaveTiles * kTile), lane);
+  for (int p = 0; p < w; ++p) pos0 += s_own[p];
+  const WaveChunk wc = wc_open(c0, ls.chunk_end, chunk_cnt, nslot, lane);
+  wc_phase_b(wc, slots, nslot, T, I, pos0, (uint32_t)sd.k, sd.d, out_idx + sd.out_offset, out_val + sd.out_offset,
+             res + sd.offset, lane);
+}
+
+// ------------------------------------------------------------------ multi-pass select
+// Radix select over the acc values in the residual buffer, multi-block: layers that are not
+// sampled, and layers whose guess was rejected when these kernels are enqueued.  The tiles
+// come from the device-built work list `items`; kDenseGrid workgroups stride over it.
+struct TileWork {
+  float* res;          // the tile's residual data
+  int n;               // valid entries
+  int lseg;
+  int local0;          // layer-local index of the first element
+  int slot;            // index into tile_gt / tile_eq
+  bool skip_level0;    // level-0 histogram already made by the streaming pass
+};
+
+__device__ __forceinline__ void get_tile(int item, const TileDesc* __restrict__ tiles,
+                                         const int32_t* __restrict__ items, float* res, TileWork& tw) {
+  const int t = items[item];
+  const TileDesc td = tiles[t];
+  tw.lseg = td.seg;
+  tw.slot = t;
+  tw.local0 = td.local0;
+  tw.res = res + td.start;
+  tw.n = td.n;
+  tw.skip_level0 = td.ctile < 0;
+}
+
 __device__ __forceinline__ void load_tile(const TileWork& tw, int w, int lane, uint32_t (&a)[kTileV][4]) {
   const int n_w = tw.n - w * kWaveChunk;
-  if (CAND) {
-    load_cand_bits<kTileV>(tw.cand + w * kWaveChunk, n_w, lane, a);
-  } else {
-    const float* r = tw.res + w * kWaveChunk;
-    load_bits<kTileV>(r, n_w, aligned16(r, r), lane, a);
-  }
+  const float* r = tw.res + w * kWaveChunk;
+  load_bits<kTileV>(r, n_w, aligned16(r, r), lane, a);
 }
-
-// The three per-tile kernels below serve both sources in one launch: workgroups
-// [0, n_cblocks) take one candidate tile each (ctiles[blockIdx.x]); the kDenseGrid workgroups
-// after them walk the fallback work list (items[0 .. *counter)), which is empty unless a
-// layer's guess was rejected.
 
 // One digit of the radix select, decided from the layer's histogram of that digit (complete
 // since the previous launch): every workgroup that needs the result computes it for itself,
@@ -861,48 +1250,51 @@ __device__ __forceinline__ void load_tile(const TileWork& tw, int w, int lane, u
 __device__ __forceinline__ bool decide_digit(const uint32_t* __restrict__ gh, int nb, int shift, uint32_t p_before,
                                              uint32_t k_before, uint32_t* s_wt, uint32_t* s_sel,
                                              uint32_t& p_after, uint32_t& k_after) {
-  __syncthreads();
-  if (threadIdx.x == 0) { s_sel[0] = 0u; s_sel[1] = 0u; }
-  __syncthreads();
-  block_find_bucket<256>(gh, nb, k_before, s_wt, s_sel);
-  p_after = p_before | (s_sel[0] << shift);
-  k_after = s_sel[1];
-  return k_after != 0u;
+  uint32_t bin;
+  const bool found = find_rank<256>(gh, nb, k_before, s_wt, s_sel, bin, k_after);
+  p_after = p_before | (bin << shift);
+  return found;
 }
 
 // Histogram of one radix digit over the entries whose higher key bits equal the prefix
 // (levels 1 and 2 first decide the digit before theirs from its histogram).
-template <int LEVEL, bool CAND>
-__device__ __forceinline__ void hist_tiles(int first, int end, int step, uint32_t* s_hist, uint32_t* s_wt,
-                                           uint32_t* s_sel, const TileDesc* __restrict__ tiles,
-                                           const int32_t* __restrict__ items, int n_tiles,
-                                           const LargeSeg* __restrict__ lsegs, const SegDesc* __restrict__ segs,
-                                           float* __restrict__ res, const uint2* __restrict__ cand,
-                                           LState* __restrict__ lstate, uint32_t* __restrict__ ghist) {
+template <int LEVEL>
+__global__ __launch_bounds__(256) void k_hist(const TileDesc* __restrict__ tiles,
+                                              const int32_t* __restrict__ items,
+                                              const uint32_t* __restrict__ counter,
+                                              const LargeSeg* __restrict__ lsegs,
+                                              const SegDesc* __restrict__ segs,
+                                              float* __restrict__ res,
+                                              DState* __restrict__ dstate,
+                                              uint32_t* __restrict__ ghist) {
+  __shared__ uint32_t s_hist[LEVEL == 0 ? kBins0 : kBins12];
+  __shared__ uint32_t s_wt[4];
+  __shared__ uint32_t s_sel[2];
   constexpr int shift = LEVEL == 0 ? 20 : (LEVEL == 1 ? 10 : 0);
   constexpr uint32_t mask = LEVEL == 0 ? 0u : (LEVEL == 1 ? 0x7FF00000u : 0x7FFFFC00u);
   constexpr int nb = LEVEL == 0 ? kBins0 : kBins12;
   const int tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
-  for (int item = first; item < end; item += step) {
+  const int end = (int)*counter;
+  for (int item = blockIdx.x; item < end; item += kDenseGrid) {
     TileWork tw;
-    if (!get_tile<CAND>(item, tiles, items, res, cand, lstate, n_tiles, tw)) continue;
+    get_tile(item, tiles, items, res, tw);
     if (LEVEL == 0 && tw.skip_level0) continue;
     uint32_t* gh = ghist + (int64_t)tw.lseg * kHistStride;
     uint32_t prefix = 0u;
     if (LEVEL == 1) {
       uint32_t kr;
       if (!decide_digit(gh, kBins0, 20, 0u, (uint32_t)segs[lsegs[tw.lseg].seg].k, s_wt, s_sel, prefix, kr)) continue;
-      if (tw.local0 == 0 && tid == 0) { lstate[tw.lseg].p0 = prefix; lstate[tw.lseg].k0 = kr; }
+      if (tw.local0 == 0 && tid == 0) { dstate[tw.lseg].p0 = prefix; dstate[tw.lseg].k0 = kr; }
     } else if (LEVEL == 2) {
       uint32_t kr;
-      const uint32_t p0 = lstate[tw.lseg].p0, k0 = lstate[tw.lseg].k0;
+      const uint32_t p0 = dstate[tw.lseg].p0, k0 = dstate[tw.lseg].k0;
       if (!decide_digit(gh + kHistLevel1, kBins12, 10, p0, k0, s_wt, s_sel, prefix, kr)) continue;
-      if (tw.local0 == 0 && tid == 0) { lstate[tw.lseg].p1 = prefix; lstate[tw.lseg].k1 = kr; }
+      if (tw.local0 == 0 && tid == 0) { dstate[tw.lseg].p1 = prefix; dstate[tw.lseg].k1 = kr; }
     }
     __syncthreads();
     for (int i = tid; i < nb; i += 256) s_hist[i] = 0u;
     uint32_t a[kTileV][4];
-    load_tile<CAND>(tw, w, lane, a);
+    load_tile(tw, w, lane, a);
     const int n_w = tw.n - w * kWaveChunk;
     __syncthreads();
 #pragma unroll
@@ -925,56 +1317,32 @@ __device__ __forceinline__ void hist_tiles(int first, int end, int step, uint32_
   }
 }
 
-template <int LEVEL>
-__global__ __launch_bounds__(256) void k_hist(int n_cblocks, const TileDesc* __restrict__ ctiles,
-                                              const TileDesc* __restrict__ tiles,
-                                              const int32_t* __restrict__ items,
-                                              const uint32_t* __restrict__ counter, int n_tiles,
-                                              const LargeSeg* __restrict__ lsegs,
-                                              const SegDesc* __restrict__ segs,
-                                              float* __restrict__ res,
-                                              const uint2* __restrict__ cand,
-                                              LState* __restrict__ lstate,
-                                              uint32_t* __restrict__ ghist) {
-  __shared__ uint32_t s_hist[LEVEL == 0 ? kBins0 : kBins12];
-  __shared__ uint32_t s_wt[4];
-  __shared__ uint32_t s_sel[2];
-  const int b = (int)blockIdx.x;
-  if (b < n_cblocks)  // uniform over the workgroup
-    hist_tiles<LEVEL, true>(b, b + 1, 1, s_hist, s_wt, s_sel, ctiles, items, n_tiles, lsegs, segs, res, cand, lstate,
-                            ghist);
-  else
-    hist_tiles<LEVEL, false>(b - n_cblocks, (int)*counter, kDenseGrid, s_hist, s_wt, s_sel, tiles, items, n_tiles,
-                             lsegs, segs, res, cand, lstate, ghist);
-}
-
 // Decides the last digit (which fixes the k-th largest key T and the number of entries equal
 // to T to take), then counts per tile how many keys are above T and how many equal T.
-template <bool CAND>
-__device__ __forceinline__ void count_tiles(int first, int end, int step, uint32_t* s_g, uint32_t* s_e,
-                                            uint32_t* s_wt, uint32_t* s_sel,
-                                            const TileDesc* __restrict__ tiles,
-                                            const int32_t* __restrict__ items, int n_tiles,
-                                            float* __restrict__ res, const uint2* __restrict__ cand,
-                                            LState* __restrict__ lstate, const uint32_t* __restrict__ ghist,
-                                            uint32_t* __restrict__ tile_gt,
-                                            uint32_t* __restrict__ tile_eq) {
+__global__ __launch_bounds__(256) void k_count(const TileDesc* __restrict__ tiles,
+                                               const int32_t* __restrict__ items,
+                                               const uint32_t* __restrict__ counter,
+                                               float* __restrict__ res,
+                                               DState* __restrict__ dstate,
+                                               const uint32_t* __restrict__ ghist,
+                                               uint32_t* __restrict__ tile_gt,
+                                               uint32_t* __restrict__ tile_eq) {
+  __shared__ uint32_t s_g[4], s_e[4];
+  __shared__ uint32_t s_wt[4];
+  __shared__ uint32_t s_sel[2];
   const int tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
-  for (int item = first; item < end; item += step) {
+  const int end = (int)*counter;
+  for (int item = blockIdx.x; item < end; item += kDenseGrid) {
     TileWork tw;
-    if (!get_tile<CAND>(item, tiles, items, res, cand, lstate, n_tiles, tw)) {
-      // an empty candidate tile of a layer in candidate mode still takes part in the scan
-      if (CAND && tw.active && tid == 0) { tile_gt[tw.slot] = 0u; tile_eq[tw.slot] = 0u; }
-      continue;
-    }
+    get_tile(item, tiles, items, res, tw);
     uint32_t T, rtake;
-    const uint32_t p1 = lstate[tw.lseg].p1, k1 = lstate[tw.lseg].k1;
+    const uint32_t p1 = dstate[tw.lseg].p1, k1 = dstate[tw.lseg].k1;
     if (!decide_digit(ghist + (int64_t)tw.lseg * kHistStride + kHistLevel2, kBins12, 0, p1, k1, s_wt, s_sel, T,
                       rtake))
       continue;
-    if (tw.local0 == 0 && tid == 0) { lstate[tw.lseg].prefix = T; lstate[tw.lseg].k_rem = rtake; }
+    if (tw.local0 == 0 && tid == 0) { dstate[tw.lseg].prefix = T; dstate[tw.lseg].k_rem = rtake; }
     uint32_t a[kTileV][4];
-    load_tile<CAND>(tw, w, lane, a);
+    load_tile(tw, w, lane, a);
     uint32_t cg, ce;
     lane_count<kTileV>(a, tw.n - w * kWaveChunk, lane, T, cg, ce);
     cg = wave_sum(cg);
@@ -989,41 +1357,16 @@ __device__ __forceinline__ void count_tiles(int first, int end, int step, uint32
   }
 }
 
-__global__ __launch_bounds__(256) void k_count(int n_cblocks, const TileDesc* __restrict__ ctiles,
-                                               const TileDesc* __restrict__ tiles,
-                                               const int32_t* __restrict__ items,
-                                               const uint32_t* __restrict__ counter, int n_tiles,
-                                               float* __restrict__ res,
-                                               const uint2* __restrict__ cand,
-                                               LState* __restrict__ lstate,
-                                               const uint32_t* __restrict__ ghist,
-                                               uint32_t* __restrict__ tile_gt,
-                                               uint32_t* __restrict__ tile_eq) {
-  __shared__ uint32_t s_g[4], s_e[4];
-  __shared__ uint32_t s_wt[4];
-  __shared__ uint32_t s_sel[2];
-  const int b = (int)blockIdx.x;
-  if (b < n_cblocks)  // uniform over the workgroup
-    count_tiles<true>(b, b + 1, 1, s_g, s_e, s_wt, s_sel, ctiles, items, n_tiles, res, cand, lstate, ghist, tile_gt,
-                      tile_eq);
-  else
-    count_tiles<false>(b - n_cblocks, (int)*counter, kDenseGrid, s_g, s_e, s_wt, s_sel, tiles, items, n_tiles, res,
-                       cand, lstate, ghist, tile_gt, tile_eq);
-}
-
-// Exclusive scan of the per-tile counts inside each large layer (in place): over the
-// layer's dense tiles in MODE_DENSE, over its candidate tiles in MODE_SPARSE.
+// Exclusive scan of the per-tile counts inside each large layer that takes the multi-pass
+// route (in place).
 __global__ __launch_bounds__(1024) void k_scan(const LargeSeg* __restrict__ lsegs,
-                                               const LState* __restrict__ lstate, int n_tiles,
+                                               const LState* __restrict__ lstate,
                                                uint32_t* __restrict__ tile_gt,
                                                uint32_t* __restrict__ tile_eq) {
   __shared__ uint32_t s_wt[16];
   const LargeSeg ls = lsegs[blockIdx.x];
-  const uint32_t mode = lstate[blockIdx.x].mode;
-  int begin, end;
-  if (mode == MODE_DENSE) { begin = ls.tile_begin; end = ls.tile_end; }
-  else if (ls.cand_class == CAND_LARGE) { begin = n_tiles + ls.ctile_begin; end = n_tiles + ls.ctile_end; }
-  else return;
+  if (lstate[blockIdx.x].mode != MODE_DENSE) return;
+  const int begin = ls.tile_begin, end = ls.tile_end;
   uint32_t carry_g = 0, carry_e = 0;
   for (int base = begin; base < end; base += 1024) {
     const int i = base + threadIdx.x;
@@ -1042,28 +1385,30 @@ __global__ __launch_bounds__(1024) void k_scan(const LargeSeg* __restrict__ lseg
 }
 
 // Final pass: ordered emission of the kept pairs and zeroing of their residual slots.
-template <bool CAND>
-__device__ __forceinline__ void emit_tiles(int first, int end, int step, uint32_t* s_g, uint32_t* s_e,
-                                           const TileDesc* __restrict__ tiles,
-                                           const int32_t* __restrict__ items, int n_tiles,
-                                           const LargeSeg* __restrict__ lsegs,
-                                           const SegDesc* __restrict__ segs, float* __restrict__ res,
-                                           const uint2* __restrict__ cand,
-                                           const LState* __restrict__ lstate,
-                                           const uint32_t* __restrict__ tile_gt,
-                                           const uint32_t* __restrict__ tile_eq,
-                                           int32_t* __restrict__ out_idx, float* __restrict__ out_val) {
+__global__ __launch_bounds__(256) void k_emit(const TileDesc* __restrict__ tiles,
+                                              const int32_t* __restrict__ items,
+                                              const uint32_t* __restrict__ counter,
+                                              const LargeSeg* __restrict__ lsegs,
+                                              const SegDesc* __restrict__ segs,
+                                              float* __restrict__ res,
+                                              const DState* __restrict__ dstate,
+                                              const uint32_t* __restrict__ tile_gt,
+                                              const uint32_t* __restrict__ tile_eq,
+                                              int32_t* __restrict__ out_idx,
+                                              float* __restrict__ out_val) {
+  __shared__ uint32_t s_g[4], s_e[4];
   const int tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
-  for (int item = first; item < end; item += step) {
+  const int end = (int)*counter;
+  for (int item = blockIdx.x; item < end; item += kDenseGrid) {
     TileWork tw;
-    if (!get_tile<CAND>(item, tiles, items, res, cand, lstate, n_tiles, tw)) continue;
-    const LState st = lstate[tw.lseg];
+    get_tile(item, tiles, items, res, tw);
+    const DState st = dstate[tw.lseg];
     const uint32_t T = st.prefix, rtake = st.k_rem;
     const uint32_t tg = tile_gt[tw.slot], te = tile_eq[tw.slot];
     const SegDesc sd = segs[lsegs[tw.lseg].seg];
     const int n_w = tw.n - w * kWaveChunk;
     uint32_t a[kTileV][4];
-    load_tile<CAND>(tw, w, lane, a);
+    load_tile(tw, w, lane, a);
     uint32_t cg, ce;
     lane_count<kTileV>(a, n_w, lane, T, cg, ce);
     cg = wave_sum(cg);
@@ -1073,43 +1418,12 @@ __device__ __forceinline__ void emit_tiles(int first, int end, int step, uint32_
     __syncthreads();
     uint32_t gb = tg, eb = te;
     for (int i = 0; i < w; ++i) { gb += s_g[i]; eb += s_e[i]; }
-    if (CAND) {
-      // every wave runs: entries zeroed by the streaming pass but not kept must get acc back
-      wave_emit<kTileV, EMIT_CAND>(a, n_w, lane, T, rtake, gb, eb, (uint32_t)sd.k, 0, out_idx + sd.out_offset,
-                                   out_val + sd.out_offset, res + sd.offset, false, tw.cand + w * kWaveChunk,
-                                   st.tau_hi);
-    } else {
-      // nothing to emit in this wave if it holds no key above T and its ties come too late
-      if (cg == 0 && (ce == 0 || eb >= rtake)) continue;
-      float* r = tw.res + w * kWaveChunk;
-      wave_emit<kTileV, EMIT_ZERO>(a, n_w, lane, T, rtake, gb, eb, (uint32_t)sd.k, tw.local0 + w * kWaveChunk,
-                                   out_idx + sd.out_offset, out_val + sd.out_offset, r, aligned16(r, r), nullptr,
-                                   0u);
-    }
+    // nothing to emit in this wave if it holds no key above T and its ties come too late
+    if (cg == 0 && (ce == 0 || eb >= rtake)) continue;
+    float* r = tw.res + w * kWaveChunk;
+    wave_emit<kTileV, EMIT_ZERO>(a, n_w, lane, T, rtake, gb, eb, (uint32_t)sd.k, tw.local0 + w * kWaveChunk,
+                                 out_idx + sd.out_offset, out_val + sd.out_offset, r, aligned16(r, r));
   }
-}
-
-__global__ __launch_bounds__(256) void k_emit(int n_cblocks, const TileDesc* __restrict__ ctiles,
-                                              const TileDesc* __restrict__ tiles,
-                                              const int32_t* __restrict__ items,
-                                              const uint32_t* __restrict__ counter, int n_tiles,
-                                              const LargeSeg* __restrict__ lsegs,
-                                              const SegDesc* __restrict__ segs,
-                                              float* __restrict__ res,
-                                              const uint2* __restrict__ cand,
-                                              const LState* __restrict__ lstate,
-                                              const uint32_t* __restrict__ tile_gt,
-                                              const uint32_t* __restrict__ tile_eq,
-                                              int32_t* __restrict__ out_idx,
-                                              float* __restrict__ out_val) {
-  __shared__ uint32_t s_g[4], s_e[4];
-  const int b = (int)blockIdx.x;
-  if (b < n_cblocks)  // uniform over the workgroup
-    emit_tiles<true>(b, b + 1, 1, s_g, s_e, ctiles, items, n_tiles, lsegs, segs, res, cand, lstate,
-                     tile_gt, tile_eq, out_idx, out_val);
-  else
-    emit_tiles<false>(b - n_cblocks, (int)*counter, kDenseGrid, s_g, s_e, tiles, items, n_tiles, lsegs, segs, res,
-                      cand, lstate, tile_gt, tile_eq, out_idx, out_val);
 }
 
 // ------------------------------------------------------------------ merge ----
@@ -1415,19 +1729,23 @@ __global__ __launch_bounds__(256) void k_delta_finish(const SegDesc* __restrict_
 // ------------------------------------------------------------------ launch ---
 const char* kernel_name(int id) {
   static const char* names[K_NUM] = {
-      "k_zero_u32", "k_small<4,1>", "k_small<4,8>", "k_small<16,10>", "k_sample", "k_stream", "k_cscan",
-      "k_cgather", "k_small<4,1,cand>", "k_small<4,8,cand>", "k_small<16,10,cand>", "k_hist", "k_count",
-      "k_scan", "k_emit", "k_merge_bounds", "k_merge", "k_merge<apply>", "k_delta_tiles", "k_delta_finish",
-      "sparsify_call"};
+      "k_prep", "k_small<4,1>", "k_small<4,8>", "k_small<16,10>", "k_stream", "k_finish", "k_group_a", "k_group_b",
+      "k_hist", "k_count", "k_scan", "k_emit", "k_merge_bounds", "k_merge", "k_merge<apply>", "k_delta_tiles",
+      "k_delta_finish", "sparsify_call"};
   return (id >= 0 && id < K_NUM) ? names[id] : nullptr;
 }
 
-hipError_t launch_zero_u32(uint32_t* p, int64_t n, hipStream_t s, Prof* prof) {
+__global__ void k_fill_u32(uint32_t* __restrict__ p, int64_t n, uint32_t value) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t step = (int64_t)gridDim.x * blockDim.x;
+  for (; i < n; i += step) p[i] = value;
+}
+
+hipError_t launch_fill_u32(uint32_t* p, int64_t n, uint32_t value, hipStream_t s) {
   if (n <= 0) return hipSuccess;
   int64_t blocks = (n + 255) / 256;
   if (blocks > 4096) blocks = 4096;
-  ProfScope ps(prof, K_ZERO, s);
-  hipLaunchKernelGGL(k_zero_u32, dim3((unsigned)blocks), dim3(256), 0, s, p, n);
+  hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)blocks), dim3(256), 0, s, p, n, value);
   return hipGetLastError();
 }
 
@@ -1435,36 +1753,31 @@ hipError_t launch_small(int cls, int nseg, const SegDesc* segs, const int32_t* l
                         float* res, float lr, int32_t* out_idx, float* out_val, hipStream_t s, Prof* prof) {
   if (nseg <= 0) return hipSuccess;
   ProfScope ps(prof, K_SMALL0 + cls, s);
-  const LargeSeg* nl = nullptr;
-  const LState* ns = nullptr;
-  const uint2* nc = nullptr;
   if (cls == 0)
-    hipLaunchKernelGGL((k_small<4, 1, false>), dim3(nseg), dim3(256), 0, s, segs, list, nl, ns, nc, grad, res, lr,
-                       out_idx, out_val);
+    hipLaunchKernelGGL((k_small<4, 1>), dim3(nseg), dim3(256), 0, s, segs, list, grad, res, lr, out_idx, out_val);
   else if (cls == 1)
-    hipLaunchKernelGGL((k_small<4, 8, false>), dim3(nseg), dim3(256), 0, s, segs, list, nl, ns, nc, grad, res, lr,
-                       out_idx, out_val);
+    hipLaunchKernelGGL((k_small<4, 8>), dim3(nseg), dim3(256), 0, s, segs, list, grad, res, lr, out_idx, out_val);
   else
-    hipLaunchKernelGGL((k_small<16, 10, false>), dim3(nseg), dim3(1024), 0, s, segs, list, nl, ns, nc, grad, res,
-                       lr, out_idx, out_val);
+    hipLaunchKernelGGL((k_small<16, 10>), dim3(nseg), dim3(1024), 0, s, segs, list, grad, res, lr, out_idx,
+                       out_val);
   return hipGetLastError();
 }
 
 hipError_t launch_large(const LargePlan& pl, const Scratch& sc, const SegDesc* segs, const float* grad,
-                        float* res, float lr, int32_t* out_idx, float* out_val, hipStream_t s, Prof* prof) {
+                        float* res, float lr, int32_t* out_idx, float* out_val, bool chain, hipStream_t s,
+                        Prof* prof) {
   if (pl.n_large <= 0) return hipSuccess;
-  // the layers' histograms and, behind them, the counters: one clearing launch per call
+  if (pl.has_dense) chain = true;
   uint32_t* counters = sc.ghist + (int64_t)pl.n_large * kHistStride;
-  hipError_t e = launch_zero_u32(sc.ghist, (int64_t)pl.n_large * kHistStride + 16, s, prof);
-  if (e != hipSuccess) return e;
-  if (pl.n_sampled > 0) {
-    ProfScope ps(prof, K_SAMPLE, s);
+  const int ch = chain ? 1 : 0;
+  {
+    ProfScope ps(prof, K_PREP, s);
     if (pl.big_sample)
-      hipLaunchKernelGGL((k_sample<true>), dim3(pl.n_sampled), dim3(1024), 0, s, segs, pl.sampled, pl.lsegs, grad,
-                         res, lr, sc.lstate);
+      hipLaunchKernelGGL((k_prep<true>), dim3(pl.n_large), dim3(1024), 0, s, segs, pl.lsegs, grad, res, lr, sc.lstate,
+                         sc.bh, sc.ghist, counters, ch);
     else
-      hipLaunchKernelGGL((k_sample<false>), dim3(pl.n_sampled), dim3(1024), 0, s, segs, pl.sampled, pl.lsegs, grad,
-                         res, lr, sc.lstate);
+      hipLaunchKernelGGL((k_prep<false>), dim3(pl.n_large), dim3(1024), 0, s, segs, pl.lsegs, grad, res, lr,
+                         sc.lstate, sc.bh, sc.ghist, counters, ch);
   }
   {
     const int nl = (pl.n_tiles + kStreamLaunchTiles - 1) / kStreamLaunchTiles;
@@ -1472,65 +1785,54 @@ hipError_t launch_large(const LargePlan& pl, const Scratch& sc, const SegDesc* s
     for (int t0 = 0; t0 < pl.n_tiles; t0 += kStreamLaunchTiles) {
       const int nt = pl.n_tiles - t0 < kStreamLaunchTiles ? pl.n_tiles - t0 : kStreamLaunchTiles;
       hipLaunchKernelGGL((k_stream<kStreamWaves, kStreamV>), dim3(nt), dim3(kStreamWaves * 64), kStreamLdsPad, s,
-                         pl.tiles + t0, grad, res, lr, sc.lstate, sc.chunk_cnt, sc.slots, pl.slot, sc.ghist);
+                         pl.tiles + t0, grad, res, lr, sc.lstate, sc.chunk_cnt, sc.slots, pl.slot, sc.bh, sc.ghist);
     }
   }
   {
-    ProfScope ps(prof, K_CSCAN, s);
-    hipLaunchKernelGGL(k_cscan, dim3(pl.n_large), dim3(1024), 0, s, segs, pl.lsegs, sc.lstate, sc.chunk_cnt,
-                       pl.slot, sc.chunk_off, counters, sc.items);
+    ProfScope ps(prof, K_FINISH, s);
+    hipLaunchKernelGGL(k_finish, dim3(pl.n_large), dim3(1024), 0, s, segs, pl.lsegs, sc.lstate, sc.chunk_cnt,
+                       sc.slots, pl.slot, sc.bh, res, out_idx, out_val, counters, sc.items, ch, sc.fail_flag);
   }
-  if (pl.n_chunks > 0) {
-    ProfScope ps(prof, K_CGATHER, s);
-    hipLaunchKernelGGL(k_cgather, dim3((pl.n_chunks + 255) / 256), dim3(256), 0, s, pl.n_chunks, pl.chunk_lseg,
-                       pl.lsegs, sc.lstate, sc.chunk_cnt, sc.chunk_off, sc.slots, pl.slot, sc.cand, segs, res);
+  if (pl.n_groups > 0) {
+    {
+      ProfScope ps(prof, K_GROUP_A, s);
+      hipLaunchKernelGGL(k_group_a, dim3(pl.n_groups), dim3(256), 0, s, pl.groups, pl.lsegs, sc.lstate, sc.chunk_cnt,
+                         sc.slots, pl.slot, sc.wgt, sc.band, sc.band_cnt);
+    }
+    ProfScope ps(prof, K_GROUP_B, s);
+    hipLaunchKernelGGL(k_group_b, dim3(pl.n_groups + pl.n_multi), dim3(256), 0, s, pl.n_groups, pl.groups, pl.multi,
+                       segs, pl.lsegs, sc.lstate, sc.chunk_cnt, sc.slots, pl.slot, sc.wgt, sc.band, sc.band_cnt, res,
+                       out_idx, out_val, counters, sc.items, ch, sc.fail_flag);
   }
-  const float* ng = nullptr;
-  if (pl.n_cand_small[0] > 0) {
-    ProfScope ps(prof, K_CSMALL0, s);
-    hipLaunchKernelGGL((k_small<4, 1, true>), dim3(pl.n_cand_small[0]), dim3(256), 0, s, segs, pl.cand_small[0],
-                       pl.lsegs, sc.lstate, sc.cand, ng, res, lr, out_idx, out_val);
-  }
-  if (pl.n_cand_small[1] > 0) {
-    ProfScope ps(prof, K_CSMALL1, s);
-    hipLaunchKernelGGL((k_small<4, 8, true>), dim3(pl.n_cand_small[1]), dim3(256), 0, s, segs, pl.cand_small[1],
-                       pl.lsegs, sc.lstate, sc.cand, ng, res, lr, out_idx, out_val);
-  }
-  if (pl.n_cand_small[2] > 0) {
-    ProfScope ps(prof, K_CSMALL2, s);
-    hipLaunchKernelGGL((k_small<16, 10, true>), dim3(pl.n_cand_small[2]), dim3(1024), 0, s, segs,
-                       pl.cand_small[2], pl.lsegs, sc.lstate, sc.cand, ng, res, lr, out_idx, out_val);
-  }
-  // candidate tiles first, then the workgroups of the fallback work list
-  const int nct = pl.n_ctiles;
-  const dim3 grid(nct + kDenseGrid), b(256);
-  // the digit chosen from each level's histogram is computed by the workgroups of the next launch
-  for (int level = 0; level < 3; ++level) {
-    ProfScope ps(prof, K_HIST, s);
-    if (level == 0)
-      hipLaunchKernelGGL((k_hist<0>), grid, b, 0, s, nct, pl.ctiles, pl.tiles, sc.items, counters, pl.n_tiles,
-                         pl.lsegs, segs, res, sc.cand, sc.lstate, sc.ghist);
-    else if (level == 1)
-      hipLaunchKernelGGL((k_hist<1>), grid, b, 0, s, nct, pl.ctiles, pl.tiles, sc.items, counters, pl.n_tiles,
-                         pl.lsegs, segs, res, sc.cand, sc.lstate, sc.ghist);
-    else
-      hipLaunchKernelGGL((k_hist<2>), grid, b, 0, s, nct, pl.ctiles, pl.tiles, sc.items, counters, pl.n_tiles,
-                         pl.lsegs, segs, res, sc.cand, sc.lstate, sc.ghist);
-  }
-  {
-    ProfScope ps(prof, K_COUNT, s);
-    hipLaunchKernelGGL(k_count, grid, b, 0, s, nct, pl.ctiles, pl.tiles, sc.items, counters, pl.n_tiles, res,
-                       sc.cand, sc.lstate, sc.ghist, sc.tile_gt, sc.tile_eq);
-  }
-  {
-    ProfScope ps(prof, K_SCAN, s);
-    hipLaunchKernelGGL(k_scan, dim3(pl.n_large), dim3(1024), 0, s, pl.lsegs, sc.lstate, pl.n_tiles, sc.tile_gt,
-                       sc.tile_eq);
-  }
-  {
-    ProfScope ps(prof, K_EMIT, s);
-    hipLaunchKernelGGL(k_emit, grid, b, 0, s, nct, pl.ctiles, pl.tiles, sc.items, counters, pl.n_tiles, pl.lsegs,
-                       segs, res, sc.cand, sc.lstate, sc.tile_gt, sc.tile_eq, out_idx, out_val);
+  if (chain) {
+    const dim3 grid(kDenseGrid), b(256);
+    // the digit chosen from each level's histogram is computed by the workgroups of the next launch
+    for (int level = 0; level < 3; ++level) {
+      ProfScope ps(prof, K_HIST, s);
+      if (level == 0)
+        hipLaunchKernelGGL((k_hist<0>), grid, b, 0, s, pl.tiles, sc.items, counters, pl.lsegs, segs, res, sc.dstate,
+                           sc.ghist);
+      else if (level == 1)
+        hipLaunchKernelGGL((k_hist<1>), grid, b, 0, s, pl.tiles, sc.items, counters, pl.lsegs, segs, res, sc.dstate,
+                           sc.ghist);
+      else
+        hipLaunchKernelGGL((k_hist<2>), grid, b, 0, s, pl.tiles, sc.items, counters, pl.lsegs, segs, res, sc.dstate,
+                           sc.ghist);
+    }
+    {
+      ProfScope ps(prof, K_COUNT, s);
+      hipLaunchKernelGGL(k_count, grid, b, 0, s, pl.tiles, sc.items, counters, res, sc.dstate, sc.ghist, sc.tile_gt,
+                         sc.tile_eq);
+    }
+    {
+      ProfScope ps(prof, K_SCAN, s);
+      hipLaunchKernelGGL(k_scan, dim3(pl.n_large), dim3(1024), 0, s, pl.lsegs, sc.lstate, sc.tile_gt, sc.tile_eq);
+    }
+    {
+      ProfScope ps(prof, K_EMIT, s);
+      hipLaunchKernelGGL(k_emit, grid, b, 0, s, pl.tiles, sc.items, counters, pl.lsegs, segs, res, sc.dstate,
+                         sc.tile_gt, sc.tile_eq, out_idx, out_val);
+    }
   }
   return hipGetLastError();
 }

@@ -58,6 +58,11 @@ def lib():
         L.lags_delta_monitor.argtypes = [vp, vp, vp, i64, vp, vp, i32, i64, vp, vp]
         L.lags_last_routes.restype = ctypes.c_int
         L.lags_last_routes.argtypes = [vp, vp, ctypes.POINTER(i32), i32]
+        L.lags_debug_fallback_chain.restype, L.lags_debug_fallback_chain.argtypes = ctypes.c_int, [vp, ctypes.c_int]
+        L.lags_debug_scratch_info.restype = ctypes.c_int
+        L.lags_debug_scratch_info.argtypes = [vp, ctypes.c_int, ctypes.POINTER(vp), ctypes.POINTER(i64),
+                                              ctypes.POINTER(i64)]
+        L.lags_debug_poison_scratch.restype, L.lags_debug_poison_scratch.argtypes = ctypes.c_int, [vp, vp]
         L.lags_profile_enable.restype, L.lags_profile_enable.argtypes = ctypes.c_int, [vp, ctypes.c_int]
         L.lags_profile_enable_kernel.restype = ctypes.c_int
         L.lags_profile_enable_kernel.argtypes = [vp, ctypes.c_int]
@@ -200,6 +205,19 @@ class Context:
         arr = (ctypes.c_int32 * table.n)()
         _check(lib().lags_last_routes(self.handle, table.handle, arr, table.n), "lags_last_routes")
         return list(arr)
+
+    def lags_debug_fallback_chain(self, mode):
+        _check(lib().lags_debug_fallback_chain(self.handle, int(mode)), "lags_debug_fallback_chain")
+
+    def lags_debug_scratch_info(self, which):
+        """(address, bytes, number of retired buffers) of scratch buffer `which`."""
+        p, b, r = ctypes.c_void_p(0), ctypes.c_int64(0), ctypes.c_int64(0)
+        _check(lib().lags_debug_scratch_info(self.handle, int(which), ctypes.byref(p), ctypes.byref(b),
+                                             ctypes.byref(r)), "lags_debug_scratch_info")
+        return (p.value or 0), b.value, r.value
+
+    def lags_debug_poison_scratch(self, stream=None):
+        _check(lib().lags_debug_poison_scratch(self.handle, _stream(stream)), "lags_debug_poison_scratch")
 
     def lags_profile_enable(self, on):
         _check(lib().lags_profile_enable(self.handle, int(bool(on))), "lags_profile_enable")
