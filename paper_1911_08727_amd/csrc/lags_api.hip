@@ -54,7 +54,7 @@ struct DevBuf {
 struct lags_ctx {
   int device = 0;
   // scratch of the large layers' path, sized for the largest table created so far
-  DevBuf bh, lstate, chunk_cnt, slots, wgt, band, band_cnt, ghist, dstate, tile_gt, tile_eq, items;
+  DevBuf bh_part, top_part, lstate, chunk_cnt, slots, wgt, band, band_cnt, ghist, dstate, tile_gt, tile_eq, items;
   DevBuf bounds;   // merge: P rows of tile start positions, sized at the first merge call that needs it
   DevBuf partials; // delta metric: two doubles per merge tile
   // Once a call of this context has been recorded by stream capture, scratch that has to grow is
@@ -77,7 +77,8 @@ struct lags_ctx {
   std::vector<void*>* retire_list() { return captured ? &retired : nullptr; }
   Scratch scratch() const {
     Scratch sc;
-    sc.bh = static_cast<uint32_t*>(bh.p);
+    sc.bh_part = static_cast<uint32_t*>(bh_part.p);
+    sc.top_part = static_cast<uint32_t*>(top_part.p);
     sc.lstate = static_cast<LState*>(lstate.p);
     sc.chunk_cnt = static_cast<uint32_t*>(chunk_cnt.p);
     sc.slots = static_cast<uint2*>(slots.p);
@@ -109,6 +110,7 @@ struct lags_table {
   LargeSeg* d_lsegs = nullptr;
   TileDesc* d_tiles = nullptr;
   GroupDesc* d_groups = nullptr;
+  GroupDesc* d_hparts = nullptr;
   int32_t* d_multi = nullptr;
   TileDesc* d_mtiles = nullptr;
   BChunk* d_bchunks = nullptr;
@@ -150,7 +152,7 @@ bool ranges_overlap(const void* a, int64_t abytes, const void* b, int64_t bbytes
 }
 
 std::vector<DevBuf*> all_bufs(lags_ctx* ctx) {
-  return {&ctx->bh, &ctx->lstate, &ctx->chunk_cnt, &ctx->slots, &ctx->wgt, &ctx->band, &ctx->band_cnt, &ctx->ghist,
+  return {&ctx->bh_part, &ctx->top_part, &ctx->lstate, &ctx->chunk_cnt, &ctx->slots, &ctx->wgt, &ctx->band, &ctx->band_cnt, &ctx->ghist,
           &ctx->dstate, &ctx->tile_gt, &ctx->tile_eq, &ctx->items, &ctx->bounds, &ctx->partials};
 }
 
@@ -161,6 +163,7 @@ void free_table_device(lags_table* t) {
   if (t->d_lsegs) (void)hipFree(t->d_lsegs);
   if (t->d_tiles) (void)hipFree(t->d_tiles);
   if (t->d_groups) (void)hipFree(t->d_groups);
+  if (t->d_hparts) (void)hipFree(t->d_hparts);
   if (t->d_multi) (void)hipFree(t->d_multi);
   if (t->d_mtiles) (void)hipFree(t->d_mtiles);
   if (t->d_bchunks) (void)hipFree(t->d_bchunks);
@@ -172,19 +175,13 @@ void free_table_device(lags_table* t) {
 // largest key.  Returns false if the layer is not worth sampling (k too large for the slots).
 bool plan_sample(int64_t d, int64_t k, LargeSeg* ls, double* per_tile) {
   int64_t pieces, stride;
-  int64_t piece_len = kSamplePiece;
-  ls->sample_big = 0;
-  if (d >= kBigSampleD && k >= kBigSampleK) {
-    pieces = kSamplePieces;
-    stride = d / kSamplePieces;
-    piece_len = kSamplePieceBig;
-    ls->sample_big = 1;
-  } else if (d >= kSampleMax) {
+  const int64_t piece_len = kSamplePiece * kSampleBatches;
+  if (d >= kSamplePieces * piece_len) {
     pieces = kSamplePieces;
     stride = d / kSamplePieces;
   } else {
-    pieces = (d + kSamplePiece - 1) / kSamplePiece;
-    stride = kSamplePiece;
+    pieces = (d + piece_len - 1) / piece_len;
+    stride = piece_len;
   }
   const double m = (double)std::min<int64_t>(d, pieces * piece_len);
   const double fk = (double)k * m / (double)d;
@@ -196,6 +193,11 @@ bool plan_sample(int64_t d, int64_t k, LargeSeg* ls, double* per_tile) {
   // expected candidates per tile must stay well inside the largest slot size
   *per_tile = jd / m * (double)kTile;
   if (*per_tile > (double)kSlotMax * 0.5) return false;
+  // The candidates between the threshold and the expected k-th largest key, (jd - fk) / fk * k of
+  // them, spread over at least 512 buckets; the bucket of the k-th largest key must hold no more
+  // than kBandCap entries.  Layers that keep so many entries that this leaves less than a factor
+  // 4 take the multi-pass route.
+  if ((jd - fk) / fk * (double)k / 512.0 > (double)kBandCap / 4.0) return false;
   ls->sample_rank = (int32_t)jd;
   // the sample's best estimate of the k-th largest key: it sets the width of the candidate buckets
   ls->sample_rank_hi = (int32_t)std::max(1.0, std::floor(fk));
@@ -214,7 +216,7 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
   t->n = n;
   std::vector<int32_t> small[3], multi;
   std::vector<TileDesc> tiles, mtiles;
-  std::vector<GroupDesc> groups;
+  std::vector<GroupDesc> groups, hparts;
   std::vector<BChunk> bchunks;
   std::vector<int32_t> seg_mtile0;
   int64_t n_chunks = 0;        // tiles of sampled layers: each owns `slot` candidate slots
@@ -249,7 +251,6 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
         if ((int64_t)tiles.size() + nt > kMaxTiles) { delete t; return LAGS_ECAPACITY; }
         if (ls.sampled) {
           max_per_tile = std::max(max_per_tile, per_tile);
-          if (ls.sample_big) t->plan.big_sample = true;
           ls.chunk_begin = (int32_t)n_chunks;
           ls.chunk_end = (int32_t)(n_chunks + nt);
           ls.wchunk_begin = (int32_t)n_wchunks;
@@ -266,6 +267,14 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
               groups.push_back(gd);
             }
             ls.group_end = (int32_t)groups.size();
+            ls.group_h_begin = (int32_t)hparts.size();
+            for (int64_t h = 0; h * kCountTiles < nt; ++h) {
+              GroupDesc hp;
+              hp.lseg = li;
+              hp.first = (int32_t)h;
+              hparts.push_back(hp);
+            }
+            ls.group_h_end = (int32_t)hparts.size();
             multi.push_back(li);
           }
         } else {
@@ -323,6 +332,7 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
   pl.n_wchunks = (int)n_wchunks;
   pl.n_groups = (int)groups.size();
   pl.n_multi = (int)multi.size();
+  pl.n_hparts = (int)hparts.size();
   for (const LargeSeg& ls : t->lsegs) pl.n_sampled += ls.sampled;
   // candidates cluster (e.g. the few non-zero rows of an embedding gradient), so a tile may
   // hold several times the layer's average: the slots leave a factor 8 where they can
@@ -334,6 +344,7 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
   if (rc == LAGS_OK) rc = upload(&t->d_lsegs, t->lsegs);
   if (rc == LAGS_OK) rc = upload(&t->d_tiles, tiles);
   if (rc == LAGS_OK) rc = upload(&t->d_groups, groups);
+  if (rc == LAGS_OK) rc = upload(&t->d_hparts, hparts);
   if (rc == LAGS_OK) rc = upload(&t->d_multi, multi);
   if (rc == LAGS_OK) rc = upload(&t->d_mtiles, mtiles);
   if (rc == LAGS_OK) rc = upload(&t->d_bchunks, bchunks);
@@ -344,11 +355,13 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
   pl.lsegs = t->d_lsegs;
   pl.tiles = t->d_tiles;
   pl.groups = t->d_groups;
+  pl.hparts = t->d_hparts;
   pl.multi = t->d_multi;
   if (pl.n_large > 0) {
     std::vector<void*>* rl = ctx->retire_list();
     const size_t nl = (size_t)pl.n_large;
-    if (rc == LAGS_OK) rc = ctx->bh.grow(nl * kFineBins * sizeof(uint32_t), rl);
+    if (rc == LAGS_OK) rc = ctx->bh_part.grow((size_t)pl.n_hparts * kFineBins * sizeof(uint32_t), rl);
+    if (rc == LAGS_OK) rc = ctx->top_part.grow((size_t)pl.n_hparts * sizeof(uint32_t), rl);
     if (rc == LAGS_OK) rc = ctx->lstate.grow(nl * sizeof(LState), rl);
     if (rc == LAGS_OK) rc = ctx->chunk_cnt.grow((size_t)pl.n_chunks * sizeof(uint32_t), rl);
     if (rc == LAGS_OK) rc = ctx->slots.grow((size_t)pl.n_chunks * (size_t)pl.slot * sizeof(uint2), rl);

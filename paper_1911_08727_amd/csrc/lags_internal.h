@@ -33,27 +33,23 @@ constexpr int kSmall2 = 16 * 10 * 256;   // <= 40960 : 16 waves, 10 rounds
 constexpr int kSamplePiece = 64;
 constexpr int kSamplePieces = 256;
 constexpr int kSampleMax = kSamplePiece * kSamplePieces;   // 16384 sampled elements
-// Layers that keep many entries (k >= kBigSampleK) of many elements take four times the sample:
-// the threshold is then tighter (about 1.7 k candidates instead of 2.7 k at rho = 0.001).
-constexpr int kSamplePieceBig = 256;                       // 256 pieces x 256 = 65536 sampled elements
-constexpr int kBigSampleK = 8192;
-constexpr int64_t kBigSampleD = 1 << 20;
+constexpr int kSampleBatches = 1;        // 16 sample keys per thread (2 or 4: pieces of 128 or 256 elements)
 constexpr int kSlotMin = 128;            // candidate slots per tile of a sampled layer: the table uses the
 constexpr int kSlotMax = 2048;           // smallest power of two >= 8x the expected count of any layer
 constexpr int kDenseGrid = 1024;         // workgroups of the multi-pass kernels (grid-stride)
-// Finish of a sampled layer.  The streaming pass counts its candidates in kFineBins buckets of
-// 2^shift key steps above the threshold tau (one global atomic each; same-address atomics cost
-// about 0.1-0.2 us on this chip, so the buckets are many and cover only the part of the key range
-// where the k-th largest key is expected: candidates above it are counted per tile instead).
-// The bucket that holds the k-th largest key is then resolved exactly among its own entries
-// ("band"), which must number at most kBandCap.
+// Finish of a sampled layer.  The candidates are counted in kFineBins buckets of 2^shift key
+// steps above the threshold tau; the buckets cover the part of the key range where the k-th
+// largest key is expected, candidates above it are counted in one number.  The bucket that
+// holds the k-th largest key is then resolved exactly among its own entries ("band"), which
+// must number at most kBandCap.
 constexpr int kFineBins = 4096;
-constexpr int kBandCap = 2048;
-constexpr int kWaveTiles = 32;           // a wave flattens the slots of 32 consecutive tiles ("wave chunk")
-constexpr int kGroupWaves = 4;           // a workgroup of the multi-workgroup finish: 4 wave chunks
+constexpr int kBandCap = 4096;
+constexpr int kWaveTiles = 8;            // a wave flattens the slots of 8 consecutive tiles ("wave chunk")
+constexpr int kGroupWaves = 8;           // a workgroup of the multi-workgroup finish: 8 wave chunks
 constexpr int kGroupTiles = kWaveTiles * kGroupWaves;
 constexpr int kGroupBand = 64;           // band entries one group may contribute
-constexpr int kFusedTiles = 1024;        // sampled layers of up to this many tiles are finished by one workgroup
+constexpr int kCountTiles = 512;         // tiles per workgroup of the partial bucket counts
+constexpr int kFusedTiles = 512;         // sampled layers of up to this many tiles are finished by one workgroup
 // The streaming pass is HBM-bound and runs best when each CU holds only three of its
 // workgroups (12 waves, about 96 KB of loads in flight per CU): measured on MI355X, 26.6 GB in
 // 4.05 ms, against 4.36 ms at the eight workgroups that registers and static LDS would allow
@@ -108,23 +104,24 @@ struct LargeSeg {       // static plan of one large layer
   int32_t wchunk_begin; // sampled layers: first of the layer's wave chunks in the per-wave-chunk array
   int32_t group_begin;  // multi-workgroup finish: the layer's groups [group_begin, group_end)
   int32_t group_end;
+  int32_t group_h_begin;  // ... and its parts of the bucket counts [group_h_begin, group_h_end)
+  int32_t group_h_end;
   int32_t sample_rank;  // rank (1-based, from the top) of the sample key used as threshold tau
   int32_t sample_rank_hi;  // rank of the sample key that estimates the layer's k-th largest key
   int32_t sample_pieces;
   int32_t sample_stride;
-  int32_t sample_big;   // 1: pieces of kSamplePieceBig elements (the large sample), 0: of kSamplePiece
 };
 
-struct GroupDesc {      // one workgroup of the multi-workgroup finish
+struct GroupDesc {      // one workgroup of the multi-workgroup finish (a group, or a part of the bucket counts)
   int32_t lseg;         // large-layer index
-  int32_t first;        // index of the group inside its layer
+  int32_t first;        // index of the group (part) inside its layer
 };
 
 enum : uint32_t { MODE_DENSE = 0, MODE_SPARSE = 1 };
 
 struct LState {         // per call, per large layer
   uint32_t tau;         // candidates are the entries with key >= tau
-  uint32_t tau_top;     // candidates with key >= tau_top are counted per tile, the others per bucket
+  uint32_t tau_top;     // candidates with key >= tau_top are counted in one number, the others per bucket
   uint32_t shift;       // bucket of a candidate below tau_top: (key - tau) >> shift
   uint32_t mode;        // MODE_SPARSE: the guess held, the slots contain the top k
   uint32_t bstar;       // the bucket that holds the k-th largest key
@@ -144,20 +141,21 @@ struct DState {         // per call, per large layer on the multi-pass route: th
 };
 
 struct LargePlan {      // everything launch_large needs (device pointers + counts)
-  int n_large = 0, n_tiles = 0, n_sampled = 0, n_chunks = 0, n_wchunks = 0, n_groups = 0, n_multi = 0;
+  int n_large = 0, n_tiles = 0, n_sampled = 0, n_chunks = 0, n_wchunks = 0, n_groups = 0, n_multi = 0, n_hparts = 0;
   int slot = kSlotMin;                  // candidate slots per sampled tile
-  bool big_sample = false;              // some layer uses the large sample
   bool has_dense = false;               // some large layer is not sampled: the multi-pass kernels always run
   const LargeSeg* lsegs = nullptr;
   const TileDesc* tiles = nullptr;      // dense tiles
   const GroupDesc* groups = nullptr;    // groups of the layers with fused == 0
+  const GroupDesc* hparts = nullptr;    // parts of their bucket counts
   const int32_t* multi = nullptr;       // large-layer indices of those layers
 };
 
 struct Scratch {        // context-owned device memory, contents meaningless between calls
-  uint32_t* bh = nullptr;         // n_large * kFineBins: candidate buckets; zeroed each call
+  uint32_t* bh_part = nullptr;    // n_hparts * kFineBins: partial bucket counts
+  uint32_t* top_part = nullptr;   // n_hparts: candidates at or above tau_top
   LState* lstate = nullptr;       // n_large
-  uint32_t* chunk_cnt = nullptr;  // n_chunks: candidates of the tile | those at or above tau_top << 16
+  uint32_t* chunk_cnt = nullptr;  // n_chunks: candidates of the tile
   uint2* slots = nullptr;         // n_chunks * slot
   uint32_t* wgt = nullptr;        // n_wchunks: entries above the decisive bucket per wave chunk
   uint2* band = nullptr;          // n_groups * kGroupBand
@@ -173,7 +171,7 @@ struct Scratch {        // context-owned device memory, contents meaningless bet
 
 // Kernel ids for the optional event timing.
 enum KernelId {
-  K_PREP = 0, K_SMALL0, K_SMALL1, K_SMALL2, K_STREAM, K_FINISH, K_GROUP_A, K_GROUP_B,
+  K_PREP = 0, K_SMALL0, K_SMALL1, K_SMALL2, K_STREAM, K_GROUP_H, K_FINISH, K_GROUP_A, K_GROUP_B,
   K_HIST, K_COUNT, K_SCAN, K_EMIT,
   K_MERGE_BOUNDS, K_MERGE, K_MERGE_APPLY, K_DELTA_TILES, K_DELTA_FINISH,
   K_SPARSIFY_CALL,      // not a kernel: the whole sparsify call on the caller's stream, fork to join

@@ -405,33 +405,17 @@ __device__ __forceinline__ void block_sum2(uint32_t& a, uint32_t& b, uint32_t* s
   b = tb;
 }
 
-// Threshold guess for one large layer: form acc on up to 256 pieces of 64 (V = 4) or 256
-// (V = 16) consecutive elements spread over the layer (with a hashed offset inside each
-// stride); tau is a key that at least `sample_rank` sample keys reach (and few more), t_est one
-// that at least `sample_rank_hi` reach: the sample's estimate of the layer's k-th largest key.
-// Any value would be correct (the guess is verified by counting); a good one keeps the
-// candidates few.  Missing sample slots count as key 0.
-//
-// The two keys come from two histograms over 1024 linear bins, which spread the top of the
-// sample evenly (bins of exponent bits would put it all into a handful of LDS words):
-// first the per-thread maxima over the 2^26 key steps below the largest sample key M, which
-// gives a floor F that at least `sample_rank` thread maxima reach; then the sample entries at
-// or above F over [F, M].  The lower edge of the bin that holds a rank is returned, so the
-// threshold may admit the few sample entries that share that bin.  Ranks above 1024 (very
-// dense layers) and samples whose top spans more than 2^26 key steps take an exact radix
-// select instead.
-// Keys of one batch of the sample: 4 wave rounds (16 keys per thread).  BATCHES = 1: a round of a
-// wave covers 4 pieces of 64 elements (16 lanes each); BATCHES = 4 (the large sample): the same
-// number of pieces, each 256 elements long (one wave round), so that it touches no more pages
-// than the small one.
+// Keys of one batch of the sample: 4 wave rounds (16 keys per thread) of the 256 pieces of
+// 64 * BATCHES consecutive elements each (a wave round covers 64 / (16 * BATCHES) pieces).
 template <int BATCHES>
 __device__ __forceinline__ void sample_batch(int batch, const LargeSeg& ls, int li, const SegDesc& sd,
                                              const float* __restrict__ g, const float* __restrict__ r, bool vec,
                                              float lr, int lane, int w, uint32_t (&a)[4][4]) {
   constexpr int V = 4 * BATCHES;
-  constexpr int PL = BATCHES == 1 ? kSamplePiece : kSamplePieceBig;  // piece length
-  constexpr int LP = PL / 4;                                         // lanes per piece
-  constexpr int PR = 64 / LP;                                        // pieces per wave round
+  constexpr int PL = kSamplePiece * BATCHES;   // piece length
+  constexpr int LP = PL / 4;                   // lanes per piece
+  constexpr int PR = 64 / LP;                  // pieces per wave round
+  static_assert(BATCHES == 1 || BATCHES == 2 || BATCHES == 4, "a piece is a whole number of lanes of one wave round");
 #pragma unroll
   for (int jj = 0; jj < 4; ++jj) {
     const int j = batch * 4 + jj;
@@ -461,9 +445,9 @@ __device__ __forceinline__ void sample_batch(int batch, const LargeSeg& ls, int 
   }
 }
 
-// Threshold guess for one large layer: form acc on up to 256 pieces of 64 (BATCHES = 1) or 256
-// (BATCHES = 4) consecutive elements spread over the layer (with a hashed offset inside each
-// stride); tau is a key that at least `sample_rank` sample keys reach (and few more), t_est one
+// Threshold guess for one large layer: form acc on up to 256 pieces of 64 * BATCHES
+// consecutive elements spread over the layer (with a hashed offset inside each stride);
+// tau is a key that at least `sample_rank` sample keys reach (and few more), t_est one
 // that at least `sample_rank_hi` reach: the sample's estimate of the layer's k-th largest key.
 // Any value would be correct (the guess is verified by counting); a good one keeps the
 // candidates few.  Missing sample slots count as key 0.
@@ -472,9 +456,8 @@ __device__ __forceinline__ void sample_batch(int batch, const LargeSeg& ls, int 
 // sample evenly (bins of exponent bits would put it all into a handful of LDS words):
 // first the per-thread maxima over the 2^26 key steps below the largest sample key M, which
 // gives a floor F that at least `sample_rank` thread maxima reach; then the sample entries at
-// or above F over [F, M] (the sample is read a second time: it is in cache, and the large
-// sample would not fit the registers).  The lower edge of the bin that holds a rank is
-// returned, so the threshold may admit the few sample entries that share that bin.  Ranks
+// or above F over [F, M].  The lower edge of the bin that holds a rank is returned; where that
+// bin holds clearly more entries than the rank needs, the rank is resolved inside it.  Ranks
 // above 1024 (very dense layers) and samples whose top spans more than 2^26 key steps take an
 // exact radix select over the first batch instead, with the ranks scaled to it.
 template <int BATCHES>
@@ -482,7 +465,7 @@ __device__ __forceinline__ void sample_layer(const LargeSeg& ls, int li, const S
                                              const float* __restrict__ grad, const float* __restrict__ res,
                                              float lr, uint32_t* s_hist, uint32_t* s_wt, uint32_t* s_sel,
                                              uint32_t& tau, uint32_t& t_est) {
-  constexpr int NT = 1024;  // 16 waves; a wave takes 4 pieces per round
+  constexpr int NT = 1024;  // 16 waves
   const int tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
   const float* g = grad + sd.offset;
   const float* r = res + sd.offset;
@@ -553,6 +536,7 @@ __device__ __forceinline__ void sample_layer(const LargeSeg& ls, int li, const S
       extra = s_hist[bin] - rib;
     }
   } else {
+    if (BATCHES > 1) sample_batch<BATCHES>(0, ls, li, sd, g, r, vec, lr, lane, w, a);
     uint32_t rtake;
     const uint32_t r1 = rank / BATCHES > 0 ? rank / BATCHES : 1u, r2 = rank_hi / BATCHES > 0 ? rank_hi / BATCHES : 1u;
     block_radix_select<NT, 4>(a, 4 * 256, lane, r1, s_hist, s_wt, s_sel, tau, rtake);
@@ -561,26 +545,22 @@ __device__ __forceinline__ void sample_layer(const LargeSeg& ls, int li, const S
   if (t_est < tau) t_est = tau;
 }
 
-// One workgroup per large layer: clears the layer's per-call scratch (candidate buckets, flags,
-// and, when the multi-pass kernels will run, their histograms and work counter) and guesses
-// the threshold of a sampled layer.  BIG: the table holds layers with the large sample; those
-// workgroups take the four-batch path.
-template <bool BIG>
+// One workgroup per large layer: resets the layer's per-call state (and, when the multi-pass
+// kernels will run, their histograms and work counter) and guesses the threshold of a sampled
+// layer.
 __global__ __launch_bounds__(1024) void k_prep(const SegDesc* __restrict__ segs,
                                                const LargeSeg* __restrict__ lsegs,
                                                const float* __restrict__ grad,
                                                const float* __restrict__ res, float lr,
-                                               LState* __restrict__ lstate, uint32_t* __restrict__ bh,
-                                               uint32_t* __restrict__ ghist, uint32_t* __restrict__ counters,
-                                               int chain) {
+                                               LState* __restrict__ lstate, uint32_t* __restrict__ ghist,
+                                               uint32_t* __restrict__ counters, int chain) {
   __shared__ uint32_t s_hist[kBins0];
   __shared__ uint32_t s_wt[16];
   __shared__ uint32_t s_sel[2];
   const int li = blockIdx.x, tid = threadIdx.x;
   const LargeSeg ls = lsegs[li];
-  static_assert(kFineBins == 4096 && kHistStride == 4096, "one 16-byte store per thread clears either");
-  reinterpret_cast<uint4*>(bh + (int64_t)li * kFineBins)[tid] = make_uint4(0u, 0u, 0u, 0u);
   if (chain) {
+    static_assert(kHistStride == 4096, "one 16-byte store per thread clears a layer's histograms");
     reinterpret_cast<uint4*>(ghist + (int64_t)li * kHistStride)[tid] = make_uint4(0u, 0u, 0u, 0u);
     if (li == 0 && tid < 16) counters[tid] = 0u;
   }
@@ -595,10 +575,7 @@ __global__ __launch_bounds__(1024) void k_prep(const SegDesc* __restrict__ segs,
   }
   const SegDesc sd = segs[ls.seg];
   uint32_t tau, t_est;
-  if (BIG && ls.sample_big)  // uniform over the workgroup
-    sample_layer<4>(ls, li, sd, grad, res, lr, s_hist, s_wt, s_sel, tau, t_est);
-  else
-    sample_layer<1>(ls, li, sd, grad, res, lr, s_hist, s_wt, s_sel, tau, t_est);
+  sample_layer<kSampleBatches>(ls, li, sd, grad, res, lr, s_hist, s_wt, s_sel, tau, t_est);
   if (tid == 0) {
     // bucket width: the distance from tau to the estimate of the k-th largest key spans 512 to
     // 1023 buckets, so the 4096 buckets reach four to eight times that distance above tau
@@ -630,48 +607,37 @@ __device__ __forceinline__ void store_bits_nt(float* __restrict__ r, int lane, c
 // Candidate collection of one tile inside the streaming pass (all waves of the workgroup call
 // it; contains one barrier).  Every entry with key >= tau goes, in index order, into the
 // tile's slots (entries beyond nslot are dropped; the count written to *cnt then exceeds nslot
-// and marks the tile as overflowed).  A candidate below tau_top adds one to its bucket of the
-// layer's histogram; those at or above tau_top are counted in the upper half of *cnt.
-// FULL: the wave's chunk is complete, no bounds checks.
+// and marks the tile as overflowed).  FULL: the wave's chunk is complete, no bounds checks.
 template <int NW, int V, bool FULL>
 __device__ __forceinline__ void stream_collect(const uint32_t (&a)[V][4], int n_w, int lane, int w, uint32_t tau,
-                                               uint32_t tau_top, uint32_t shift, int32_t idx0,
-                                               uint2* __restrict__ slot, int nslot, uint32_t* __restrict__ cnt,
-                                               uint32_t* __restrict__ bh, uint32_t* s_cnt) {
+                                               int32_t idx0, uint2* __restrict__ slot, int nslot,
+                                               uint32_t* __restrict__ cnt, uint32_t* s_cnt) {
   // one ballot per element slot of the wave; bitwise & keeps the code free of branches
   uint64_t m[V][4];
-  uint32_t wtop = 0;
 #pragma unroll
   for (int j = 0; j < V; ++j) {
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
-      const uint32_t key = a[j][c] & 0x7FFFFFFFu;
-      const bool valid = FULL ? true : (j * 256 + lane * 4 + c < n_w);
-      m[j][c] = __builtin_amdgcn_ballot_w64((key >= tau) & valid);
-      wtop += (uint32_t)__popcll(__builtin_amdgcn_ballot_w64((key >= tau_top) & valid));
+      const bool ge = (a[j][c] & 0x7FFFFFFFu) >= tau;
+      if (FULL) m[j][c] = __builtin_amdgcn_ballot_w64(ge);
+      else m[j][c] = __builtin_amdgcn_ballot_w64(ge & (j * 256 + lane * 4 + c < n_w));
     }
   }
   uint32_t wtot = 0;
 #pragma unroll
   for (int j = 0; j < V; ++j)
     wtot += (uint32_t)(__popcll(m[j][0]) + __popcll(m[j][1]) + __popcll(m[j][2]) + __popcll(m[j][3]));
-  if (lane == 0) s_cnt[w] = wtot | (wtop << 16);  // each at most 1024 per wave, 4096 per tile
+  if (lane == 0) s_cnt[w] = wtot;
   __syncthreads();
   uint32_t base = 0, total = 0;
 #pragma unroll
   for (int i = 0; i < NW; ++i) {
     const uint32_t t = s_cnt[i];
-    if (i < w) base += t & 0xFFFFu;
+    if (i < w) base += t;
     total += t;
   }
   if (threadIdx.x == 0) *cnt = total;
   if (wtot == 0) return;  // wave-uniform
-  // A tile that overflows its slots rejects the layer's guess: its bucket counts are not needed
-  // (and a tile full of equal keys would send thousands of atomics to one address).
-  const bool counted = (total & 0xFFFFu) <= (uint32_t)nslot;  // uniform over the workgroup
-  // The first bucket the wave meets is counted in a scalar and added once at the end, so that
-  // many candidates with one key (quantised values) cost one atomic per wave.
-  uint32_t hot = 0xFFFFFFFFu, hot_n = 0;
 #pragma unroll
   for (int j = 0; j < V; ++j) {
     const uint32_t tot =
@@ -686,29 +652,21 @@ __device__ __forceinline__ void stream_collect(const uint32_t (&a)[V][4], int n_
         const bool f = FULL ? key >= tau : ((key >= tau) & (e + c < n_w));
         if (f & (pos < (uint32_t)nslot)) slot[pos] = make_uint2((uint32_t)(idx0 + e + c), a[j][c]);
         pos += f ? 1u : 0u;
-        if (counted && m[j][c]) {  // wave-uniform
-          const uint32_t b = (f & (key < tau_top)) ? (key - tau) >> shift : 0xFFFFFFFFu;
-          const uint64_t act = __ballot(b != 0xFFFFFFFFu);
-          if (act) {  // wave-uniform
-            if (hot == 0xFFFFFFFFu) hot = (uint32_t)__builtin_amdgcn_readlane((int)b, __builtin_ctzll(act));
-            hot_n += (uint32_t)__popcll(__ballot(b == hot));
-            if (b != hot && b != 0xFFFFFFFFu) atomicAdd(&bh[b], 1u);
-          }
-        }
       }
       base += tot;
     }
   }
-  if (lane == 0 && hot_n) atomicAdd(&bh[hot], hot_n);
 }
 
 // The one pass over grad and residual of every large layer: acc = residual + lr*grad is
 // written into the residual buffer (it is the final residual everywhere but at the k kept
 // entries).  Tiles of sampled layers also collect, in index order, the entries with
-// key >= tau into the tile's slots and count them by bucket; tiles of the other layers add to
-// the layer's histogram of key bits 30..20.  Both arrays are touched exactly once, so full
-// aligned tiles use non-temporal 16-byte loads and stores.  The launch adds kStreamLdsPad bytes
-// of unused dynamic LDS per workgroup to cap the workgroups per CU.
+// key >= tau into the tile's slots; tiles of the other layers add to the layer's histogram of
+// key bits 30..20.  Both arrays are touched exactly once, so full aligned tiles use
+// non-temporal 16-byte loads and stores.  The launch adds kStreamLdsPad bytes of unused
+// dynamic LDS per workgroup to cap the workgroups per CU.  The pass issues no global atomics
+// for sampled layers (same-address atomics cost 0.06-0.2 us each on this chip: one per tile
+// on a per-layer counter measured 7x the whole pass).
 template <int NW, int V>
 __global__ __launch_bounds__(NW * 64) void k_stream(const TileDesc* __restrict__ tiles,
                                                 const float* __restrict__ grad,
@@ -716,7 +674,6 @@ __global__ __launch_bounds__(NW * 64) void k_stream(const TileDesc* __restrict__
                                                 const LState* __restrict__ lstate,
                                                 uint32_t* __restrict__ chunk_cnt,
                                                 uint2* __restrict__ slots, int nslot,
-                                                uint32_t* __restrict__ bh,
                                                 uint32_t* __restrict__ ghist) {
   __shared__ uint32_t s_hist[kBins0];
   __shared__ uint32_t s_cnt[NW];
@@ -725,11 +682,9 @@ __global__ __launch_bounds__(NW * 64) void k_stream(const TileDesc* __restrict__
   const TileDesc td = tiles[blockIdx.x];
   const int tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
   const bool collect = td.ctile >= 0;  // uniform over the workgroup
-  uint32_t tau = 0, tau_top = 0, shift = 0;
+  uint32_t tau = 0;
   if (collect) {
     tau = lstate[td.seg].tau;
-    tau_top = lstate[td.seg].tau_top;
-    shift = lstate[td.seg].shift;
   } else {
     for (int i = tid; i < kBins0; i += NT) s_hist[i] = 0u;
   }
@@ -760,10 +715,9 @@ __global__ __launch_bounds__(NW * 64) void k_stream(const TileDesc* __restrict__
   if (collect) {
     uint2* slot = slots + (int64_t)td.ctile * nslot;
     uint32_t* cnt = chunk_cnt + td.ctile;
-    uint32_t* bhl = bh + (int64_t)td.seg * kFineBins;
     const int32_t idx0 = td.local0 + w * WC;
-    if (fast) stream_collect<NW, V, true>(a, n_w, lane, w, tau, tau_top, shift, idx0, slot, nslot, cnt, bhl, s_cnt);
-    else stream_collect<NW, V, false>(a, n_w, lane, w, tau, tau_top, shift, idx0, slot, nslot, cnt, bhl, s_cnt);
+    if (fast) stream_collect<NW, V, true>(a, n_w, lane, w, tau, idx0, slot, nslot, cnt, s_cnt);
+    else stream_collect<NW, V, false>(a, n_w, lane, w, tau, idx0, slot, nslot, cnt, s_cnt);
     if (fast) store_bits_nt<V>(r, lane, a);
     else store_bits<V>(r, n_w, vec, lane, a);
   } else {
@@ -789,24 +743,28 @@ __global__ __launch_bounds__(NW * 64) void k_stream(const TileDesc* __restrict__
 
 // ------------------------------------------------------------------ finish ---
 // After the streaming pass a sampled layer's candidates sit in its tiles' slots (index order
-// inside a tile, tiles in index order) and are counted per bucket.  The finish
+// inside a tile, tiles in index order).  The finish
+//   counts    the candidates in kFineBins buckets of 2^shift key steps above tau (those at or
+//             above tau_top, the end of the buckets, in one number);
 //   decides   whether the guess held (at least k candidates, no tile overflowed) and which
 //             bucket b* holds the k-th largest key, so that every candidate above b* is kept
 //             and k_rem of the entries in b* (the "band", at most kBandCap) are;
-//   phase A   counts per wave chunk (32 tiles) the candidates above b* and collects the band;
+//   phase A   counts per wave chunk (8 tiles) the candidates above b* and collects the band;
 //   selects   among the band the entry of rank k_rem in the order (key descending, index
 //             ascending): its key T and index I fix the kept set, key > T or key == T and index <= I;
 //   phase B   writes the kept pairs in index order (position = kept entries of the earlier wave
 //             chunks + kept band entries with a smaller index + rank inside the wave chunk) and
 //             zeroes their residual.
-// Small layers do all of it in one workgroup (k_finish); large ones decide in k_finish and run
-// the phases as one launch each over groups of 128 tiles, every workgroup of phase B selecting
-// T and I for itself from the band.  No workgroup ever waits for another one.
+// Layers of up to kFusedTiles tiles do all of it in one workgroup (k_finish).  Larger ones take
+// one launch per step: k_group_h (partial bucket counts per 512 tiles), k_finish (decides),
+// k_group_a and k_group_b over groups of 64 tiles, every workgroup of phase B selecting T and
+// I for itself from the band.  No workgroup ever waits for another one, and nothing is added
+// with global atomics.
 
-// A wave's view of the slots of up to 32 consecutive tiles as one flat, index-ordered list.
+// A wave's view of the slots of up to kWaveTiles consecutive tiles as one flat, index-ordered list.
 struct WaveChunk {
   int c0;           // first tile (chunk number)
-  uint32_t pre;     // lane l < 32: entries of the tiles before tile c0 + l
+  uint32_t pre;     // lane l < kWaveTiles: entries of the tiles before tile c0 + l
   uint32_t total;   // entries of all its tiles
 };
 
@@ -814,8 +772,8 @@ __device__ __forceinline__ WaveChunk wc_open(int c0, int c_end, const uint32_t* 
                                              int lane) {
   uint32_t cnt = 0;
   if (lane < kWaveTiles && c0 + lane < c_end) {
-    cnt = chunk_cnt[c0 + lane] & 0xFFFFu;
-    cnt = cnt < (uint32_t)nslot ? cnt : (uint32_t)nslot;  // an overflowed tile never gets here; stay in bounds anyway
+    cnt = chunk_cnt[c0 + lane];
+    cnt = cnt < (uint32_t)nslot ? cnt : (uint32_t)nslot;  // an overflowed tile rejects the layer; stay in bounds anyway
   }
   const uint32_t incl = wave_incl_scan(cnt, lane);
   WaveChunk wc;
@@ -828,9 +786,10 @@ __device__ __forceinline__ WaveChunk wc_open(int c0, int c_end, const uint32_t* 
 // Entry e < total of the flat list (all 64 lanes call it; e may differ per lane).
 __device__ __forceinline__ uint2 wc_entry(const WaveChunk& wc, uint32_t e, const uint2* __restrict__ slots,
                                           int nslot) {
+  static_assert(kWaveTiles == 8, "three search steps");
   int lo = 0, hi = kWaveTiles - 1;  // last tile whose exclusive count is <= e
 #pragma unroll
-  for (int step = 0; step < 5; ++step) {
+  for (int step = 0; step < 3; ++step) {
     const int mid = (lo + hi + 1) >> 1;
     const uint32_t v = __shfl(wc.pre, mid, 64);
     if (v <= e) lo = mid; else hi = mid - 1;
@@ -839,15 +798,48 @@ __device__ __forceinline__ uint2 wc_entry(const WaveChunk& wc, uint32_t e, const
   return slots[(int64_t)(wc.c0 + lo) * nslot + (e - p0)];
 }
 
+// Calls f(entry, live) for the wave chunk's entries, 64 at a time in index order, all lanes
+// taking part (live = the lane holds an entry).  Two loads are issued before the first is used.
+template <typename F>
+__device__ __forceinline__ void wc_for_each(const WaveChunk& wc, const uint2* __restrict__ slots, int nslot,
+                                            int lane, F f) {
+  for (uint32_t base = 0; base < wc.total; base += 128) {  // wave-uniform trip count
+    const bool two = base + 64 < wc.total;                 // wave-uniform
+    const bool live0 = base + lane < wc.total, live1 = base + 64 + lane < wc.total;
+    const uint2 e0 = wc_entry(wc, live0 ? base + lane : wc.total - 1, slots, nslot);
+    uint2 e1 = make_uint2(0u, 0u);
+    if (two) e1 = wc_entry(wc, live1 ? base + 64 + lane : wc.total - 1, slots, nslot);
+    f(e0, live0);
+    if (two) f(e1, live1);
+  }
+}
+
+// Bucket counts of one wave chunk into the LDS histogram s_fine; returns the number of
+// candidates at or above tau_top (wave-uniform).
+__device__ __forceinline__ uint32_t wc_count(const WaveChunk& wc, const uint2* __restrict__ slots, int nslot,
+                                             uint32_t tau, uint32_t tau_top, uint32_t shift, uint32_t* s_fine,
+                                             int lane) {
+  uint32_t n_top = 0;
+  wc_for_each(wc, slots, nslot, lane, [&](uint2 en, bool live) {
+    const uint32_t key = en.y & 0x7FFFFFFFu;
+    const bool top = key >= tau_top;
+    n_top += (uint32_t)__popcll(__ballot(live && top));
+    if (live && !top) {
+      // slots hold keys in [tau, tau_top) here; the clamps only keep a corrupted entry inside the array
+      const uint32_t b = key >= tau ? (key - tau) >> shift : 0u;
+      atomicAdd(&s_fine[b < (uint32_t)kFineBins ? b : (uint32_t)kFineBins - 1u], 1u);
+    }
+  });
+  return n_top;
+}
+
 // Phase A over one wave chunk: returns the number of candidates above bucket b* (wave-uniform)
 // and appends the entries of bucket b* to band[0 .. cap) through the LDS counter *s_nband.
 __device__ __forceinline__ uint32_t wc_phase_a(const WaveChunk& wc, const uint2* __restrict__ slots, int nslot,
                                                uint32_t tau, uint32_t tau_top, uint32_t shift, uint32_t bstar,
                                                uint2* band, uint32_t cap, uint32_t* s_nband, int lane) {
   uint32_t n_gt = 0;
-  for (uint32_t base = 0; base < wc.total; base += 64) {  // wave-uniform trip count
-    const bool live = base + lane < wc.total;
-    const uint2 en = wc_entry(wc, live ? base + lane : wc.total - 1, slots, nslot);
+  wc_for_each(wc, slots, nslot, lane, [&](uint2 en, bool live) {
     const uint32_t key = en.y & 0x7FFFFFFFu;
     const bool top = key >= tau_top;
     const uint32_t b = (key - tau) >> shift;
@@ -856,25 +848,43 @@ __device__ __forceinline__ uint32_t wc_phase_a(const WaveChunk& wc, const uint2*
       const uint32_t pos = atomicAdd(s_nband, 1u);
       if (pos < cap) band[pos] = en;
     }
-  }
+  });
   return n_gt;
 }
 
-// The band entry of rank k_rem (1-based) in the order (key descending, index ascending), by
-// counting for every entry how many precede it.  s_ti[0] = its key T, s_ti[1] = its index I.
-// The band has m <= kBandCap entries in LDS; 1 <= k_rem <= m.  Ends with a barrier.
+// The band entry of rank k_rem (1-based) in the order (key descending, index ascending):
+// s_ti[0] = its key T, s_ti[1] = its index I.  The band has m <= kBandCap entries in LDS, all
+// with keys in [lo, lo + 2^shift); 1 <= k_rem <= m.  A histogram over 1024 sub-buckets names
+// the sub-bucket of that entry; inside it every entry counts how many precede it (cheap unless
+// thousands of entries share one key).  s_bins: 1024 words.  Ends with a barrier.
 template <int NT>
-__device__ __forceinline__ void band_select(const uint2* s_band, uint32_t m, uint32_t k_rem, uint32_t* s_ti) {
+__device__ __forceinline__ void band_select(const uint2* s_band, uint32_t m, uint32_t k_rem, uint32_t lo,
+                                            uint32_t shift, uint32_t* s_bins, uint32_t* s_wt, uint32_t* s_sel,
+                                            uint32_t* s_ti) {
+  const uint32_t s1 = shift > 10u ? shift - 10u : 0u;
+  __syncthreads();
+  for (int i = threadIdx.x; i < 1024; i += NT) s_bins[i] = 0u;
+  __syncthreads();
   for (uint32_t i = threadIdx.x; i < m; i += NT) {
-    const uint2 en = s_band[i];
-    const uint32_t key = en.y & 0x7FFFFFFFu;
-    uint32_t before = 0;
-    for (uint32_t q = 0; q < m; ++q) {
-      const uint2 o = s_band[q];
-      const uint32_t ok = o.y & 0x7FFFFFFFu;
-      before += (ok > key) || (ok == key && o.x < en.x);
+    const uint32_t sub = ((s_band[i].y & 0x7FFFFFFFu) - lo) >> s1;
+    atomicAdd(&s_bins[sub < 1023u ? sub : 1023u], 1u);
+  }
+  uint32_t b1, r1;
+  if (find_rank<NT>(s_bins, 1024, k_rem, s_wt, s_sel, b1, r1)) {  // uniform over the workgroup
+    for (uint32_t i = threadIdx.x; i < m; i += NT) {
+      const uint2 en = s_band[i];
+      const uint32_t key = en.y & 0x7FFFFFFFu;
+      const uint32_t sub = (key - lo) >> s1;
+      if ((sub < 1023u ? sub : 1023u) != b1) continue;
+      uint32_t before = 0;
+      for (uint32_t q = 0; q < m; ++q) {
+        const uint2 o = s_band[q];
+        const uint32_t ok = o.y & 0x7FFFFFFFu;
+        const uint32_t osub = (ok - lo) >> s1;
+        before += ((osub < 1023u ? osub : 1023u) == b1) && ((ok > key) || (ok == key && o.x < en.x));
+      }
+      if (before + 1u == r1) { s_ti[0] = key; s_ti[1] = en.x; }
     }
-    if (before + 1u == k_rem) { s_ti[0] = key; s_ti[1] = en.x; }
   }
   __syncthreads();
 }
@@ -897,9 +907,7 @@ __device__ __forceinline__ void wc_phase_b(const WaveChunk& wc, const uint2* __r
                                            uint32_t T, uint32_t I, uint32_t pos0, uint32_t k, int32_t d,
                                            int32_t* __restrict__ oi, float* __restrict__ ov, float* __restrict__ rl,
                                            int lane) {
-  for (uint32_t base = 0; base < wc.total; base += 64) {  // wave-uniform trip count
-    const bool live = base + lane < wc.total;
-    const uint2 en = wc_entry(wc, live ? base + lane : wc.total - 1, slots, nslot);
+  wc_for_each(wc, slots, nslot, lane, [&](uint2 en, bool live) {
     const uint32_t key = en.y & 0x7FFFFFFFu;
     const bool keep = live && (key > T || (key == T && en.x <= I));
     const uint64_t mk = __ballot(keep);
@@ -910,7 +918,7 @@ __device__ __forceinline__ void wc_phase_b(const WaveChunk& wc, const uint2* __r
       rl[en.x] = 0.0f;
     }
     pos0 += (uint32_t)__popcll(mk);
-  }
+  });
 }
 
 // Exact selection of one layer by one workgroup from the acc values in the residual buffer:
@@ -932,8 +940,8 @@ __device__ __forceinline__ void rescue_layer(const SegDesc& sd, float* __restric
     __syncthreads();
     for (int i = tid; i < nb; i += NT) s_hist[i] = 0u;
     __syncthreads();
-    for (int base = 0; base < sd.d; base += NT) {  // uniform trip count: the peeled add needs whole waves
-      const int i = base + tid;
+    for (int64_t base = 0; base < sd.d; base += NT) {  // uniform trip count: the peeled add needs whole waves
+      const int64_t i = base + tid;  // 64 bits: base + NT may pass 2^31
       uint32_t b = 0xFFFFFFFFu;
       if (i < sd.d) {
         const uint32_t key = __float_as_uint(rl[i]) & 0x7FFFFFFFu;
@@ -949,8 +957,8 @@ __device__ __forceinline__ void rescue_layer(const SegDesc& sd, float* __restric
   }
   const uint32_t T = prefix, rtake = k_rem;
   uint32_t gb = 0, eb = 0;  // keys above T and equal to T before the current block of NT elements
-  for (int base = 0; base < sd.d; base += NT) {
-    const int i = base + tid;
+  for (int64_t base = 0; base < sd.d; base += NT) {
+    const int64_t i = base + tid;
     uint32_t bits = 0u, fg = 0u, fe = 0u;
     if (i < sd.d) {
       bits = __float_as_uint(rl[i]);
@@ -964,7 +972,7 @@ __device__ __forceinline__ void rescue_layer(const SegDesc& sd, float* __restric
     const uint32_t g0 = gb + (excl & 0xFFFFu), e0 = eb + (excl >> 16);
     const uint32_t pos = g0 + (e0 < rtake ? e0 : rtake);
     if ((fg || (fe && e0 < rtake)) && pos < (uint32_t)sd.k) {
-      oi[pos] = i;
+      oi[pos] = (int32_t)i;
       ov[pos] = __uint_as_float(bits);
       rl[i] = 0.0f;
     }
@@ -1004,6 +1012,43 @@ __device__ __forceinline__ void reject_layer(int li, const LargeSeg& ls, const S
   else rescue_layer<NT>(sd, res, out_idx, out_val, s_hist, s_wt, s_sel);
 }
 
+// Partial bucket counts of the layers finished by groups: one workgroup per kCountTiles tiles
+// writes its 4096 counts and its number of candidates at or above tau_top (no atomics: k_finish
+// adds the parts).
+__global__ __launch_bounds__(1024) void k_group_h(const GroupDesc* __restrict__ hparts,
+                                                  const LargeSeg* __restrict__ lsegs,
+                                                  const LState* __restrict__ lstate,
+                                                  const uint32_t* __restrict__ chunk_cnt,
+                                                  const uint2* __restrict__ slots, int nslot,
+                                                  uint32_t* __restrict__ bh_part, uint32_t* __restrict__ top_part) {
+  constexpr int NW = 16;
+  __shared__ uint32_t s_fine[kFineBins];
+  __shared__ uint32_t s_top[NW];
+  const GroupDesc hp = hparts[blockIdx.x];
+  const LargeSeg ls = lsegs[hp.lseg];
+  const LState st = lstate[hp.lseg];
+  const int tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
+  reinterpret_cast<uint4*>(s_fine)[tid] = make_uint4(0u, 0u, 0u, 0u);
+  __syncthreads();
+  constexpr int kWcPerPart = kCountTiles / kWaveTiles;
+  const int nwc = (ls.chunk_end - ls.chunk_begin + kWaveTiles - 1) / kWaveTiles;
+  const int q_end = (hp.first + 1) * kWcPerPart < nwc ? (hp.first + 1) * kWcPerPart : nwc;
+  uint32_t n_top = 0;
+  for (int q = hp.first * kWcPerPart + w; q < q_end; q += NW) {
+    const WaveChunk wc = wc_open(ls.chunk_begin + q * kWaveTiles, ls.chunk_end, chunk_cnt, nslot, lane);
+    n_top += wc_count(wc, slots, nslot, st.tau, st.tau_top, st.shift, s_fine, lane);
+  }
+  if (lane == 0) s_top[w] = n_top;
+  __syncthreads();
+  reinterpret_cast<uint4*>(bh_part + (int64_t)blockIdx.x * kFineBins)[tid] = reinterpret_cast<const uint4*>(s_fine)[tid];
+  if (tid == 0) {
+    uint32_t t = 0;
+#pragma unroll
+    for (int i = 0; i < NW; ++i) t += s_top[i];
+    top_part[blockIdx.x] = t;
+  }
+}
+
 // One workgroup per large layer.  Layers that are not sampled hand their tiles to the
 // multi-pass kernels.  Sampled layers get their verdict and decisive bucket; those of at most
 // kFusedTiles tiles are finished here, the others by k_group_a and k_group_b.
@@ -1012,20 +1057,23 @@ __global__ __launch_bounds__(1024) void k_finish(const SegDesc* __restrict__ seg
                                                  LState* __restrict__ lstate,
                                                  const uint32_t* __restrict__ chunk_cnt,
                                                  const uint2* __restrict__ slots, int nslot,
-                                                 const uint32_t* __restrict__ bh,
+                                                 const uint32_t* __restrict__ bh_part,
+                                                 const uint32_t* __restrict__ top_part,
                                                  float* __restrict__ res, int32_t* __restrict__ out_idx,
                                                  float* __restrict__ out_val, uint32_t* __restrict__ counter,
                                                  int32_t* __restrict__ items, int chain,
                                                  uint32_t* __restrict__ fail_flag) {
   constexpr int NT = 1024, NW = 16;
   constexpr int kMaxWc = kFusedTiles / kWaveTiles;
+  static_assert(kMaxWc <= NT, "one thread per wave chunk in the scan of their counts");
   __shared__ uint2 s_band[kBandCap];
-  __shared__ uint32_t s_hist[kBins0];
+  __shared__ uint32_t s_fine[kFineBins];   // bucket counts; the rescue's histograms reuse it
   __shared__ uint32_t s_wt[2 * NW];
   __shared__ uint32_t s_sel[2];
   __shared__ uint32_t s_ti[2];
   __shared__ uint32_t s_nband;
   __shared__ uint32_t s_wgt[kMaxWc];
+  static_assert(kFineBins >= kBins0, "the rescue's histogram fits");
   const int li = blockIdx.x, tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
   const LargeSeg ls = lsegs[li];
   const SegDesc sd = segs[ls.seg];
@@ -1034,30 +1082,65 @@ __global__ __launch_bounds__(1024) void k_finish(const SegDesc* __restrict__ seg
     return;
   }
   const LState st = lstate[li];
-  // totals of the tiles: candidates, candidates at or above tau_top, overflowed tiles
+  const int nwc = (ls.chunk_end - ls.chunk_begin + kWaveTiles - 1) / kWaveTiles;
+  // totals of the tiles: candidates, overflowed tiles
   uint32_t n = 0, ntop = 0;
   int over = 0;
-  for (int c = ls.chunk_begin + tid; c < ls.chunk_end; c += NT) {
-    const uint32_t word = chunk_cnt[c];
-    over |= (word & 0xFFFFu) > (uint32_t)nslot;
-    n += word & 0xFFFFu;
-    ntop += word >> 16;
+  {
+    const int c_end = ls.chunk_end;
+    for (int c0 = ls.chunk_begin + tid; c0 < c_end; c0 += 8 * NT) {
+      uint32_t v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = c0 + u * NT < c_end ? chunk_cnt[c0 + u * NT] : 0u;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        over |= v[u] > (uint32_t)nslot;
+        n += v[u];
+      }
+    }
+  }
+  // bucket counts: of the own slots (fused), or the sum of the parts that k_group_h wrote
+  if (ls.fused) {
+    reinterpret_cast<uint4*>(s_fine)[tid] = make_uint4(0u, 0u, 0u, 0u);
+    __syncthreads();
+    for (int q = w; q < nwc; q += NW) {
+      const WaveChunk wc = wc_open(ls.chunk_begin + q * kWaveTiles, ls.chunk_end, chunk_cnt, nslot, lane);
+      ntop += wc_count(wc, slots, nslot, st.tau, st.tau_top, st.shift, s_fine, lane);
+    }
+    ntop = lane == 0 ? ntop : 0u;  // the count is wave-uniform: one lane carries it into the sum
+  } else {
+    uint4 acc = make_uint4(0u, 0u, 0u, 0u);
+    const uint4* part = reinterpret_cast<const uint4*>(bh_part + (int64_t)ls.group_h_begin * kFineBins) + tid;
+    const int np = ls.group_h_end - ls.group_h_begin;
+    int p = 0;
+    for (; p + 4 <= np; p += 4) {
+      uint4 v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) v[u] = part[(int64_t)(p + u) * (kFineBins / 4)];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) { acc.x += v[u].x; acc.y += v[u].y; acc.z += v[u].z; acc.w += v[u].w; }
+    }
+    for (; p < np; ++p) {
+      const uint4 v = part[(int64_t)p * (kFineBins / 4)];
+      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
+    reinterpret_cast<uint4*>(s_fine)[tid] = acc;
+    for (int h = tid; h < np; h += NT) ntop += top_part[ls.group_h_begin + h];
   }
   block_sum2<NT>(n, ntop, s_wt);
   over = __syncthreads_or(over);
   const uint32_t k = (uint32_t)sd.k;
-  const uint32_t* bhl = bh + (int64_t)li * kFineBins;
   uint32_t bstar = 0, k_rem = 0, n_band = 0;
   bool ok = !over && n >= k && ntop < k;  // uniform over the workgroup
   if (ok) {
-    ok = find_rank<NT>(bhl, kFineBins, k - ntop, s_wt, s_sel, bstar, k_rem);
+    ok = find_rank<NT>(s_fine, kFineBins, k - ntop, s_wt, s_sel, bstar, k_rem);
     if (ok) {
-      n_band = bhl[bstar];
+      n_band = s_fine[bstar];
       ok = n_band <= (uint32_t)kBandCap;
     }
   }
   if (!ok) {
-    reject_layer<NT>(li, ls, sd, chain, lstate, fail_flag, counter, items, res, out_idx, out_val, s_hist, s_wt, s_sel);
+    reject_layer<NT>(li, ls, sd, chain, lstate, fail_flag, counter, items, res, out_idx, out_val, s_fine, s_wt, s_sel);
     return;
   }
   if (!ls.fused) {
@@ -1070,7 +1153,6 @@ __global__ __launch_bounds__(1024) void k_finish(const SegDesc* __restrict__ seg
     return;
   }
   // one workgroup finishes the layer: a wave takes every 16th wave chunk
-  const int nwc = (ls.chunk_end - ls.chunk_begin + kWaveTiles - 1) / kWaveTiles;  // <= kMaxWc
   if (tid == 0) s_nband = 0u;
   __syncthreads();
   for (int q = w; q < nwc; q += NW) {
@@ -1082,15 +1164,22 @@ __global__ __launch_bounds__(1024) void k_finish(const SegDesc* __restrict__ seg
   __syncthreads();
   const uint32_t m = s_nband < (uint32_t)kBandCap ? s_nband : (uint32_t)kBandCap;  // equals n_band
   if (tid == 0) { s_ti[0] = 0xFFFFFFFFu; s_ti[1] = 0u; }
+  // exclusive scan of the wave chunks' counts (in place)
+  {
+    const uint32_t v = tid < nwc ? s_wgt[tid] : 0u;
+    uint32_t tot;
+    const uint32_t incl = block_incl_scan<NT>(v, s_wt, tot);
+    if (tid < nwc) s_wgt[tid] = incl - v;
+  }
   __syncthreads();
-  band_select<NT>(s_band, m, k_rem, s_ti);
+  band_select<NT>(s_band, m, k_rem, st.tau + (bstar << st.shift), st.shift, s_fine, s_wt, s_sel, s_ti);
   const uint32_t T = s_ti[0], I = s_ti[1];
   int32_t* oi = out_idx + sd.out_offset;
   float* ov = out_val + sd.out_offset;
   float* rl = res + sd.offset;
   for (int q = w; q < nwc; q += NW) {
-    uint32_t pos0 = band_kept_before(s_band, m, T, I, (uint32_t)q * (uint32_t)(kWaveTiles * kTile), lane);
-    for (int p = 0; p < q; ++p) pos0 += s_wgt[p];
+    const uint32_t pos0 =
+        s_wgt[q] + band_kept_before(s_band, m, T, I, (uint32_t)q * (uint32_t)(kWaveTiles * kTile), lane);
     const WaveChunk wc = wc_open(ls.chunk_begin + q * kWaveTiles, ls.chunk_end, chunk_cnt, nslot, lane);
     wc_phase_b(wc, slots, nslot, T, I, pos0, k, sd.d, oi, ov, rl, lane);
   }
@@ -1100,15 +1189,15 @@ __global__ __launch_bounds__(1024) void k_finish(const SegDesc* __restrict__ seg
   }
 }
 
-// Phase A of the layers finished by groups: one workgroup per group of 128 tiles, one wave per
+// Phase A of the layers finished by groups: one workgroup per group of 64 tiles, one wave per
 // wave chunk.  Writes the wave chunks' counts of candidates above b* and the group's band entries.
-__global__ __launch_bounds__(256) void k_group_a(const GroupDesc* __restrict__ groups,
-                                                 const LargeSeg* __restrict__ lsegs,
-                                                 LState* __restrict__ lstate,
-                                                 const uint32_t* __restrict__ chunk_cnt,
-                                                 const uint2* __restrict__ slots, int nslot,
-                                                 uint32_t* __restrict__ wgt, uint2* __restrict__ band,
-                                                 uint32_t* __restrict__ band_cnt) {
+__global__ __launch_bounds__(kGroupWaves * 64) void k_group_a(const GroupDesc* __restrict__ groups,
+                                                            const LargeSeg* __restrict__ lsegs,
+                                                            LState* __restrict__ lstate,
+                                                            const uint32_t* __restrict__ chunk_cnt,
+                                                            const uint2* __restrict__ slots, int nslot,
+                                                            uint32_t* __restrict__ wgt, uint2* __restrict__ band,
+                                                            uint32_t* __restrict__ band_cnt) {
   __shared__ uint32_t s_nband;
   const GroupDesc gd = groups[blockIdx.x];
   const LState st = lstate[gd.lseg];
@@ -1137,24 +1226,25 @@ __global__ __launch_bounds__(256) void k_group_a(const GroupDesc* __restrict__ g
 // gathers the layer's band from all groups, selects T and I, sums the counts of the earlier
 // wave chunks and emits.  Workgroups behind them: one per such layer, which records the route
 // and, if some group's band overflowed, selects the layer from the residual buffer instead.
-__global__ __launch_bounds__(256) void k_group_b(int n_groups, const GroupDesc* __restrict__ groups,
-                                                 const int32_t* __restrict__ multi,
-                                                 const SegDesc* __restrict__ segs,
-                                                 const LargeSeg* __restrict__ lsegs,
-                                                 LState* __restrict__ lstate,
-                                                 const uint32_t* __restrict__ chunk_cnt,
-                                                 const uint2* __restrict__ slots, int nslot,
-                                                 const uint32_t* __restrict__ wgt,
-                                                 const uint2* __restrict__ band,
-                                                 const uint32_t* __restrict__ band_cnt,
-                                                 float* __restrict__ res, int32_t* __restrict__ out_idx,
-                                                 float* __restrict__ out_val, uint32_t* __restrict__ counter,
-                                                 int32_t* __restrict__ items, int chain,
-                                                 uint32_t* __restrict__ fail_flag) {
-  constexpr int NT = 256;
+__global__ __launch_bounds__(kGroupWaves * 64) void k_group_b(int n_groups, const GroupDesc* __restrict__ groups,
+                                                            const int32_t* __restrict__ multi,
+                                                            const SegDesc* __restrict__ segs,
+                                                            const LargeSeg* __restrict__ lsegs,
+                                                            LState* __restrict__ lstate,
+                                                            const uint32_t* __restrict__ chunk_cnt,
+                                                            const uint2* __restrict__ slots, int nslot,
+                                                            const uint32_t* __restrict__ wgt,
+                                                            const uint2* __restrict__ band,
+                                                            const uint32_t* __restrict__ band_cnt,
+                                                            float* __restrict__ res, int32_t* __restrict__ out_idx,
+                                                            float* __restrict__ out_val,
+                                                            uint32_t* __restrict__ counter,
+                                                            int32_t* __restrict__ items, int chain,
+                                                            uint32_t* __restrict__ fail_flag) {
+  constexpr int NT = kGroupWaves * 64;
   __shared__ uint2 s_band[kBandCap];
   __shared__ uint32_t s_hist[kBins0];
-  __shared__ uint32_t s_wt[8];
+  __shared__ uint32_t s_wt[2 * kGroupWaves];
   __shared__ uint32_t s_sel[2];
   __shared__ uint32_t s_ti[2];
   __shared__ uint32_t s_own[kGroupWaves];
@@ -1191,12 +1281,17 @@ __global__ __launch_bounds__(256) void k_group_b(int n_groups, const GroupDesc* 
   m = m < (uint32_t)kBandCap ? m : (uint32_t)kBandCap;  // equals n_band
   if (tid == 0) { s_ti[0] = 0xFFFFFFFFu; s_ti[1] = 0u; }
   __syncthreads();
-  band_select<NT>(s_band, m, st.k_rem, s_ti);
+  band_select<NT>(s_band, m, st.k_rem, st.tau + (st.bstar << st.shift), st.shift, s_hist, s_wt, s_sel, s_ti);
   const uint32_t T = s_ti[0], I = s_ti[1];
   // kept candidates above b* in the wave chunks before this group, then inside it
   const int q0 = gd.first * kGroupWaves;
   uint32_t before = 0, unused = 0;
-  for (int p = tid; p < q0; p += NT) before += wgt[ls.wchunk_begin + p];
+  for (int p0 = tid; p0 < q0; p0 += 4 * NT) {
+    uint32_t v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) v[u] = p0 + u * NT < q0 ? wgt[ls.wchunk_begin + p0 + u * NT] : 0u;
+    before += (v[0] + v[1]) + (v[2] + v[3]);
+  }
   block_sum2<NT>(before, unused, s_wt);
   const int q = q0 + w;
   const int c0 = ls.chunk_begin + q * kWaveTiles;
@@ -1729,7 +1824,8 @@ __global__ __launch_bounds__(256) void k_delta_finish(const SegDesc* __restrict_
 // ------------------------------------------------------------------ launch ---
 const char* kernel_name(int id) {
   static const char* names[K_NUM] = {
-      "k_prep", "k_small<4,1>", "k_small<4,8>", "k_small<16,10>", "k_stream", "k_finish", "k_group_a", "k_group_b",
+      "k_prep", "k_small<4,1>", "k_small<4,8>", "k_small<16,10>", "k_stream", "k_group_h", "k_finish", "k_group_a",
+      "k_group_b",
       "k_hist", "k_count", "k_scan", "k_emit", "k_merge_bounds", "k_merge", "k_merge<apply>", "k_delta_tiles",
       "k_delta_finish", "sparsify_call"};
   return (id >= 0 && id < K_NUM) ? names[id] : nullptr;
@@ -1772,12 +1868,8 @@ hipError_t launch_large(const LargePlan& pl, const Scratch& sc, const SegDesc* s
   const int ch = chain ? 1 : 0;
   {
     ProfScope ps(prof, K_PREP, s);
-    if (pl.big_sample)
-      hipLaunchKernelGGL((k_prep<true>), dim3(pl.n_large), dim3(1024), 0, s, segs, pl.lsegs, grad, res, lr, sc.lstate,
-                         sc.bh, sc.ghist, counters, ch);
-    else
-      hipLaunchKernelGGL((k_prep<false>), dim3(pl.n_large), dim3(1024), 0, s, segs, pl.lsegs, grad, res, lr,
-                         sc.lstate, sc.bh, sc.ghist, counters, ch);
+    hipLaunchKernelGGL(k_prep, dim3(pl.n_large), dim3(1024), 0, s, segs, pl.lsegs, grad, res, lr, sc.lstate, sc.ghist,
+                       counters, ch);
   }
   {
     const int nl = (pl.n_tiles + kStreamLaunchTiles - 1) / kStreamLaunchTiles;
@@ -1785,24 +1877,30 @@ hipError_t launch_large(const LargePlan& pl, const Scratch& sc, const SegDesc* s
     for (int t0 = 0; t0 < pl.n_tiles; t0 += kStreamLaunchTiles) {
       const int nt = pl.n_tiles - t0 < kStreamLaunchTiles ? pl.n_tiles - t0 : kStreamLaunchTiles;
       hipLaunchKernelGGL((k_stream<kStreamWaves, kStreamV>), dim3(nt), dim3(kStreamWaves * 64), kStreamLdsPad, s,
-                         pl.tiles + t0, grad, res, lr, sc.lstate, sc.chunk_cnt, sc.slots, pl.slot, sc.bh, sc.ghist);
+                         pl.tiles + t0, grad, res, lr, sc.lstate, sc.chunk_cnt, sc.slots, pl.slot, sc.ghist);
     }
+  }
+  if (pl.n_hparts > 0) {
+    ProfScope ps(prof, K_GROUP_H, s);
+    hipLaunchKernelGGL(k_group_h, dim3(pl.n_hparts), dim3(1024), 0, s, pl.hparts, pl.lsegs, sc.lstate, sc.chunk_cnt,
+                       sc.slots, pl.slot, sc.bh_part, sc.top_part);
   }
   {
     ProfScope ps(prof, K_FINISH, s);
     hipLaunchKernelGGL(k_finish, dim3(pl.n_large), dim3(1024), 0, s, segs, pl.lsegs, sc.lstate, sc.chunk_cnt,
-                       sc.slots, pl.slot, sc.bh, res, out_idx, out_val, counters, sc.items, ch, sc.fail_flag);
+                       sc.slots, pl.slot, sc.bh_part, sc.top_part, res, out_idx, out_val, counters, sc.items, ch,
+                       sc.fail_flag);
   }
   if (pl.n_groups > 0) {
     {
       ProfScope ps(prof, K_GROUP_A, s);
-      hipLaunchKernelGGL(k_group_a, dim3(pl.n_groups), dim3(256), 0, s, pl.groups, pl.lsegs, sc.lstate, sc.chunk_cnt,
-                         sc.slots, pl.slot, sc.wgt, sc.band, sc.band_cnt);
+      hipLaunchKernelGGL(k_group_a, dim3(pl.n_groups), dim3(kGroupWaves * 64), 0, s, pl.groups, pl.lsegs, sc.lstate,
+                         sc.chunk_cnt, sc.slots, pl.slot, sc.wgt, sc.band, sc.band_cnt);
     }
     ProfScope ps(prof, K_GROUP_B, s);
-    hipLaunchKernelGGL(k_group_b, dim3(pl.n_groups + pl.n_multi), dim3(256), 0, s, pl.n_groups, pl.groups, pl.multi,
-                       segs, pl.lsegs, sc.lstate, sc.chunk_cnt, sc.slots, pl.slot, sc.wgt, sc.band, sc.band_cnt, res,
-                       out_idx, out_val, counters, sc.items, ch, sc.fail_flag);
+    hipLaunchKernelGGL(k_group_b, dim3(pl.n_groups + pl.n_multi), dim3(kGroupWaves * 64), 0, s, pl.n_groups,
+                       pl.groups, pl.multi, segs, pl.lsegs, sc.lstate, sc.chunk_cnt, sc.slots, pl.slot, sc.wgt,
+                       sc.band, sc.band_cnt, res, out_idx, out_val, counters, sc.items, ch, sc.fail_flag);
   }
   if (chain) {
     const dim3 grid(kDenseGrid), b(256);
