@@ -201,7 +201,7 @@ int lags_last_routes(lags_ctx *ctx, const lags_table *t, int32_t *route, int32_t
  * Results are the same in every mode. */
 int lags_debug_fallback_chain(lags_ctx *ctx, int mode);
 
-/* Diagnostic: address and size of the context's scratch buffer number `which` (0 <= which < 15),
+/* Diagnostic: address and size of the context's scratch buffer number `which` (0 <= which < 16),
  * and how many outgrown buffers the context keeps alive for recorded graphs. */
 int lags_debug_scratch_info(lags_ctx *ctx, int which, const void **ptr, int64_t *bytes, int64_t *retired);
 

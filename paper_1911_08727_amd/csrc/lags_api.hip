@@ -54,7 +54,7 @@ struct DevBuf {
 struct lags_ctx {
   int device = 0;
   // scratch of the large layers' path, sized for the largest table created so far
-  DevBuf bh_part, top_part, lstate, chunk_cnt, slots, wgt, band, band_cnt, ghist, dstate, tile_gt, tile_eq, items;
+  DevBuf bh_part, coarse_part, part_info, lstate, chunk_cnt, slots, wgt, band, band_cnt, ghist, dstate, tile_gt, tile_eq, items;
   DevBuf bounds;   // merge: P rows of tile start positions, sized at the first merge call that needs it
   DevBuf partials; // delta metric: two doubles per merge tile
   // Once a call of this context has been recorded by stream capture, scratch that has to grow is
@@ -78,7 +78,8 @@ struct lags_ctx {
   Scratch scratch() const {
     Scratch sc;
     sc.bh_part = static_cast<uint32_t*>(bh_part.p);
-    sc.top_part = static_cast<uint32_t*>(top_part.p);
+    sc.coarse_part = static_cast<uint32_t*>(coarse_part.p);
+    sc.part_info = static_cast<uint4*>(part_info.p);
     sc.lstate = static_cast<LState*>(lstate.p);
     sc.chunk_cnt = static_cast<uint32_t*>(chunk_cnt.p);
     sc.slots = static_cast<uint2*>(slots.p);
@@ -152,7 +153,7 @@ bool ranges_overlap(const void* a, int64_t abytes, const void* b, int64_t bbytes
 }
 
 std::vector<DevBuf*> all_bufs(lags_ctx* ctx) {
-  return {&ctx->bh_part, &ctx->top_part, &ctx->lstate, &ctx->chunk_cnt, &ctx->slots, &ctx->wgt, &ctx->band, &ctx->band_cnt, &ctx->ghist,
+  return {&ctx->bh_part, &ctx->coarse_part, &ctx->part_info, &ctx->lstate, &ctx->chunk_cnt, &ctx->slots, &ctx->wgt, &ctx->band, &ctx->band_cnt, &ctx->ghist,
           &ctx->dstate, &ctx->tile_gt, &ctx->tile_eq, &ctx->items, &ctx->bounds, &ctx->partials};
 }
 
@@ -361,7 +362,8 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
     std::vector<void*>* rl = ctx->retire_list();
     const size_t nl = (size_t)pl.n_large;
     if (rc == LAGS_OK) rc = ctx->bh_part.grow((size_t)pl.n_hparts * kFineBins * sizeof(uint32_t), rl);
-    if (rc == LAGS_OK) rc = ctx->top_part.grow((size_t)pl.n_hparts * sizeof(uint32_t), rl);
+    if (rc == LAGS_OK) rc = ctx->coarse_part.grow((size_t)pl.n_hparts * kCoarseBins * sizeof(uint32_t), rl);
+    if (rc == LAGS_OK) rc = ctx->part_info.grow((size_t)pl.n_hparts * sizeof(uint4), rl);
     if (rc == LAGS_OK) rc = ctx->lstate.grow(nl * sizeof(LState), rl);
     if (rc == LAGS_OK) rc = ctx->chunk_cnt.grow((size_t)pl.n_chunks * sizeof(uint32_t), rl);
     if (rc == LAGS_OK) rc = ctx->slots.grow((size_t)pl.n_chunks * (size_t)pl.slot * sizeof(uint2), rl);

@@ -48,7 +48,8 @@ constexpr int kWaveTiles = 8;            // a wave flattens the slots of 8 conse
 constexpr int kGroupWaves = 8;           // a workgroup of the multi-workgroup finish: 8 wave chunks
 constexpr int kGroupTiles = kWaveTiles * kGroupWaves;
 constexpr int kGroupBand = 64;           // band entries one group may contribute
-constexpr int kCountTiles = 512;         // tiles per workgroup of the partial bucket counts
+constexpr int kCountTiles = 256;         // tiles per workgroup of the partial bucket counts
+constexpr int kCoarseBins = 64;          // those counts are also summed over runs of 64 buckets
 constexpr int kFusedTiles = 512;         // sampled layers of up to this many tiles are finished by one workgroup
 // The streaming pass is HBM-bound and runs best when each CU holds only three of its
 // workgroups (12 waves, about 96 KB of loads in flight per CU): measured on MI355X, 26.6 GB in
@@ -121,6 +122,7 @@ enum : uint32_t { MODE_DENSE = 0, MODE_SPARSE = 1 };
 
 struct LState {         // per call, per large layer
   uint32_t tau;         // candidates are the entries with key >= tau
+  uint32_t t_zero;      // candidates with key >= t_zero had their residual zeroed by the streaming pass
   uint32_t tau_top;     // candidates with key >= tau_top are counted in one number, the others per bucket
   uint32_t shift;       // bucket of a candidate below tau_top: (key - tau) >> shift
   uint32_t mode;        // MODE_SPARSE: the guess held, the slots contain the top k
@@ -129,7 +131,8 @@ struct LState {         // per call, per large layer
   uint32_t n_band;      // entries in that bucket
   uint32_t band_over;   // a group collected more band entries than it can hold
   uint32_t route;       // for lags_last_routes: 1 accepted, 2 rejected, 3 not sampled
-  uint32_t pad[3];
+  uint32_t T, I;        // multi-workgroup finish: kept = key > T, or key == T and index <= I
+
 };
 
 struct DState {         // per call, per large layer on the multi-pass route: the radix select's progress
@@ -153,11 +156,12 @@ struct LargePlan {      // everything launch_large needs (device pointers + coun
 
 struct Scratch {        // context-owned device memory, contents meaningless between calls
   uint32_t* bh_part = nullptr;    // n_hparts * kFineBins: partial bucket counts
-  uint32_t* top_part = nullptr;   // n_hparts: candidates at or above tau_top
+  uint32_t* coarse_part = nullptr;  // n_hparts * kCoarseBins: their sums over runs of 64 buckets
+  uint4* part_info = nullptr;     // n_hparts: candidates, candidates at or above tau_top, overflow flag
   LState* lstate = nullptr;       // n_large
   uint32_t* chunk_cnt = nullptr;  // n_chunks: candidates of the tile
   uint2* slots = nullptr;         // n_chunks * slot
-  uint32_t* wgt = nullptr;        // n_wchunks: entries above the decisive bucket per wave chunk
+  uint32_t* wgt = nullptr;        // n_wchunks: entries above the decisive bucket per wave chunk, then output positions
   uint2* band = nullptr;          // n_groups * kGroupBand
   uint32_t* band_cnt = nullptr;   // n_groups
   // multi-pass route (layers that are not sampled, rejected guesses)
@@ -171,7 +175,7 @@ struct Scratch {        // context-owned device memory, contents meaningless bet
 
 // Kernel ids for the optional event timing.
 enum KernelId {
-  K_PREP = 0, K_SMALL0, K_SMALL1, K_SMALL2, K_STREAM, K_GROUP_H, K_FINISH, K_GROUP_A, K_GROUP_B,
+  K_PREP = 0, K_SMALL0, K_SMALL1, K_SMALL2, K_STREAM, K_GROUP_H, K_FINISH, K_GROUP_A, K_GROUP_P, K_GROUP_B,
   K_HIST, K_COUNT, K_SCAN, K_EMIT,
   K_MERGE_BOUNDS, K_MERGE, K_MERGE_APPLY, K_DELTA_TILES, K_DELTA_FINISH,
   K_SPARSIFY_CALL,      // not a kernel: the whole sparsify call on the caller's stream, fork to join

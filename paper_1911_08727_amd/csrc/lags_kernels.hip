@@ -585,6 +585,7 @@ __global__ __launch_bounds__(1024) void k_prep(const SegDesc* __restrict__ segs,
     const uint64_t top = (uint64_t)tau + ((uint64_t)kFineBins << shift);
     LState st = {};
     st.tau = tau;
+    st.t_zero = t_est;
     st.tau_top = top > 0x80000000ull ? 0x80000000u : (uint32_t)top;  // keys are below 2^31
     st.shift = shift;
     st.mode = MODE_DENSE;
@@ -607,10 +608,11 @@ __device__ __forceinline__ void store_bits_nt(float* __restrict__ r, int lane, c
 // Candidate collection of one tile inside the streaming pass (all waves of the workgroup call
 // it; contains one barrier).  Every entry with key >= tau goes, in index order, into the
 // tile's slots (entries beyond nslot are dropped; the count written to *cnt then exceeds nslot
-// and marks the tile as overflowed).  FULL: the wave's chunk is complete, no bounds checks.
+// and marks the tile as overflowed), and collected entries with key >= t_zero are replaced by
+// zero in `a`.  FULL: the wave's chunk is complete, no bounds checks.
 template <int NW, int V, bool FULL>
-__device__ __forceinline__ void stream_collect(const uint32_t (&a)[V][4], int n_w, int lane, int w, uint32_t tau,
-                                               int32_t idx0, uint2* __restrict__ slot, int nslot,
+__device__ __forceinline__ void stream_collect(uint32_t (&a)[V][4], int n_w, int lane, int w, uint32_t tau,
+                                               uint32_t t_zero, int32_t idx0, uint2* __restrict__ slot, int nslot,
                                                uint32_t* __restrict__ cnt, uint32_t* s_cnt) {
   // one ballot per element slot of the wave; bitwise & keeps the code free of branches
   uint64_t m[V][4];
@@ -650,7 +652,13 @@ __device__ __forceinline__ void stream_collect(const uint32_t (&a)[V][4], int n_
       for (int c = 0; c < 4; ++c) {
         const uint32_t key = a[j][c] & 0x7FFFFFFFu;
         const bool f = FULL ? key >= tau : ((key >= tau) & (e + c < n_w));
-        if (f & (pos < (uint32_t)nslot)) slot[pos] = make_uint2((uint32_t)(idx0 + e + c), a[j][c]);
+        const bool put = f & (pos < (uint32_t)nslot);
+        if (put) slot[pos] = make_uint2((uint32_t)(idx0 + e + c), a[j][c]);
+        // an entry at or above t_zero is expected to be kept: its residual is written as zero
+        // right here, with the rest of its line (its value is safe in the slot); the finish
+        // corrects the entries for which that expectation turns out wrong.  A scattered 4-byte
+        // write later costs about as much as a whole line of this pass.
+        a[j][c] = (put & (key >= t_zero)) ? 0u : a[j][c];
         pos += f ? 1u : 0u;
       }
       base += tot;
@@ -682,9 +690,10 @@ __global__ __launch_bounds__(NW * 64) void k_stream(const TileDesc* __restrict__
   const TileDesc td = tiles[blockIdx.x];
   const int tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
   const bool collect = td.ctile >= 0;  // uniform over the workgroup
-  uint32_t tau = 0;
+  uint32_t tau = 0, t_zero = 0;
   if (collect) {
     tau = lstate[td.seg].tau;
+    t_zero = lstate[td.seg].t_zero;
   } else {
     for (int i = tid; i < kBins0; i += NT) s_hist[i] = 0u;
   }
@@ -716,8 +725,8 @@ __global__ __launch_bounds__(NW * 64) void k_stream(const TileDesc* __restrict__
     uint2* slot = slots + (int64_t)td.ctile * nslot;
     uint32_t* cnt = chunk_cnt + td.ctile;
     const int32_t idx0 = td.local0 + w * WC;
-    if (fast) stream_collect<NW, V, true>(a, n_w, lane, w, tau, idx0, slot, nslot, cnt, s_cnt);
-    else stream_collect<NW, V, false>(a, n_w, lane, w, tau, idx0, slot, nslot, cnt, s_cnt);
+    if (fast) stream_collect<NW, V, true>(a, n_w, lane, w, tau, t_zero, idx0, slot, nslot, cnt, s_cnt);
+    else stream_collect<NW, V, false>(a, n_w, lane, w, tau, t_zero, idx0, slot, nslot, cnt, s_cnt);
     if (fast) store_bits_nt<V>(r, lane, a);
     else store_bits<V>(r, n_w, vec, lane, a);
   } else {
@@ -756,9 +765,12 @@ __global__ __launch_bounds__(NW * 64) void k_stream(const TileDesc* __restrict__
 //             chunks + kept band entries with a smaller index + rank inside the wave chunk) and
 //             zeroes their residual.
 // Layers of up to kFusedTiles tiles do all of it in one workgroup (k_finish).  Larger ones take
-// one launch per step: k_group_h (partial bucket counts per 512 tiles), k_finish (decides),
-// k_group_a and k_group_b over groups of 64 tiles, every workgroup of phase B selecting T and
-// I for itself from the band.  No workgroup ever waits for another one, and nothing is added
+// one launch per step: k_group_h (partial bucket counts per 256 tiles), k_finish (decides),
+// k_group_a over groups of 64 tiles, k_group_p (one workgroup per layer: selects, turns the
+// counts into output positions), k_group_b over the groups again.  Work that every group would
+// repeat is done once per layer: hundreds of workgroups reading the same few kilobytes at the
+// same time queue up at the cache channels that hold them (measured 30 us instead of 10 for the
+// 392 groups of a 100 M-element layer).  No workgroup ever waits for another one, and nothing is added
 // with global atomics.
 
 // A wave's view of the slots of up to kWaveTiles consecutive tiles as one flat, index-ordered list.
@@ -901,24 +913,49 @@ __device__ __forceinline__ uint32_t band_kept_before(const uint2* s_band, uint32
   return wave_sum(c);
 }
 
-// Phase B over one wave chunk: the kept entries go to out[pos0 ...] in index order and their
-// residual is zeroed.  Positions are checked against k so that no state can write out of bounds.
+// Phase B over one wave chunk: the kept entries go to out[pos0 ...] in index order.  The
+// streaming pass wrote zero for the entries with key >= t_zero and acc for the others, so the
+// residual is written only where that differs from the outcome: zero for kept entries below
+// t_zero, acc for dropped entries at or above it.  Positions are checked against k so that no
+// state can write out of bounds.
 __device__ __forceinline__ void wc_phase_b(const WaveChunk& wc, const uint2* __restrict__ slots, int nslot,
-                                           uint32_t T, uint32_t I, uint32_t pos0, uint32_t k, int32_t d,
-                                           int32_t* __restrict__ oi, float* __restrict__ ov, float* __restrict__ rl,
-                                           int lane) {
+                                           uint32_t T, uint32_t I, uint32_t t_zero, uint32_t pos0, uint32_t k,
+                                           int32_t d, int32_t* __restrict__ oi, float* __restrict__ ov,
+                                           float* __restrict__ rl, int lane) {
   wc_for_each(wc, slots, nslot, lane, [&](uint2 en, bool live) {
     const uint32_t key = en.y & 0x7FFFFFFFu;
     const bool keep = live && (key > T || (key == T && en.x <= I));
+    const bool zeroed = key >= t_zero;  // what the streaming pass assumed
     const uint64_t mk = __ballot(keep);
     const uint32_t pos = pos0 + mbcnt64(mk);
-    if (keep && pos < k && en.x < (uint32_t)d) {
-      oi[pos] = (int32_t)en.x;
-      ov[pos] = __uint_as_float(en.y);
-      rl[en.x] = 0.0f;
+    if (live && en.x < (uint32_t)d) {
+      if (keep && pos < k) {
+        oi[pos] = (int32_t)en.x;
+        ov[pos] = __uint_as_float(en.y);
+      }
+      if (keep && !zeroed) rl[en.x] = 0.0f;
+      if (!keep && zeroed) rl[en.x] = __uint_as_float(en.y);
     }
     pos0 += (uint32_t)__popcll(mk);
   });
+}
+
+// Gives the entries that the streaming pass zeroed (slotted, key >= t_zero) their acc back:
+// a layer whose guess is rejected is selected from the acc values in the residual buffer.
+template <int NT>
+__device__ __forceinline__ void restore_layer(const LargeSeg& ls, const SegDesc& sd, uint32_t t_zero,
+                                              const uint32_t* __restrict__ chunk_cnt,
+                                              const uint2* __restrict__ slots, int nslot, float* __restrict__ res) {
+  const int lane = lane_id(), w = threadIdx.x >> 6;
+  const int nwc = (ls.chunk_end - ls.chunk_begin + kWaveTiles - 1) / kWaveTiles;
+  float* rl = res + sd.offset;
+  for (int q = w; q < nwc; q += NT / 64) {
+    const WaveChunk wc = wc_open(ls.chunk_begin + q * kWaveTiles, ls.chunk_end, chunk_cnt, nslot, lane);
+    wc_for_each(wc, slots, nslot, lane, [&](uint2 en, bool live) {
+      if (live && (en.y & 0x7FFFFFFFu) >= t_zero && en.x < (uint32_t)sd.d) rl[en.x] = __uint_as_float(en.y);
+    });
+  }
+  __syncthreads();  // the workgroup's own later reads of the residual see these writes
 }
 
 // Exact selection of one layer by one workgroup from the acc values in the residual buffer:
@@ -993,11 +1030,13 @@ __device__ __forceinline__ void append_tiles(const LargeSeg& ls, uint32_t* __res
   for (int j = threadIdx.x; j < nt; j += NT) items[b + j] = ls.tile_begin + j;
 }
 
-// A rejected guess: the layer is selected from the acc values in the residual buffer, by the
-// multi-pass kernels if they are enqueued in this call (chain), else by this workgroup.  The
-// context's pinned host word is set so that later calls enqueue them.
+// A rejected guess: the early zeros are undone and the layer is selected from the acc values
+// in the residual buffer, by the multi-pass kernels if they are enqueued in this call (chain),
+// else by this workgroup.  The context's pinned host word is set so that later calls enqueue them.
 template <int NT>
-__device__ __forceinline__ void reject_layer(int li, const LargeSeg& ls, const SegDesc& sd, int chain,
+__device__ __forceinline__ void reject_layer(int li, const LargeSeg& ls, const SegDesc& sd, uint32_t t_zero,
+                                             const uint32_t* __restrict__ chunk_cnt,
+                                             const uint2* __restrict__ slots, int nslot, int chain,
                                              LState* __restrict__ lstate, uint32_t* __restrict__ fail_flag,
                                              uint32_t* __restrict__ counter, int32_t* __restrict__ items,
                                              float* __restrict__ res, int32_t* __restrict__ out_idx,
@@ -1008,22 +1047,24 @@ __device__ __forceinline__ void reject_layer(int li, const LargeSeg& ls, const S
     lstate[li].route = 2u;
     __hip_atomic_store(fail_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
   }
+  restore_layer<NT>(ls, sd, t_zero, chunk_cnt, slots, nslot, res);
   if (chain) append_tiles<NT>(ls, counter, items, s_sel);
   else rescue_layer<NT>(sd, res, out_idx, out_val, s_hist, s_wt, s_sel);
 }
 
 // Partial bucket counts of the layers finished by groups: one workgroup per kCountTiles tiles
-// writes its 4096 counts and its number of candidates at or above tau_top (no atomics: k_finish
-// adds the parts).
+// writes its 4096 counts, their sums over runs of 64 buckets, and its totals (candidates,
+// candidates at or above tau_top, whether a tile overflowed).  No atomics: k_finish adds the parts.
 __global__ __launch_bounds__(1024) void k_group_h(const GroupDesc* __restrict__ hparts,
                                                   const LargeSeg* __restrict__ lsegs,
                                                   const LState* __restrict__ lstate,
                                                   const uint32_t* __restrict__ chunk_cnt,
                                                   const uint2* __restrict__ slots, int nslot,
-                                                  uint32_t* __restrict__ bh_part, uint32_t* __restrict__ top_part) {
+                                                  uint32_t* __restrict__ bh_part, uint32_t* __restrict__ coarse_part,
+                                                  uint4* __restrict__ part_info) {
   constexpr int NW = 16;
   __shared__ uint32_t s_fine[kFineBins];
-  __shared__ uint32_t s_top[NW];
+  __shared__ uint32_t s_tot[3 * NW];
   const GroupDesc hp = hparts[blockIdx.x];
   const LargeSeg ls = lsegs[hp.lseg];
   const LState st = lstate[hp.lseg];
@@ -1033,20 +1074,47 @@ __global__ __launch_bounds__(1024) void k_group_h(const GroupDesc* __restrict__ 
   constexpr int kWcPerPart = kCountTiles / kWaveTiles;
   const int nwc = (ls.chunk_end - ls.chunk_begin + kWaveTiles - 1) / kWaveTiles;
   const int q_end = (hp.first + 1) * kWcPerPart < nwc ? (hp.first + 1) * kWcPerPart : nwc;
-  uint32_t n_top = 0;
+  uint32_t n = 0, n_top = 0, over = 0;  // wave-uniform
   for (int q = hp.first * kWcPerPart + w; q < q_end; q += NW) {
-    const WaveChunk wc = wc_open(ls.chunk_begin + q * kWaveTiles, ls.chunk_end, chunk_cnt, nslot, lane);
+    const int c0 = ls.chunk_begin + q * kWaveTiles;
+    const uint32_t raw = (lane < kWaveTiles && c0 + lane < ls.chunk_end) ? chunk_cnt[c0 + lane] : 0u;
+    over |= __ballot(raw > (uint32_t)nslot) != 0ull;
+    n += wave_sum(raw);
+    const WaveChunk wc = wc_open(c0, ls.chunk_end, chunk_cnt, nslot, lane);
     n_top += wc_count(wc, slots, nslot, st.tau, st.tau_top, st.shift, s_fine, lane);
   }
-  if (lane == 0) s_top[w] = n_top;
+  if (lane == 0) { s_tot[w] = n; s_tot[NW + w] = n_top; s_tot[2 * NW + w] = over; }
   __syncthreads();
-  reinterpret_cast<uint4*>(bh_part + (int64_t)blockIdx.x * kFineBins)[tid] = reinterpret_cast<const uint4*>(s_fine)[tid];
-  if (tid == 0) {
-    uint32_t t = 0;
+  const uint4 mine = reinterpret_cast<const uint4*>(s_fine)[tid];
+  reinterpret_cast<uint4*>(bh_part + (int64_t)blockIdx.x * kFineBins)[tid] = mine;
+  // buckets 64 c .. 64 c + 63 are held by the 16 threads 16 c .. 16 c + 15
+  uint32_t c4 = (mine.x + mine.y) + (mine.z + mine.w);
 #pragma unroll
-    for (int i = 0; i < NW; ++i) t += s_top[i];
-    top_part[blockIdx.x] = t;
+  for (int o = 8; o > 0; o >>= 1) c4 += __shfl_xor(c4, o, 64);
+  if ((tid & 15) == 0) coarse_part[(int64_t)blockIdx.x * kCoarseBins + (tid >> 4)] = c4;
+  if (tid == 0) {
+    uint4 info = make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+    for (int i = 0; i < NW; ++i) { info.x += s_tot[i]; info.y += s_tot[NW + i]; info.z |= s_tot[2 * NW + i]; }
+    part_info[blockIdx.x] = info;
   }
+}
+
+// Among 64 counts c[0..63] held one per lane (ordered by key), the bin that holds the entry of
+// rank `rank` counted from bin 63 downwards, and the rank inside that bin; false if they hold
+// fewer than `rank`.  Wave-uniform result.
+__device__ __forceinline__ bool wave_find_rank64(uint32_t c, uint32_t rank, int lane, uint32_t& bin,
+                                                 uint32_t& rank_in_bin, uint32_t& count_in_bin) {
+  const uint32_t rev = __shfl(c, 63 - lane, 64);           // lane l holds bin 63 - l
+  const uint32_t incl = wave_incl_scan(rev, lane);         // entries in bins 63 - l .. 63
+  const uint64_t reach = __ballot(incl >= rank);
+  if (reach == 0ull) return false;
+  const int l = __builtin_ctzll(reach);
+  const uint32_t at = __shfl(incl, l, 64), own = __shfl(rev, l, 64);
+  bin = (uint32_t)(63 - l);
+  rank_in_bin = rank - (at - own);
+  count_in_bin = own;
+  return true;
 }
 
 // One workgroup per large layer.  Layers that are not sampled hand their tiles to the
@@ -1058,7 +1126,8 @@ __global__ __launch_bounds__(1024) void k_finish(const SegDesc* __restrict__ seg
                                                  const uint32_t* __restrict__ chunk_cnt,
                                                  const uint2* __restrict__ slots, int nslot,
                                                  const uint32_t* __restrict__ bh_part,
-                                                 const uint32_t* __restrict__ top_part,
+                                                 const uint32_t* __restrict__ coarse_part,
+                                                 const uint4* __restrict__ part_info,
                                                  float* __restrict__ res, int32_t* __restrict__ out_idx,
                                                  float* __restrict__ out_val, uint32_t* __restrict__ counter,
                                                  int32_t* __restrict__ items, int chain,
@@ -1083,24 +1152,17 @@ __global__ __launch_bounds__(1024) void k_finish(const SegDesc* __restrict__ seg
   }
   const LState st = lstate[li];
   const int nwc = (ls.chunk_end - ls.chunk_begin + kWaveTiles - 1) / kWaveTiles;
-  // totals of the tiles: candidates, overflowed tiles
-  uint32_t n = 0, ntop = 0;
+  const uint32_t k = (uint32_t)sd.k;
+  uint32_t n = 0, ntop = 0, bstar = 0, k_rem = 0, n_band = 0;
   int over = 0;
-  {
-    const int c_end = ls.chunk_end;
-    for (int c0 = ls.chunk_begin + tid; c0 < c_end; c0 += 8 * NT) {
-      uint32_t v[8];
-#pragma unroll
-      for (int u = 0; u < 8; ++u) v[u] = c0 + u * NT < c_end ? chunk_cnt[c0 + u * NT] : 0u;
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        over |= v[u] > (uint32_t)nslot;
-        n += v[u];
-      }
-    }
-  }
-  // bucket counts: of the own slots (fused), or the sum of the parts that k_group_h wrote
+  bool ok;  // uniform over the workgroup
   if (ls.fused) {
+    // totals of the tiles (candidates, overflowed tiles) and bucket counts of the own slots
+    for (int c = ls.chunk_begin + tid; c < ls.chunk_end; c += NT) {  // at most kFusedTiles <= NT tiles
+      const uint32_t v = chunk_cnt[c];
+      over |= v > (uint32_t)nslot;
+      n += v;
+    }
     reinterpret_cast<uint4*>(s_fine)[tid] = make_uint4(0u, 0u, 0u, 0u);
     __syncthreads();
     for (int q = w; q < nwc; q += NW) {
@@ -1108,39 +1170,68 @@ __global__ __launch_bounds__(1024) void k_finish(const SegDesc* __restrict__ seg
       ntop += wc_count(wc, slots, nslot, st.tau, st.tau_top, st.shift, s_fine, lane);
     }
     ntop = lane == 0 ? ntop : 0u;  // the count is wave-uniform: one lane carries it into the sum
-  } else {
-    uint4 acc = make_uint4(0u, 0u, 0u, 0u);
-    const uint4* part = reinterpret_cast<const uint4*>(bh_part + (int64_t)ls.group_h_begin * kFineBins) + tid;
-    const int np = ls.group_h_end - ls.group_h_begin;
-    int p = 0;
-    for (; p + 4 <= np; p += 4) {
-      uint4 v[4];
-#pragma unroll
-      for (int u = 0; u < 4; ++u) v[u] = part[(int64_t)(p + u) * (kFineBins / 4)];
-#pragma unroll
-      for (int u = 0; u < 4; ++u) { acc.x += v[u].x; acc.y += v[u].y; acc.z += v[u].z; acc.w += v[u].w; }
-    }
-    for (; p < np; ++p) {
-      const uint4 v = part[(int64_t)p * (kFineBins / 4)];
-      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
-    }
-    reinterpret_cast<uint4*>(s_fine)[tid] = acc;
-    for (int h = tid; h < np; h += NT) ntop += top_part[ls.group_h_begin + h];
-  }
-  block_sum2<NT>(n, ntop, s_wt);
-  over = __syncthreads_or(over);
-  const uint32_t k = (uint32_t)sd.k;
-  uint32_t bstar = 0, k_rem = 0, n_band = 0;
-  bool ok = !over && n >= k && ntop < k;  // uniform over the workgroup
-  if (ok) {
-    ok = find_rank<NT>(s_fine, kFineBins, k - ntop, s_wt, s_sel, bstar, k_rem);
+    block_sum2<NT>(n, ntop, s_wt);
+    over = __syncthreads_or(over);
+    ok = !over && n >= k && ntop < k;
     if (ok) {
-      n_band = s_fine[bstar];
-      ok = n_band <= (uint32_t)kBandCap;
+      ok = find_rank<NT>(s_fine, kFineBins, k - ntop, s_wt, s_sel, bstar, k_rem);
+      if (ok) n_band = s_fine[bstar];
+    }
+  } else {
+    // the parts that k_group_h wrote: totals, then the run of 64 buckets that holds the k-th
+    // largest key from the coarse counts, then the bucket inside that run
+    const int h0 = ls.group_h_begin, np = ls.group_h_end - ls.group_h_begin;
+    for (int h = tid; h < np; h += NT) {
+      const uint4 info = part_info[h0 + h];
+      n += info.x;
+      ntop += info.y;
+      over |= info.z != 0u;
+    }
+    block_sum2<NT>(n, ntop, s_wt);
+    over = __syncthreads_or(over);
+    ok = !over && n >= k && ntop < k;
+    if (ok) {  // wave w adds the parts w, w + 16, ...; every wave then adds the 16 rows for itself
+      static_assert(kCoarseBins == 64 && kFineBins == 64 * kCoarseBins, "one lane per bin at both levels");
+      uint32_t acc = 0;
+      for (int h = w; h < np; h += 4 * NW) {
+        uint32_t v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+          v[u] = h + u * NW < np ? coarse_part[(int64_t)(h0 + h + u * NW) * kCoarseBins + lane] : 0u;
+        acc += (v[0] + v[1]) + (v[2] + v[3]);
+      }
+      s_fine[w * 64 + lane] = acc;
+      __syncthreads();
+      uint32_t c = 0;
+#pragma unroll
+      for (int i = 0; i < NW; ++i) c += s_fine[i * 64 + lane];
+      uint32_t crun = 0, rank_in_run = 0, unused = 0;
+      ok = wave_find_rank64(c, k - ntop, lane, crun, rank_in_run, unused);
+      __syncthreads();
+      if (ok) {
+        acc = 0;
+        for (int h = w; h < np; h += 4 * NW) {
+          uint32_t v[4];
+#pragma unroll
+          for (int u = 0; u < 4; ++u)
+            v[u] = h + u * NW < np ? bh_part[(int64_t)(h0 + h + u * NW) * kFineBins + crun * 64u + lane] : 0u;
+          acc += (v[0] + v[1]) + (v[2] + v[3]);
+        }
+        s_fine[w * 64 + lane] = acc;
+        __syncthreads();
+        c = 0;
+#pragma unroll
+        for (int i = 0; i < NW; ++i) c += s_fine[i * 64 + lane];
+        uint32_t b = 0;
+        ok = wave_find_rank64(c, rank_in_run, lane, b, k_rem, n_band);
+        bstar = crun * 64u + b;
+      }
     }
   }
+  ok = ok && n_band <= (uint32_t)kBandCap;
   if (!ok) {
-    reject_layer<NT>(li, ls, sd, chain, lstate, fail_flag, counter, items, res, out_idx, out_val, s_fine, s_wt, s_sel);
+    reject_layer<NT>(li, ls, sd, st.t_zero, chunk_cnt, slots, nslot, chain, lstate, fail_flag, counter, items, res,
+                     out_idx, out_val, s_fine, s_wt, s_sel);
     return;
   }
   if (!ls.fused) {
@@ -1181,7 +1272,7 @@ __global__ __launch_bounds__(1024) void k_finish(const SegDesc* __restrict__ seg
     const uint32_t pos0 =
         s_wgt[q] + band_kept_before(s_band, m, T, I, (uint32_t)q * (uint32_t)(kWaveTiles * kTile), lane);
     const WaveChunk wc = wc_open(ls.chunk_begin + q * kWaveTiles, ls.chunk_end, chunk_cnt, nslot, lane);
-    wc_phase_b(wc, slots, nslot, T, I, pos0, k, sd.d, oi, ov, rl, lane);
+    wc_phase_b(wc, slots, nslot, T, I, st.t_zero, pos0, k, sd.d, oi, ov, rl, lane);
   }
   if (tid == 0) {
     lstate[li].mode = MODE_SPARSE;
@@ -1222,88 +1313,119 @@ __global__ __launch_bounds__(kGroupWaves * 64) void k_group_a(const GroupDesc* _
   }
 }
 
-// Phase B of the layers finished by groups.  Workgroups [0, n_groups): one group each; it
-// gathers the layer's band from all groups, selects T and I, sums the counts of the earlier
-// wave chunks and emits.  Workgroups behind them: one per such layer, which records the route
-// and, if some group's band overflowed, selects the layer from the residual buffer instead.
-__global__ __launch_bounds__(kGroupWaves * 64) void k_group_b(int n_groups, const GroupDesc* __restrict__ groups,
-                                                            const int32_t* __restrict__ multi,
-                                                            const SegDesc* __restrict__ segs,
-                                                            const LargeSeg* __restrict__ lsegs,
-                                                            LState* __restrict__ lstate,
-                                                            const uint32_t* __restrict__ chunk_cnt,
-                                                            const uint2* __restrict__ slots, int nslot,
-                                                            const uint32_t* __restrict__ wgt,
-                                                            const uint2* __restrict__ band,
-                                                            const uint32_t* __restrict__ band_cnt,
-                                                            float* __restrict__ res, int32_t* __restrict__ out_idx,
-                                                            float* __restrict__ out_val,
-                                                            uint32_t* __restrict__ counter,
-                                                            int32_t* __restrict__ items, int chain,
-                                                            uint32_t* __restrict__ fail_flag) {
-  constexpr int NT = kGroupWaves * 64;
+// Between the phases of the layers finished by groups: one workgroup per such layer gathers the
+// band from all groups, selects T and I, and turns the wave chunks' counts of candidates above
+// b* into output positions (exclusive scan of count + kept band entries of the wave chunk, in
+// place).  If some group's band overflowed, the layer is selected from the residual buffer instead.
+__global__ __launch_bounds__(1024) void k_group_p(const int32_t* __restrict__ multi,
+                                                  const SegDesc* __restrict__ segs,
+                                                  const LargeSeg* __restrict__ lsegs,
+                                                  LState* __restrict__ lstate,
+                                                  const uint32_t* __restrict__ chunk_cnt,
+                                                  const uint2* __restrict__ slots, int nslot,
+                                                  uint32_t* __restrict__ wgt,
+                                                  const uint2* __restrict__ band,
+                                                  const uint32_t* __restrict__ band_cnt,
+                                                  float* __restrict__ res, int32_t* __restrict__ out_idx,
+                                                  float* __restrict__ out_val, uint32_t* __restrict__ counter,
+                                                  int32_t* __restrict__ items, int chain,
+                                                  uint32_t* __restrict__ fail_flag) {
+  constexpr int NT = 1024;
   __shared__ uint2 s_band[kBandCap];
   __shared__ uint32_t s_hist[kBins0];
-  __shared__ uint32_t s_wt[2 * kGroupWaves];
+  __shared__ uint32_t s_wt[32];
   __shared__ uint32_t s_sel[2];
   __shared__ uint32_t s_ti[2];
-  __shared__ uint32_t s_own[kGroupWaves];
-  const int tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
-  if ((int)blockIdx.x >= n_groups) {  // uniform over the workgroup
-    const int li = multi[blockIdx.x - n_groups];
-    const LState st = lstate[li];
-    if (st.mode != MODE_SPARSE) return;  // rejected by k_finish, dealt with there
-    if (!st.band_over) {
-      if (tid == 0) lstate[li].route = 1u;
-      return;
-    }
-    const LargeSeg ls = lsegs[li];
-    reject_layer<NT>(li, ls, segs[ls.seg], chain, lstate, fail_flag, counter, items, res, out_idx, out_val, s_hist,
-                     s_wt, s_sel);
+  const int tid = threadIdx.x;
+  const int li = multi[blockIdx.x];
+  const LState st = lstate[li];
+  if (st.mode != MODE_SPARSE) return;  // rejected by k_finish, dealt with there
+  const LargeSeg ls = lsegs[li];
+  if (st.band_over) {  // uniform over the workgroup
+    reject_layer<NT>(li, ls, segs[ls.seg], st.t_zero, chunk_cnt, slots, nslot, chain, lstate, fail_flag, counter,
+                     items, res, out_idx, out_val, s_hist, s_wt, s_sel);
     return;
   }
-  const GroupDesc gd = groups[blockIdx.x];
-  const LState st = lstate[gd.lseg];
-  if (st.mode != MODE_SPARSE || st.band_over) return;  // uniform over the workgroup
-  const LargeSeg ls = lsegs[gd.lseg];
-  const SegDesc sd = segs[ls.seg];
-  // the layer's band: the groups' entries one after the other (any order serves the selection)
+  // the layer's band: the groups' entries one after the other (any order serves the selection);
+  // thread e copies entry e, its group found by a search over the groups' offsets
   uint32_t m = 0;
+  uint32_t* s_off = s_hist;  // NT words
   for (int g0 = ls.group_begin; g0 < ls.group_end; g0 += NT) {  // uniform trip count
     const int g = g0 + tid;
     const uint32_t cnt = g < ls.group_end ? band_cnt[g] : 0u;
     uint32_t tot;
-    uint32_t at = m + block_incl_scan<NT>(cnt, s_wt, tot) - cnt;
-    for (uint32_t i = 0; i < cnt; ++i, ++at)
-      if (at < (uint32_t)kBandCap) s_band[at] = band[(int64_t)g * kGroupBand + i];
+    s_off[tid] = block_incl_scan<NT>(cnt, s_wt, tot) - cnt;
+    __syncthreads();
+    for (uint32_t e = tid; e < tot; e += NT) {
+      int lo = 0, hi = NT - 1;  // last group whose offset is <= e
+      while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (s_off[mid] <= e) lo = mid; else hi = mid - 1;
+      }
+      const uint32_t i = e - s_off[lo];
+      if (m + e < (uint32_t)kBandCap && i < (uint32_t)kGroupBand) s_band[m + e] = band[(int64_t)(g0 + lo) * kGroupBand + i];
+    }
     m += tot;
+    __syncthreads();
   }
   m = m < (uint32_t)kBandCap ? m : (uint32_t)kBandCap;  // equals n_band
   if (tid == 0) { s_ti[0] = 0xFFFFFFFFu; s_ti[1] = 0u; }
   __syncthreads();
   band_select<NT>(s_band, m, st.k_rem, st.tau + (st.bstar << st.shift), st.shift, s_hist, s_wt, s_sel, s_ti);
   const uint32_t T = s_ti[0], I = s_ti[1];
-  // kept candidates above b* in the wave chunks before this group, then inside it
-  const int q0 = gd.first * kGroupWaves;
-  uint32_t before = 0, unused = 0;
-  for (int p0 = tid; p0 < q0; p0 += 4 * NT) {
-    uint32_t v[4];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) v[u] = p0 + u * NT < q0 ? wgt[ls.wchunk_begin + p0 + u * NT] : 0u;
-    before += (v[0] + v[1]) + (v[2] + v[3]);
+  // output position of every wave chunk's first kept entry
+  const int nwc = (ls.chunk_end - ls.chunk_begin + kWaveTiles - 1) / kWaveTiles;
+  uint32_t* wl = wgt + ls.wchunk_begin;
+  uint32_t* s_blk = s_hist;  // NT words: kept band entries per wave chunk of the current block
+  uint32_t carry = 0;
+  for (int base = 0; base < nwc; base += NT) {  // uniform trip count
+    __syncthreads();
+    s_blk[tid] = 0u;
+    __syncthreads();
+    for (uint32_t i = tid; i < m; i += NT) {
+      const uint2 en = s_band[i];
+      const uint32_t key = en.y & 0x7FFFFFFFu;
+      const uint32_t q = en.x / (uint32_t)(kWaveTiles * kTile) - (uint32_t)base;  // wraps to a large value below base
+      if ((key > T || (key == T && en.x <= I)) && q < (uint32_t)NT) atomicAdd(&s_blk[q], 1u);
+    }
+    __syncthreads();
+    const uint32_t v = base + tid < nwc ? wl[base + tid] + s_blk[tid] : 0u;
+    uint32_t tot;
+    const uint32_t incl = block_incl_scan<NT>(v, s_wt, tot);
+    if (base + tid < nwc) wl[base + tid] = carry + incl - v;
+    carry += tot;
   }
-  block_sum2<NT>(before, unused, s_wt);
-  const int q = q0 + w;
+  if (tid == 0) {
+    lstate[li].T = T;
+    lstate[li].I = I;
+    lstate[li].route = 1u;
+  }
+}
+
+// Phase B of the layers finished by groups: one workgroup per group, one wave per wave chunk,
+// which emits its kept entries from the position that k_group_p computed.
+__global__ __launch_bounds__(kGroupWaves * 64) void k_group_b(const GroupDesc* __restrict__ groups,
+                                                            const SegDesc* __restrict__ segs,
+                                                            const LargeSeg* __restrict__ lsegs,
+                                                            const LState* __restrict__ lstate,
+                                                            const uint32_t* __restrict__ chunk_cnt,
+                                                            const uint2* __restrict__ slots, int nslot,
+                                                            const uint32_t* __restrict__ wgt,
+                                                            float* __restrict__ res, int32_t* __restrict__ out_idx,
+                                                            float* __restrict__ out_val) {
+  const GroupDesc gd = groups[blockIdx.x];
+  const LState st = lstate[gd.lseg];
+  if (st.mode != MODE_SPARSE || st.band_over) return;  // uniform over the workgroup
+  const LargeSeg ls = lsegs[gd.lseg];
+  const SegDesc sd = segs[ls.seg];
+  const int lane = lane_id(), w = threadIdx.x >> 6;
+  const int q = gd.first * kGroupWaves + w;
   const int c0 = ls.chunk_begin + q * kWaveTiles;
-  const bool active = c0 < ls.chunk_end;  // wave-uniform
-  if (lane == 0) s_own[w] = active ? wgt[ls.wchunk_begin + q] : 0u;
-  __syncthreads();
-  if (!active) return;
-  uint32_t pos0 = before + band_kept_before(s_band, m, T, I, (uint32_t)q * (uint32_t)(kWaveTiles * kTile), lane);
-  for (int p = 0; p < w; ++p) pos0 += s_own[p];
+  if (c0 >= ls.chunk_end) return;  // wave-uniform
+  const uint32_t pos0 = wgt[ls.wchunk_begin + q];
   const WaveChunk wc = wc_open(c0, ls.chunk_end, chunk_cnt, nslot, lane);
-  wc_phase_b(wc, slots, nslot, T, I, pos0, (uint32_t)sd.k, sd.d, out_idx + sd.out_offset, out_val + sd.out_offset,
-             res + sd.offset, lane);
+  wc_phase_b(wc, slots, nslot, st.T, st.I, st.t_zero, pos0, (uint32_t)sd.k, sd.d, out_idx + sd.out_offset,
+             out_val + sd.out_offset, res + sd.offset, lane);
 }
 
 // ------------------------------------------------------------------ multi-pass select
@@ -1825,7 +1947,7 @@ __global__ __launch_bounds__(256) void k_delta_finish(const SegDesc* __restrict_
 const char* kernel_name(int id) {
   static const char* names[K_NUM] = {
       "k_prep", "k_small<4,1>", "k_small<4,8>", "k_small<16,10>", "k_stream", "k_group_h", "k_finish", "k_group_a",
-      "k_group_b",
+      "k_group_p", "k_group_b",
       "k_hist", "k_count", "k_scan", "k_emit", "k_merge_bounds", "k_merge", "k_merge<apply>", "k_delta_tiles",
       "k_delta_finish", "sparsify_call"};
   return (id >= 0 && id < K_NUM) ? names[id] : nullptr;
@@ -1883,13 +2005,13 @@ hipError_t launch_large(const LargePlan& pl, const Scratch& sc, const SegDesc* s
   if (pl.n_hparts > 0) {
     ProfScope ps(prof, K_GROUP_H, s);
     hipLaunchKernelGGL(k_group_h, dim3(pl.n_hparts), dim3(1024), 0, s, pl.hparts, pl.lsegs, sc.lstate, sc.chunk_cnt,
-                       sc.slots, pl.slot, sc.bh_part, sc.top_part);
+                       sc.slots, pl.slot, sc.bh_part, sc.coarse_part, sc.part_info);
   }
   {
     ProfScope ps(prof, K_FINISH, s);
     hipLaunchKernelGGL(k_finish, dim3(pl.n_large), dim3(1024), 0, s, segs, pl.lsegs, sc.lstate, sc.chunk_cnt,
-                       sc.slots, pl.slot, sc.bh_part, sc.top_part, res, out_idx, out_val, counters, sc.items, ch,
-                       sc.fail_flag);
+                       sc.slots, pl.slot, sc.bh_part, sc.coarse_part, sc.part_info, res, out_idx, out_val, counters,
+                       sc.items, ch, sc.fail_flag);
   }
   if (pl.n_groups > 0) {
     {
@@ -1897,10 +2019,15 @@ hipError_t launch_large(const LargePlan& pl, const Scratch& sc, const SegDesc* s
       hipLaunchKernelGGL(k_group_a, dim3(pl.n_groups), dim3(kGroupWaves * 64), 0, s, pl.groups, pl.lsegs, sc.lstate,
                          sc.chunk_cnt, sc.slots, pl.slot, sc.wgt, sc.band, sc.band_cnt);
     }
+    {
+      ProfScope ps(prof, K_GROUP_P, s);
+      hipLaunchKernelGGL(k_group_p, dim3(pl.n_multi), dim3(1024), 0, s, pl.multi, segs, pl.lsegs, sc.lstate,
+                         sc.chunk_cnt, sc.slots, pl.slot, sc.wgt, sc.band, sc.band_cnt, res, out_idx, out_val, counters,
+                         sc.items, ch, sc.fail_flag);
+    }
     ProfScope ps(prof, K_GROUP_B, s);
-    hipLaunchKernelGGL(k_group_b, dim3(pl.n_groups + pl.n_multi), dim3(kGroupWaves * 64), 0, s, pl.n_groups,
-                       pl.groups, pl.multi, segs, pl.lsegs, sc.lstate, sc.chunk_cnt, sc.slots, pl.slot, sc.wgt,
-                       sc.band, sc.band_cnt, res, out_idx, out_val, counters, sc.items, ch, sc.fail_flag);
+    hipLaunchKernelGGL(k_group_b, dim3(pl.n_groups), dim3(kGroupWaves * 64), 0, s, pl.groups, segs, pl.lsegs,
+                       sc.lstate, sc.chunk_cnt, sc.slots, pl.slot, sc.wgt, res, out_idx, out_val);
   }
   if (chain) {
     const dim3 grid(kDenseGrid), b(256);
