@@ -254,9 +254,9 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
           max_per_tile = std::max(max_per_tile, per_tile);
           ls.chunk_begin = (int32_t)n_chunks;
           ls.chunk_end = (int32_t)(n_chunks + nt);
-          ls.wchunk_begin = (int32_t)n_wchunks;
+          ls.wchunk_begin = (int32_t)n_wchunks;   // a multiple of 4: k_group_p moves four entries at a time
           const int64_t nwc = (nt + kWaveTiles - 1) / kWaveTiles;
-          n_wchunks += nwc;
+          n_wchunks += (nwc + 3) / 4 * 4;
           ls.fused = nt <= kFusedTiles ? 1 : 0;
           if (!ls.fused) {
             ls.group_begin = (int32_t)groups.size();
