@@ -97,6 +97,23 @@ int64_t lags_table_out_offset(const lags_table *t, int32_t l);/* -1 if l is out 
 int lags_sparsify_layer(lags_ctx *ctx, const float *grad, float *residual, int64_t d, float lr,
                         int64_t k, int32_t *out_idx, float *out_val, void *hip_stream);
 
+/* lags_sparsify_layer for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same results
+ * (bit for bit) as lags_sparsify_layer, but no context: the plan and every scratch buffer live in
+ * one fixed device array of 5 MiB inside the library (one copy per GPU, held until the process
+ * ends), and the call performs no allocation of any kind: it enqueues kernels on `hip_stream`
+ * of HIP device `device` and returns.
+ *   d <= lags_noalloc_max_elements() (16,777,216), and tiles of 4096 elements x candidate slots
+ *   per tile <= 2^19: a layer that keeps up to 0.16 % of its entries uses 128 slots per tile
+ *   (16.7 M elements fit), one that keeps up to 0.4 % uses 256 (8.3 M elements fit), and so on.
+ *   Larger requests return LAGS_ECAPACITY and enqueue nothing.
+ * All calls on one GPU share the array: calls that overlap in time on one GPU (two streams, two
+ * threads) race and give undefined results; calls ordered on one stream are fine, and nothing
+ * has to be cleared between them. */
+int lags_sparsify_layer_noalloc(int device, const float *grad, float *residual, int64_t d, float lr,
+                                int64_t k, int32_t *out_idx, float *out_val, void *hip_stream);
+int64_t lags_noalloc_max_elements(void);
+
 /* Algorithm 1 lines 6-7 for every layer of a table in a few launches (the one-GPU
  * analogue of Section 5's buffering of many small tensors).
  *   grad_flat, residual_flat   device, float arrays covering every layer's [offset, offset+d)

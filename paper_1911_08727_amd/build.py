@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblags.so")
-SOURCES = ["lags_api.hip", "lags_kernels.hip"]
+SOURCES = ["lags_api.hip", "lags_kernels.hip", "lags_static.hip"]
 HEADERS = ["lags_internal.h", os.path.join("..", "..", "include", "lags.h")]
 
 HIPCC_FLAGS = [

@@ -118,6 +118,52 @@ struct lags_table {
   int32_t* d_seg_mtile0 = nullptr;
 };
 
+namespace lags {
+
+// Plan of the threshold guess for a large layer of d elements keeping k: how many sample
+// pieces and which ranks of the sample become the threshold and the estimate of the k-th
+// largest key.  Returns false if the layer is not worth sampling (k too large for the slots).
+bool plan_sample(int64_t d, int64_t k, LargeSeg* ls, double* per_tile) {
+  int64_t pieces, stride;
+  const int64_t piece_len = kSamplePiece * kSampleBatches;
+  if (d >= kSamplePieces * piece_len) {
+    pieces = kSamplePieces;
+    stride = d / kSamplePieces;
+  } else {
+    pieces = (d + piece_len - 1) / piece_len;
+    stride = piece_len;
+  }
+  const double m = (double)std::min<int64_t>(d, pieces * piece_len);
+  const double fk = (double)k * m / (double)d;
+  // the sample's rank-j key admits about j/m of the layer; j is fk plus five standard
+  // deviations of the sampled count plus a constant: fewer than k candidates (which costs the
+  // slow selection of that layer in that call) then has a probability below 1e-6
+  const double jd = std::ceil(fk + 5.0 * std::sqrt(fk) + 8.0);
+  if (jd > m) return false;
+  // expected candidates per tile must stay well inside the largest slot size
+  *per_tile = jd / m * (double)kTile;
+  if (*per_tile > (double)kSlotMax * 0.5) return false;
+  // The candidates between the threshold and the expected k-th largest key, (jd - fk) / fk * k of
+  // them, spread over at least 512 buckets; the bucket of the k-th largest key must hold no more
+  // than kBandCap entries.  Layers that keep so many entries that this leaves less than a factor
+  // 4 take the multi-pass route.
+  if ((jd - fk) / fk * (double)k / 512.0 > (double)kBandCap / 4.0) return false;
+  ls->sample_rank = (int32_t)jd;
+  // the sample's best estimate of the k-th largest key: it sets the width of the candidate buckets
+  ls->sample_rank_hi = (int32_t)std::max(1.0, std::floor(fk));
+  ls->sample_pieces = (int32_t)pieces;
+  ls->sample_stride = (int32_t)stride;
+  return true;
+}
+
+int plan_slots(double max_per_tile) {
+  int slot = kSlotMin;
+  while ((double)slot < 8.0 * max_per_tile && slot < kSlotMax) slot *= 2;
+  return slot;
+}
+
+}  // namespace lags
+
 namespace {
 
 constexpr size_t kMaxLayerPlans = 4096;  // cached one-layer plans of lags_sparsify_layer
@@ -169,42 +215,6 @@ void free_table_device(lags_table* t) {
   if (t->d_mtiles) (void)hipFree(t->d_mtiles);
   if (t->d_bchunks) (void)hipFree(t->d_bchunks);
   if (t->d_seg_mtile0) (void)hipFree(t->d_seg_mtile0);
-}
-
-// Plan of the threshold guess for a large layer of d elements keeping k: how many sample
-// pieces and which ranks of the sample become the threshold and the estimate of the k-th
-// largest key.  Returns false if the layer is not worth sampling (k too large for the slots).
-bool plan_sample(int64_t d, int64_t k, LargeSeg* ls, double* per_tile) {
-  int64_t pieces, stride;
-  const int64_t piece_len = kSamplePiece * kSampleBatches;
-  if (d >= kSamplePieces * piece_len) {
-    pieces = kSamplePieces;
-    stride = d / kSamplePieces;
-  } else {
-    pieces = (d + piece_len - 1) / piece_len;
-    stride = piece_len;
-  }
-  const double m = (double)std::min<int64_t>(d, pieces * piece_len);
-  const double fk = (double)k * m / (double)d;
-  // the sample's rank-j key admits about j/m of the layer; j is fk plus five standard
-  // deviations of the sampled count plus a constant: fewer than k candidates (which costs the
-  // slow selection of that layer in that call) then has a probability below 1e-6
-  const double jd = std::ceil(fk + 5.0 * std::sqrt(fk) + 8.0);
-  if (jd > m) return false;
-  // expected candidates per tile must stay well inside the largest slot size
-  *per_tile = jd / m * (double)kTile;
-  if (*per_tile > (double)kSlotMax * 0.5) return false;
-  // The candidates between the threshold and the expected k-th largest key, (jd - fk) / fk * k of
-  // them, spread over at least 512 buckets; the bucket of the k-th largest key must hold no more
-  // than kBandCap entries.  Layers that keep so many entries that this leaves less than a factor
-  // 4 take the multi-pass route.
-  if ((jd - fk) / fk * (double)k / 512.0 > (double)kBandCap / 4.0) return false;
-  ls->sample_rank = (int32_t)jd;
-  // the sample's best estimate of the k-th largest key: it sets the width of the candidate buckets
-  ls->sample_rank_hi = (int32_t)std::max(1.0, std::floor(fk));
-  ls->sample_pieces = (int32_t)pieces;
-  ls->sample_stride = (int32_t)stride;
-  return true;
 }
 
 // Build a table from explicit (offset, d, k) triples.
@@ -337,8 +347,7 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
   for (const LargeSeg& ls : t->lsegs) pl.n_sampled += ls.sampled;
   // candidates cluster (e.g. the few non-zero rows of an embedding gradient), so a tile may
   // hold several times the layer's average: the slots leave a factor 8 where they can
-  pl.slot = kSlotMin;
-  while ((double)pl.slot < 8.0 * max_per_tile && pl.slot < kSlotMax) pl.slot *= 2;
+  pl.slot = plan_slots(max_per_tile);
 
   int rc = upload(&t->d_segs, t->segs);
   for (int c = 0; c < 3 && rc == LAGS_OK; ++c) rc = upload(&t->d_small[c], small[c]);

@@ -205,6 +205,13 @@ struct ProfScope {
   }
 };
 
+// Planning shared by the table builder and the entry point that allocates nothing (lags_api.hip).
+// plan_sample: the sample plan of a large layer of d elements keeping k (fills the sample_*
+// fields of *ls); false if the layer is not worth sampling.  *per_tile = expected candidates
+// per tile.  plan_slots: candidate slots per tile for the largest such expectation of a table.
+bool plan_sample(int64_t d, int64_t k, LargeSeg* ls, double* per_tile);
+int plan_slots(double max_per_tile);
+
 // Launch wrappers (lags_kernels.hip).  All enqueue on `s` and return the launch status.
 hipError_t launch_fill_u32(uint32_t* p, int64_t n, uint32_t value, hipStream_t s);
 hipError_t launch_small(int cls, int nseg, const SegDesc* segs, const int32_t* list, const float* grad,

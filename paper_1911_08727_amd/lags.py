@@ -47,6 +47,9 @@ def lib():
         L.lags_table_out_offset.restype, L.lags_table_out_offset.argtypes = i64, [vp, i32]
         L.lags_sparsify_layer.restype = ctypes.c_int
         L.lags_sparsify_layer.argtypes = [vp, vp, vp, i64, f32, i64, vp, vp, vp]
+        L.lags_sparsify_layer_noalloc.restype = ctypes.c_int
+        L.lags_sparsify_layer_noalloc.argtypes = [ctypes.c_int, vp, vp, i64, f32, i64, vp, vp, vp]
+        L.lags_noalloc_max_elements.restype, L.lags_noalloc_max_elements.argtypes = i64, []
         L.lags_sparsify_model.restype = ctypes.c_int
         L.lags_sparsify_model.argtypes = [vp, vp, vp, vp, f32, vp, vp, vp]
         L.lags_merge_sparse.restype = ctypes.c_int
@@ -107,6 +110,16 @@ def _stream(stream):
 
 def lags_topk_count(d, rho):
     return int(lib().lags_topk_count(int(d), float(rho)))
+
+
+def lags_sparsify_layer_noalloc(device, grad, residual, lr, k, out_idx, out_val, stream=None):
+    _check(lib().lags_sparsify_layer_noalloc(int(device), _ptr(grad), _ptr(residual), grad.numel(), float(lr),
+                                             int(k), _ptr(out_idx), _ptr(out_val), _stream(stream)),
+           "lags_sparsify_layer_noalloc")
+
+
+def lags_noalloc_max_elements():
+    return int(lib().lags_noalloc_max_elements())
 
 
 def lags_allgather_seconds(alpha, beta, P, k):
