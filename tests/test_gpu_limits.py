@@ -4,7 +4,7 @@ and rejected arguments of the merge-type entry points."""
 import numpy as np
 import pytest
 
-from gpu_util import Gpu, assert_same, note, oracle_model_parallel
+from gpu_util import Gpu, assert_delta_close, assert_same, note, oracle_model_parallel
 from paper_1911_08727_amd import workloads
 
 pytestmark = pytest.mark.gpu
@@ -272,3 +272,167 @@ def test_two_contexts_on_two_streams(gpu, oracle):
     for t in tables:
         t.destroy()
     ctxs[1].destroy()
+
+
+def _one_table_case(rng, sizes):
+    layers, off = [], 0
+    for d, rho in sizes:
+        layers.append((off, d, rho))
+        off += d
+    return layers, off
+
+
+def test_graph_survives_scratch_growth(oracle):
+    """A graph recorded with a small table stays valid after a much larger table made the
+    context's scratch grow: outgrown buffers are kept until lags_destroy once a call has been
+    recorded (before that they are freed), so the replay still finds its scratch."""
+    import torch
+    from paper_1911_08727_amd import lags
+    g = Gpu()
+    try:
+        rng = np.random.default_rng(91)
+        small_layers, total = _one_table_case(rng, [(300_000, 0.002), (2000, 0.01), (2_300_000, 0.001)])
+        tiny = g.ctx.table([(0, 50_000, 0.01)])
+        before = g.ctx.lags_debug_scratch_info(5)          # the candidate slots
+        ts = g.ctx.table(small_layers)
+        after = g.ctx.lags_debug_scratch_info(5)
+        assert after[1] > before[1] and after[2] == 0, "growth before any capture frees the old buffer"
+        K = ts.total_k
+        g_host = rng.standard_normal(total).astype(np.float32)
+        r_host = (0.1 * rng.standard_normal(total)).astype(np.float32)
+        grad, res0 = g.to_dev(g_host), g.to_dev(r_host)
+        res = res0.clone()
+        idx = torch.empty(K, dtype=torch.int32, device=g.dev)
+        val = torch.empty(K, dtype=torch.float32, device=g.dev)
+        note("growth test: warm-up and capture with the small table")
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            g.ctx.lags_sparsify_model(ts, grad, res, 0.1, idx, val, side)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        res.copy_(res0)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            g.ctx.lags_sparsify_model(ts, grad, res, 0.1, idx, val, torch.cuda.current_stream())
+        note("growth test: a larger table moves the scratch")
+        big_layers, big_total = _one_table_case(rng, [(6_000_000, 0.004), (3_000_000, 0.001)])
+        tb = g.ctx.table(big_layers)
+        grown = g.ctx.lags_debug_scratch_info(5)
+        assert grown[0] != after[0] and grown[1] > after[1], "the slots were expected to move"
+        assert grown[2] >= 1, "the outgrown buffer must be kept for the recorded graph"
+        gb = torch.randn(big_total, device=g.dev)
+        rb = torch.zeros(big_total, device=g.dev)
+        ib = torch.empty(tb.total_k, dtype=torch.int32, device=g.dev)
+        vb = torch.empty(tb.total_k, dtype=torch.float32, device=g.dev)
+        g.ctx.lags_sparsify_model(tb, gb, rb, 0.1, ib, vb)
+        torch.cuda.synchronize()
+        res_cpu = r_host.copy()
+        for it in range(2):
+            note("growth test: replay %d of the graph recorded before the growth" % it)
+            graph.replay()
+            torch.cuda.synchronize()
+            wi, wv = oracle_model_parallel(oracle, small_layers, g_host, res_cpu, 0.1)
+            assert_same("idx replay %d" % it, idx.cpu().numpy(), wi)
+            assert_same("val replay %d" % it, val.cpu().numpy(), wv)
+            assert_same("res replay %d" % it, res.cpu().numpy(), res_cpu)
+        del graph
+        for t in (tiny, ts, tb):
+            t.destroy()
+    finally:
+        g.close()
+
+
+def test_scratch_poison_does_not_change_results(gpu, oracle):
+    """Scratch carries nothing between calls: with every scratch buffer of the context overwritten
+    by 0xFF bytes before the call, a table whose layers take all routes (one-workgroup, sampled
+    with one and with many workgroups, rejected guess, multi-pass) gives the oracle's bits, and so
+    do the merge, the apply and the delta metric."""
+    torch = gpu.torch
+    rng = np.random.default_rng(92)
+    sizes = [(700, 0.01), (250_000, 0.002), (2_600_000, 0.003), (60_000, 0.6), (180_000, 0.001), (30_000, 0.004)]
+    layers, total = _one_table_case(rng, sizes)
+    P = 3
+    table = gpu.ctx.table(layers)
+    K = table.total_k
+    g_host = [rng.standard_normal(total).astype(np.float32) for _ in range(P)]
+    for gh in g_host:
+        o, d, _ = layers[4]
+        gh[o:o + d] = 0.0                                   # an all-zero layer: the guess is rejected
+    r_host = [(0.2 * rng.standard_normal(total)).astype(np.float32) for _ in range(P)]
+    for rh in r_host:
+        o, d, _ = layers[4]
+        rh[o:o + d] = 0.0
+    for mode in (0, 1, 2, 0):
+        gpu.ctx.lags_debug_fallback_chain(mode)
+        res_cpu = [r.copy() for r in r_host]
+        all_i, all_v = np.empty(P * K, np.int32), np.empty(P * K, np.float32)
+        res_dev = torch.empty(P * total, dtype=torch.float32, device=gpu.dev)
+        for p in range(P):
+            note("poison test: fallback mode %d, worker %d" % (mode, p))
+            gpu.ctx.lags_debug_poison_scratch()
+            wi, wv = oracle_model_parallel(oracle, layers, g_host[p], res_cpu[p], 0.5)
+            gi, gv, gr = gpu.sparsify_model(layers, g_host[p], r_host[p], 0.5, table=table)
+            routes = gpu.ctx.lags_last_routes(table)
+            assert routes == [0, 1, 1, 3, 2, 0], routes
+            assert_same("idx", gi, wi)
+            assert_same("val", gv, wv)
+            assert_same("res", gr, res_cpu[p])
+            all_i[p * K:(p + 1) * K], all_v[p * K:(p + 1) * K] = gi, gv
+            res_dev[p * total:(p + 1) * total] = gpu.to_dev(gr)
+        note("poison test: merge, apply, delta after poisoning")
+        want_u = np.full(total, 5.0, np.float32)
+        oracle.merge_sparse(layers, all_i, all_v, P, K, want_u)
+        gpu.ctx.lags_debug_poison_scratch()
+        assert_same("update", gpu.merge(layers, all_i, all_v, P, K, total, table=table, fill=5.0), want_u)
+        param = rng.standard_normal(total).astype(np.float32)
+        want_v = param.copy()
+        oracle.apply_sparse(layers, all_i, all_v, P, K, want_v)
+        gpu.ctx.lags_debug_poison_scratch()
+        assert_same("param", gpu.apply(layers, all_i, all_v, P, K, param, table=table), want_v)
+        gpu.ctx.lags_debug_poison_scratch()
+        got_d = gpu.delta(layers, res_dev.cpu().numpy(), total, all_i, all_v, P, K, table=table)
+        want_d = oracle.delta_monitor(layers, res_dev.cpu().numpy(), total, all_i, all_v, P, K)
+        assert_delta_close("delta", got_d, want_d)
+    gpu.ctx.lags_debug_fallback_chain(0)
+    table.destroy()
+
+
+def test_rejected_guesses_on_layers_finished_by_groups(gpu, oracle):
+    """Layers of more than 512 tiles (finished by groups of workgroups) whose guess is rejected,
+    served by the one-workgroup selection (mode 2), by the multi-pass kernels (mode 1) and in the
+    default mode: an all-zero layer (rejected when the candidates are counted), a layer with 300
+    entries tied at the k-th largest magnitude inside one group (that group's share of the band
+    overflows: rejected between the group phases), the same ties spread over the layer (accepted)."""
+    rng = np.random.default_rng(93)
+    d, rho = 2_400_000, 0.001
+    k = 2400
+    base = rng.standard_normal(d).astype(np.float32)
+    mags = np.sort(np.abs(base))[::-1]
+    v = np.float32(mags[k - 150])                     # 300 ties at v straddle rank k
+    tied_one_group = base.copy()
+    tied_one_group[786_432 + np.arange(300) * 800] = v   # inside one group of 64 tiles, a few per tile
+    tied_spread = base.copy()
+    tied_spread[np.arange(300) * 7919 + 5] = -v
+    cases = [("zeros", np.zeros(d, np.float32), 2), ("ties in one group", tied_one_group, 2),
+             ("ties spread", tied_spread, 1)]
+    for mode in (2, 1, 0):
+        gpu.ctx.lags_debug_fallback_chain(mode)
+        for name, g, want_route in cases:
+            note("group rejection: mode %d, %s" % (mode, name))
+            routes = _check(gpu, oracle, [(0, d, rho)], g, np.zeros(d, np.float32), 1.0)
+            assert routes == [want_route], (name, mode, routes)
+    gpu.ctx.lags_debug_fallback_chain(0)
+
+
+def _check(gpu, oracle, layers, g, r0, lr):
+    table = gpu.ctx.table(layers)
+    want_r = r0.copy()
+    wi, wv = oracle_model_parallel(oracle, layers, g, want_r, lr)
+    gi, gv, gr = gpu.sparsify_model(layers, g, r0, lr, table=table)
+    routes = gpu.ctx.lags_last_routes(table)
+    table.destroy()
+    assert_same("idx", gi, wi)
+    assert_same("val", gv, wv)
+    assert_same("res", gr, want_r)
+    return routes
