@@ -242,7 +242,7 @@ def main():
     wl = workloads.make(args.workload, rho_override=rho)
     P = args.workers or wl.P
     # every job of this run lives in these two pools (sized for the largest one)
-    other = [] if args.no_configs else [workloads.make(n) for n in workloads.NAMES]
+    other = [] if args.no_configs else [workloads.make(n) for n in workloads.NAMES + workloads.EXTRA_NAMES]
     pool_elems = max([P * wl.total_d] + [w.P * w.total_d for w in other])
     grad_pool = torch.empty(N_ITERS * pool_elems, dtype=torch.float32, device=dev)
     res_pool = torch.empty(pool_elems, dtype=torch.float32, device=dev)
@@ -411,7 +411,7 @@ def main():
         configs["%s, one call per worker" % wl.name] = job.summary(sp, mg, st)
         configs["%s, one lags_sparsify_layer call per layer (worker 0)" % wl.name] = layer_sweep(torch, lags, job)
         job.close()
-        # the five benchmark configurations at their own densities, batched calls
+        # the five benchmark configurations (and the Inception-v4-shaped table) at their own densities, batched calls
         for w in other:
             j = Job(torch, lags, workloads, ctx, w, w.P, grad_pool, res_pool, dev)
             for _ in range(2):

@@ -113,7 +113,7 @@ struct lags_table {
   GroupDesc* d_groups = nullptr;
   GroupDesc* d_hparts = nullptr;
   int32_t* d_multi = nullptr;
-  TileDesc* d_mtiles = nullptr;
+  MTile* d_mtiles = nullptr;
   BChunk* d_bchunks = nullptr;
   int32_t* d_seg_mtile0 = nullptr;
 };
@@ -226,7 +226,8 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
   t->ctx = ctx;
   t->n = n;
   std::vector<int32_t> small[3], multi;
-  std::vector<TileDesc> tiles, mtiles;
+  std::vector<TileDesc> tiles;
+  std::vector<MTile> mtiles;
   std::vector<GroupDesc> groups, hparts;
   std::vector<BChunk> bchunks;
   std::vector<int32_t> seg_mtile0;
@@ -316,13 +317,14 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
         bchunks.push_back(bc);
       }
       for (int64_t i = 0; i < nmt; ++i) {
-        TileDesc td;
-        td.start = off[l] + i * kMergeTile;
-        td.n = (int32_t)std::min<int64_t>(kMergeTile, d[l] - i * kMergeTile);
-        td.seg = l;
-        td.local0 = (int32_t)(i * kMergeTile);
-        td.ctile = -1;
-        mtiles.push_back(td);
+        MTile mt;
+        mt.start = off[l] + i * kMergeTile;
+        mt.out_offset = s.out_offset;
+        mt.n = (int32_t)std::min<int64_t>(kMergeTile, d[l] - i * kMergeTile);
+        mt.seg = l;
+        mt.local0 = (int32_t)(i * kMergeTile);
+        mt.k = (int32_t)k[l];
+        mtiles.push_back(mt);
       }
     }
     t->total_k = outpos;

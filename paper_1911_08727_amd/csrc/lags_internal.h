@@ -70,7 +70,8 @@ constexpr int kStreamV = 4;
 
 constexpr int kMergeTile = 8192;
 constexpr int kMaxWorkers = 1024;
-constexpr int kBoundChunk = 16384;       // index-list entries per workgroup of k_merge_bounds
+constexpr int kBoundChunk = 2048;        // index-list entries per workgroup of k_merge_bounds
+
 
 struct BChunk {         // a run of one layer's index list, for k_merge_bounds
   int32_t seg;          // layer
@@ -92,6 +93,15 @@ struct TileDesc {       // one tile of a layer (dense tiles, merge tiles)
   int32_t seg;          // large path: index among the large layers; merge: layer index
   int32_t local0;       // layer-local index of the first element
   int32_t ctile;        // dense tiles of sampled layers: index among those tiles ("chunk"); else -1
+};
+
+struct MTile {          // one tile of the dense update (merge-type kernels), with what they need of its layer
+  int64_t start;        // absolute element offset
+  int64_t out_offset;   // position of the layer's pairs in a worker's idx/val
+  int32_t n;            // elements in the tile
+  int32_t seg;          // layer index
+  int32_t local0;       // layer-local index of the first element
+  int32_t k;            // pairs per worker of the layer
 };
 
 struct LargeSeg {       // static plan of one large layer
@@ -225,7 +235,7 @@ enum { MERGE_UPDATE = 0, MERGE_APPLY = 1, MERGE_DELTA = 2 };
 
 struct MergePlan {      // device pointers + counts of the merge-type launches
   int n_layers = 0, n_mtiles = 0, n_bchunks = 0, nb = 0;
-  const TileDesc* mtiles = nullptr;
+  const MTile* mtiles = nullptr;
   const BChunk* bchunks = nullptr;
   const int32_t* seg_mtile0 = nullptr;  // n_layers + 1: first merge tile of every layer
 };

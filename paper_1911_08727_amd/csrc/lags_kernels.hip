@@ -1815,21 +1815,31 @@ __global__ __launch_bounds__(256) void k_merge_bounds(const BChunk* __restrict__
                                                       const SegDesc* __restrict__ segs,
                                                       const int32_t* __restrict__ idx, int64_t stride_k,
                                                       int nb, int32_t* __restrict__ bounds) {
+  constexpr int U = kBoundChunk / 256;
   const BChunk bc = chunks[blockIdx.x];
   const int p = blockIdx.y;
   const SegDesc sd = segs[bc.seg];
   const int32_t* li = idx + (int64_t)p * stride_k + sd.out_offset;
   int32_t* b = bounds + (int64_t)p * nb + bc.slot0;
   const int jend = sd.k < bc.j0 + kBoundChunk ? sd.k : bc.j0 + kBoundChunk;
-  for (int j = bc.j0 + (int)threadIdx.x; j < jend; j += 256) {
+  // all loads of the thread first (an entry and its predecessor), then the stores
+  int cur[U], prev[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int j = bc.j0 + u * 256 + (int)threadIdx.x;
+    cur[u] = j < jend ? li[j] : 0;
+    prev[u] = (j < jend && j > 0) ? li[j - 1] : 0;
+  }
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int j = bc.j0 + u * 256 + (int)threadIdx.x;
+    if (j >= jend) continue;
     // indices are clamped into the layer so that bad input cannot write outside the row
-    int i1 = li[j];
-    i1 = i1 < 0 ? 0 : (i1 >= sd.d ? sd.d - 1 : i1);
+    const int i1 = cur[u] < 0 ? 0 : (cur[u] >= sd.d ? sd.d - 1 : cur[u]);
     const int t = i1 / kMergeTile;
     int tp = -1;
     if (j > 0) {
-      int i0 = li[j - 1];
-      i0 = i0 < 0 ? 0 : (i0 >= sd.d ? sd.d - 1 : i0);
+      const int i0 = prev[u] < 0 ? 0 : (prev[u] >= sd.d ? sd.d - 1 : prev[u]);
       tp = i0 / kMergeTile;
     }
     for (int q = tp + 1; q <= t; ++q) b[q] = j;
@@ -1927,8 +1937,7 @@ __device__ __forceinline__ uint32_t merge_accumulate(T* s_acc, uint32_t* s_start
 // place, v -= update, touching only the elements whose sum is not zero (v - 0 == v bit for bit,
 // and a sum that starts from +0.0f is never -0.0f).  No atomics, fixed summation order.
 template <bool APPLY>
-__global__ __launch_bounds__(256) void k_merge(const TileDesc* __restrict__ mtiles,
-                                               const SegDesc* __restrict__ segs,
+__global__ __launch_bounds__(256) void k_merge(const MTile* __restrict__ mtiles,
                                                const int32_t* __restrict__ idx,
                                                const float* __restrict__ val, int P,
                                                int64_t stride_k, int nb,
@@ -1939,8 +1948,11 @@ __global__ __launch_bounds__(256) void k_merge(const TileDesc* __restrict__ mtil
   __shared__ int32_t s_lo[256];
   __shared__ uint32_t s_wt[4];
   __shared__ uint32_t s_claim[APPLY ? kMergeTile / 32 : 1];
-  const TileDesc td = mtiles[blockIdx.x];
-  const SegDesc sd = segs[td.seg];
+  const MTile mt = mtiles[blockIdx.x];  // one read: the tile and what the kernel needs of its layer
+  TileDesc td;
+  td.start = mt.start; td.n = mt.n; td.seg = mt.seg; td.local0 = mt.local0; td.ctile = -1;
+  SegDesc sd;
+  sd.offset = 0; sd.out_offset = mt.out_offset; sd.d = 0; sd.k = mt.k;
   const int tid = threadIdx.x;
   const int slot = (int)blockIdx.x + td.seg;  // every earlier layer owns one extra (end) slot
   if (APPLY) s_claim[tid] = 0u;  // kMergeTile / 32 = 256 words; the accumulation's barriers order this
@@ -2015,8 +2027,7 @@ __global__ __launch_bounds__(256) void k_merge(const TileDesc* __restrict__ mtil
 // Section 6.2, per tile: with s = sum_p residual_p (the residuals after sparsification) and
 // x = s + sum_p selected_p, the tile's parts of ||s||^2 and ||x||^2 in double.  Sums over
 // workers run in worker order; the tile's two partial sums go to partials[2*tile], [2*tile+1].
-__global__ __launch_bounds__(256) void k_delta_tiles(const TileDesc* __restrict__ mtiles,
-                                                     const SegDesc* __restrict__ segs,
+__global__ __launch_bounds__(256) void k_delta_tiles(const MTile* __restrict__ mtiles,
                                                      const float* __restrict__ res, int64_t res_stride,
                                                      const int32_t* __restrict__ idx,
                                                      const float* __restrict__ val, int P,
@@ -2028,8 +2039,11 @@ __global__ __launch_bounds__(256) void k_delta_tiles(const TileDesc* __restrict_
   __shared__ int32_t s_lo[256];
   __shared__ uint32_t s_wt[4];
   __shared__ double s_red[8];
-  const TileDesc td = mtiles[blockIdx.x];
-  const SegDesc sd = segs[td.seg];
+  const MTile mt = mtiles[blockIdx.x];
+  TileDesc td;
+  td.start = mt.start; td.n = mt.n; td.seg = mt.seg; td.local0 = mt.local0; td.ctile = -1;
+  SegDesc sd;
+  sd.offset = 0; sd.out_offset = mt.out_offset; sd.d = 0; sd.k = mt.k;
   const int tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
   const int slot = (int)blockIdx.x + td.seg;
   (void)merge_accumulate<double>(s_acc, s_start, s_lo, s_wt, td, sd, slot, idx, val, P, stride_k, nb, bounds);
@@ -2235,16 +2249,16 @@ hipError_t launch_merge(int mode, const MergePlan& mp, int32_t* bounds, const Se
   }
   if (mode == MERGE_UPDATE) {
     ProfScope ps(prof, K_MERGE, s);
-    hipLaunchKernelGGL((k_merge<false>), dim3(mp.n_mtiles), dim3(256), 0, s, mp.mtiles, segs, idx, val, P, stride_k,
+    hipLaunchKernelGGL((k_merge<false>), dim3(mp.n_mtiles), dim3(256), 0, s, mp.mtiles, idx, val, P, stride_k,
                        mp.nb, bounds, out);
   } else if (mode == MERGE_APPLY) {
     ProfScope ps(prof, K_MERGE_APPLY, s);
-    hipLaunchKernelGGL((k_merge<true>), dim3(mp.n_mtiles), dim3(256), 0, s, mp.mtiles, segs, idx, val, P, stride_k,
+    hipLaunchKernelGGL((k_merge<true>), dim3(mp.n_mtiles), dim3(256), 0, s, mp.mtiles, idx, val, P, stride_k,
                        mp.nb, bounds, out);
   } else {
     {
       ProfScope ps(prof, K_DELTA_TILES, s);
-      hipLaunchKernelGGL(k_delta_tiles, dim3(mp.n_mtiles), dim3(256), 0, s, mp.mtiles, segs, res, res_stride, idx,
+      hipLaunchKernelGGL(k_delta_tiles, dim3(mp.n_mtiles), dim3(256), 0, s, mp.mtiles, res, res_stride, idx,
                          val, P, stride_k, mp.nb, bounds, partials);
     }
     ProfScope ps(prof, K_DELTA_FINISH, s);

@@ -189,3 +189,9 @@ def test_lstm_full():
     """Configuration 5: 7 tensors, 66,022,000 elements, embedding gradient non-zero on 2000 of
     10000 rows, rho = 0.005, P = 16, 10 iterations."""
     _run_full("lstm")
+
+
+def test_inception4_full():
+    """The Inception-v4-shaped table (third model of the paper's evaluation): 449 tensors,
+    42,679,816 elements, rho = 0.001, P = 16, 3 iterations."""
+    assert _run_full("inception4", iters=3) == 0
