@@ -1809,8 +1809,8 @@ __global__ __launch_bounds__(256) void k_emit(const TileDesc* __restrict__ tiles
 // Algorithm 1 lines 8-9.  Two kernels.
 //
 // k_merge_bounds: for every worker and layer, where each 8192-element tile of the dense
-// update starts in the worker's sorted index list: bounds[p][slot0 + t] = first list position
-// whose index lies in tile t or later; bounds[p][slot0 + ntiles] = k.  One pass over the lists.
+// update starts in the worker's sorted index list: bounds[slot0 + t][p] = first list position
+// whose index lies in tile t or later; bounds[slot0 + ntiles][p] = k.  One pass over the lists.
 __global__ __launch_bounds__(256) void k_merge_bounds(const BChunk* __restrict__ chunks,
                                                       const SegDesc* __restrict__ segs,
                                                       const int32_t* __restrict__ idx, int64_t stride_k,
@@ -1820,7 +1820,10 @@ __global__ __launch_bounds__(256) void k_merge_bounds(const BChunk* __restrict__
   const int p = blockIdx.y;
   const SegDesc sd = segs[bc.seg];
   const int32_t* li = idx + (int64_t)p * stride_k + sd.out_offset;
-  int32_t* b = bounds + (int64_t)p * nb + bc.slot0;
+  // slot-major layout: the P workers' entries of one tile slot are adjacent, so a merge
+  // workgroup reads all its workers' bounds from one or two cache lines
+  const int P = gridDim.y;
+  int32_t* b = bounds + (int64_t)bc.slot0 * P + p;
   const int jend = sd.k < bc.j0 + kBoundChunk ? sd.k : bc.j0 + kBoundChunk;
   // all loads of the thread first (an entry and its predecessor), then the stores
   int cur[U], prev[U];
@@ -1842,9 +1845,9 @@ __global__ __launch_bounds__(256) void k_merge_bounds(const BChunk* __restrict__
       const int i0 = prev[u] < 0 ? 0 : (prev[u] >= sd.d ? sd.d - 1 : prev[u]);
       tp = i0 / kMergeTile;
     }
-    for (int q = tp + 1; q <= t; ++q) b[q] = j;
+    for (int q = tp + 1; q <= t; ++q) b[(int64_t)q * P] = j;
     if (j == sd.k - 1)
-      for (int q = t + 1; q <= bc.ntiles; ++q) b[q] = sd.k;
+      for (int q = t + 1; q <= bc.ntiles; ++q) b[(int64_t)q * P] = sd.k;
   }
 }
 
@@ -1868,8 +1871,8 @@ __device__ __forceinline__ uint32_t merge_accumulate(T* s_acc, uint32_t* s_start
     int lo = 0;
     uint32_t cnt = 0;
     if (tid < np) {
-      const int32_t* b = bounds + (int64_t)(p0 + tid) * nb + slot;
-      int hi = b[1];
+      const int32_t* b = bounds + (int64_t)slot * P + (p0 + tid);  // slot-major: adjacent workers, adjacent words
+      int hi = b[P];
       lo = b[0];
       lo = lo < 0 ? 0 : (lo > sd.k ? sd.k : lo);
       hi = hi < 0 ? 0 : (hi > sd.k ? sd.k : hi);
