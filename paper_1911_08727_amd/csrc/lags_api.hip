@@ -103,11 +103,11 @@ struct lags_table {
   int64_t span_lo = 0, span_hi = 0;            // [min offset, max offset + d)
   std::vector<SegDesc> segs;                   // host copy
   std::vector<LargeSeg> lsegs;                 // host copy
-  int n_small[3] = {0, 0, 0};
+  int n_small[kSmallClasses] = {0, 0};
   MergePlan mplan;
   LargePlan plan;                              // device pointers below, owned by the table
   SegDesc* d_segs = nullptr;
-  int32_t* d_small[3] = {nullptr, nullptr, nullptr};
+  int32_t* d_small[kSmallClasses] = {nullptr, nullptr};
   LargeSeg* d_lsegs = nullptr;
   TileDesc* d_tiles = nullptr;
   GroupDesc* d_groups = nullptr;
@@ -125,10 +125,11 @@ namespace lags {
 // largest key.  Returns false if the layer is not worth sampling (k too large for the slots).
 bool plan_sample(int64_t d, int64_t k, LargeSeg* ls, double* per_tile) {
   int64_t pieces, stride;
-  const int64_t piece_len = kSamplePiece * kSampleBatches;
-  if (d >= kSamplePieces * piece_len) {
-    pieces = kSamplePieces;
-    stride = d / kSamplePieces;
+  const int64_t piece_len = kSamplePiece;
+  const int64_t max_pieces = d <= kSampleSmallElems ? kSamplePiecesSmall : kSamplePieces;
+  if (d >= max_pieces * piece_len) {
+    pieces = max_pieces;
+    stride = d / max_pieces;
   } else {
     pieces = (d + piece_len - 1) / piece_len;
     stride = piece_len;
@@ -145,9 +146,10 @@ bool plan_sample(int64_t d, int64_t k, LargeSeg* ls, double* per_tile) {
   if (*per_tile > (double)kSlotMax * 0.5) return false;
   // The candidates between the threshold and the expected k-th largest key, (jd - fk) / fk * k of
   // them, spread over at least 512 buckets; the bucket of the k-th largest key must hold no more
-  // than kBandCap entries.  Layers that keep so many entries that this leaves less than a factor
-  // 4 take the multi-pass route.
-  if ((jd - fk) / fk * (double)k / 512.0 > (double)kBandCap / 4.0) return false;
+  // than kBandCap entries (kBandCapSmall where a small workgroup finishes the layer).  Layers
+  // that keep so many entries that this leaves less than a factor 4 take the multi-pass route.
+  const int64_t band_cap = (d + kTile - 1) / kTile <= kFinishSmallTiles ? kBandCapSmall : kBandCap;
+  if ((jd - fk) / fk * (double)k / 512.0 > (double)band_cap / 4.0) return false;
   ls->sample_rank = (int32_t)jd;
   // the sample's best estimate of the k-th largest key: it sets the width of the candidate buckets
   ls->sample_rank_hi = (int32_t)std::max(1.0, std::floor(fk));
@@ -205,7 +207,7 @@ std::vector<DevBuf*> all_bufs(lags_ctx* ctx) {
 
 void free_table_device(lags_table* t) {
   if (t->d_segs) (void)hipFree(t->d_segs);
-  for (int c = 0; c < 3; ++c)
+  for (int c = 0; c < kSmallClasses; ++c)
     if (t->d_small[c]) (void)hipFree(t->d_small[c]);
   if (t->d_lsegs) (void)hipFree(t->d_lsegs);
   if (t->d_tiles) (void)hipFree(t->d_tiles);
@@ -225,7 +227,7 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
   if (!t) return LAGS_ENOMEM;
   t->ctx = ctx;
   t->n = n;
-  std::vector<int32_t> small[3], multi;
+  std::vector<int32_t> small[kSmallClasses], multi;
   std::vector<TileDesc> tiles;
   std::vector<MTile> mtiles;
   std::vector<GroupDesc> groups, hparts;
@@ -235,6 +237,12 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
   int64_t n_wchunks = 0;       // runs of kWaveTiles such tiles
   double max_per_tile = 0.0;   // largest expected candidate count per tile over the sampled layers
   constexpr int64_t kMaxTiles = 1 << 28;
+  int fuse_limit = kFusedTiles;
+  for (int32_t l = 0; l < n; ++l) {
+    LargeSeg probe = {};
+    double unused = 0.0;
+    if (d[l] > (int64_t)kFusedTiles * kTile && plan_sample(d[l], k[l], &probe, &unused)) fuse_limit = kFusedTilesShared;
+  }
   try {
     t->segs.resize(n);
     int64_t outpos = 0;
@@ -251,7 +259,6 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
       t->span_hi = std::max(t->span_hi, off[l] + d[l]);
       if (d[l] <= kSmall0) small[0].push_back(l);
       else if (d[l] <= kSmall1) small[1].push_back(l);
-      else if (d[l] <= kSmall2) small[2].push_back(l);
       else {
         LargeSeg ls = {};
         const int32_t li = (int32_t)t->lsegs.size();
@@ -268,7 +275,7 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
           ls.wchunk_begin = (int32_t)n_wchunks;   // a multiple of 4: k_group_p moves four entries at a time
           const int64_t nwc = (nt + kWaveTiles - 1) / kWaveTiles;
           n_wchunks += (nwc + 3) / 4 * 4;
-          ls.fused = nt <= kFusedTiles ? 1 : 0;
+          ls.fused = nt <= fuse_limit ? 1 : 0;
           if (!ls.fused) {
             ls.group_begin = (int32_t)groups.size();
             const int64_t ng = (nwc + kGroupWaves - 1) / kGroupWaves;
@@ -333,7 +340,7 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
     delete t;
     return LAGS_ENOMEM;
   }
-  for (int c = 0; c < 3; ++c) t->n_small[c] = (int)small[c].size();
+  for (int c = 0; c < kSmallClasses; ++c) t->n_small[c] = (int)small[c].size();
   t->mplan.n_layers = n;
   t->mplan.n_mtiles = (int)mtiles.size();
   t->mplan.n_bchunks = (int)bchunks.size();
@@ -346,13 +353,16 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
   pl.n_groups = (int)groups.size();
   pl.n_multi = (int)multi.size();
   pl.n_hparts = (int)hparts.size();
-  for (const LargeSeg& ls : t->lsegs) pl.n_sampled += ls.sampled;
+  for (const LargeSeg& ls : t->lsegs) {
+    pl.n_sampled += ls.sampled;
+    pl.n_finish_small += finish_small(ls) ? 1 : 0;
+  }
   // candidates cluster (e.g. the few non-zero rows of an embedding gradient), so a tile may
   // hold several times the layer's average: the slots leave a factor 8 where they can
   pl.slot = plan_slots(max_per_tile);
 
   int rc = upload(&t->d_segs, t->segs);
-  for (int c = 0; c < 3 && rc == LAGS_OK; ++c) rc = upload(&t->d_small[c], small[c]);
+  for (int c = 0; c < kSmallClasses && rc == LAGS_OK; ++c) rc = upload(&t->d_small[c], small[c]);
   if (rc == LAGS_OK) rc = upload(&t->d_lsegs, t->lsegs);
   if (rc == LAGS_OK) rc = upload(&t->d_tiles, tiles);
   if (rc == LAGS_OK) rc = upload(&t->d_groups, groups);
@@ -417,16 +427,20 @@ int run_sparsify(lags_ctx* ctx, const lags_table* t, const float* grad, float* r
     if (ctx->chain_mode == 2) chain = t->plan.has_dense;
   }
   ProfScope whole(&ctx->prof, K_SPARSIFY_CALL, s);
-  // small and large layers touch disjoint parts of every buffer, so the small layers' kernels
-  // can run on the side stream while the large layers' pipeline occupies the caller's stream
-  const bool have_small = t->n_small[0] + t->n_small[1] + t->n_small[2] > 0;
-  bool fork = ctx->aux && have_small && t->plan.n_large > 0;
+  // Small and large layers touch disjoint parts of every buffer, so the small layers' kernels
+  // run on the side stream while the large layers' pipeline occupies the caller's stream.  The
+  // side stream starts after the threshold guesses: those are short and everything else waits
+  // for them, and the small layers' workgroups would otherwise take their wave slots.
+  int rc = LAGS_OK;
+  if (launch_large_prep(t->plan, ctx->scratch(), t->d_segs, grad, res, lr, chain, s, &ctx->prof) != hipSuccess)
+    rc = LAGS_EHIP;
+  const bool have_small = t->n_small[0] + t->n_small[1] > 0;
+  bool fork = rc == LAGS_OK && ctx->aux && have_small && t->plan.n_large > 0;
   if (fork && (hipEventRecord(ctx->ev_fork, s) != hipSuccess ||
                hipStreamWaitEvent(ctx->aux, ctx->ev_fork, 0) != hipSuccess))
     fork = false;
   hipStream_t ss = fork ? ctx->aux : s;
-  int rc = LAGS_OK;
-  for (int c = 0; c < 3 && rc == LAGS_OK; ++c) {
+  for (int c = 0; c < kSmallClasses && rc == LAGS_OK; ++c) {
     if (launch_small(c, t->n_small[c], t->d_segs, t->d_small[c], grad, res, lr, out_idx, out_val, ss, &ctx->prof) != hipSuccess)
       rc = LAGS_EHIP;
   }
@@ -812,18 +826,16 @@ int lags_profile_reset(lags_ctx* ctx) {
 
 int64_t lags_profile_kernel_elements(const lags_table* t, int kernel_id) {
   if (!t) return -1;
-  int64_t small[3] = {0, 0, 0}, large = 0, all = 0;
+  int64_t small[kSmallClasses] = {0, 0}, large = 0, all = 0;
   for (const SegDesc& sd : t->segs) {
     all += sd.d;
     if (sd.d <= kSmall0) small[0] += sd.d;
     else if (sd.d <= kSmall1) small[1] += sd.d;
-    else if (sd.d <= kSmall2) small[2] += sd.d;
     else large += sd.d;
   }
   switch (kernel_id) {
     case K_SMALL0: return small[0];
     case K_SMALL1: return small[1];
-    case K_SMALL2: return small[2];
     case K_STREAM: return large;
     case K_MERGE: case K_MERGE_APPLY: case K_DELTA_TILES: case K_SPARSIFY_CALL: return all;
     default: return 0;

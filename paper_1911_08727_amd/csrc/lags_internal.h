@@ -24,7 +24,10 @@ constexpr int kHistStride = kBins0 + 2 * kBins12;       // level 2 at [3072, 409
 // Size classes of the one-workgroup-per-layer ("small") path: NW waves x V rounds.
 constexpr int kSmall0 = 4 * 1 * 256;     // <= 1024  : 4 waves, 1 round
 constexpr int kSmall1 = 4 * 8 * 256;     // <= 8192  : 4 waves, 8 rounds
-constexpr int kSmall2 = 16 * 10 * 256;   // <= 40960 : 16 waves, 10 rounds
+// Anything larger goes through the sampled pipeline: a single workgroup that held a layer of
+// tens of thousands of elements in registers ran for 40 us and took a whole CU's registers from
+// the streaming pass meanwhile.
+constexpr int kSmallClasses = 2;
 
 // Threshold guess from a sample (large layers): 256 pieces of 64 consecutive elements.
 // The sample only has to rank the top k roughly: a smaller sample admits more candidates
@@ -33,7 +36,12 @@ constexpr int kSmall2 = 16 * 10 * 256;   // <= 40960 : 16 waves, 10 rounds
 constexpr int kSamplePiece = 64;
 constexpr int kSamplePieces = 256;
 constexpr int kSampleMax = kSamplePiece * kSamplePieces;   // 16384 sampled elements
-constexpr int kSampleBatches = 1;        // 16 sample keys per thread (2 or 4: pieces of 128 or 256 elements)
+// Layers of up to kSampleSmallElems elements are guessed from a quarter of that.  The sample is
+// read from scattered 256-byte pieces before the streaming pass can start; a shorter one admits
+// more candidates (its threshold is less sharp), and below about two million elements the bytes
+// saved on the sample outweigh the bytes of the extra candidates.
+constexpr int kSamplePiecesSmall = 64;
+constexpr int64_t kSampleSmallElems = 1 << 20;
 constexpr int kSlotMin = 128;            // candidate slots per tile of a sampled layer: the table uses the
 constexpr int kSlotMax = 2048;           // smallest power of two >= 8x the expected count of any layer
 constexpr int kDenseGrid = 1024;         // workgroups of the multi-pass kernels (grid-stride)
@@ -44,6 +52,7 @@ constexpr int kDenseGrid = 1024;         // workgroups of the multi-pass kernels
 // must number at most kBandCap.
 constexpr int kFineBins = 4096;
 constexpr int kBandCap = 4096;
+constexpr int kBandCapSmall = 1024;        // ... of the layers that k_finish takes with workgroups of 256 threads
 constexpr int kWaveTiles = 8;            // a wave flattens the slots of 8 consecutive tiles ("wave chunk")
 constexpr int kGroupWaves = 8;           // a workgroup of the multi-workgroup finish: 8 wave chunks
 constexpr int kGroupTiles = kWaveTiles * kGroupWaves;
@@ -51,6 +60,10 @@ constexpr int kGroupBand = 64;           // band entries one group may contribut
 constexpr int kCountTiles = 256;         // tiles per workgroup of the partial bucket counts
 constexpr int kCoarseBins = 64;          // those counts are also summed over runs of 64 buckets
 constexpr int kFusedTiles = 512;         // sampled layers of up to this many tiles are finished by one workgroup
+// ... unless the table also holds a sampled layer above kFusedTiles: the launches of the finish
+// by groups are then paid anyway, and a single workgroup walking hundreds of tiles would be the
+// longest thing in k_finish.  Such tables keep only layers of up to this many tiles in one workgroup.
+constexpr int kFusedTilesShared = 128;
 // The streaming pass is HBM-bound and runs best when each CU holds only three of its
 // workgroups (12 waves, about 96 KB of loads in flight per CU): measured on MI355X, 26.6 GB in
 // 4.05 ms, against 4.36 ms at the eight workgroups that registers and static LDS would allow
@@ -123,6 +136,14 @@ struct LargeSeg {       // static plan of one large layer
   int32_t sample_stride;
 };
 
+// Sampled layers of at most this many tiles that one workgroup finishes are finished by one of
+// 256 threads instead of 1024 (four wave chunks per wave at most): a CU holds six of those
+// side by side, against two of the large ones, and a table of many layers is done sooner.
+constexpr int kFinishSmallTiles = 128;
+__host__ __device__ inline bool finish_small(const LargeSeg& ls) {
+  return ls.sampled && ls.fused && ls.chunk_end - ls.chunk_begin <= kFinishSmallTiles;
+}
+
 struct GroupDesc {      // one workgroup of the multi-workgroup finish (a group, or a part of the bucket counts)
   int32_t lseg;         // large-layer index
   int32_t first;        // index of the group (part) inside its layer
@@ -155,6 +176,7 @@ struct DState {         // per call, per large layer on the multi-pass route: th
 
 struct LargePlan {      // everything launch_large needs (device pointers + counts)
   int n_large = 0, n_tiles = 0, n_sampled = 0, n_chunks = 0, n_wchunks = 0, n_groups = 0, n_multi = 0, n_hparts = 0;
+  int n_finish_small = 0;               // large layers that k_finish takes with workgroups of 256 threads
   int slot = kSlotMin;                  // candidate slots per sampled tile
   bool has_dense = false;               // some large layer is not sampled: the multi-pass kernels always run
   const LargeSeg* lsegs = nullptr;
@@ -185,7 +207,7 @@ struct Scratch {        // context-owned device memory, contents meaningless bet
 
 // Kernel ids for the optional event timing.
 enum KernelId {
-  K_PREP = 0, K_SMALL0, K_SMALL1, K_SMALL2, K_STREAM, K_GROUP_H, K_FINISH, K_GROUP_A, K_GROUP_P, K_GROUP_B,
+  K_PREP = 0, K_SMALL0, K_SMALL1, K_STREAM, K_GROUP_H, K_FINISH, K_GROUP_A, K_GROUP_P, K_GROUP_B,
   K_HIST, K_COUNT, K_SCAN, K_EMIT,
   K_MERGE_BOUNDS, K_MERGE, K_MERGE_APPLY, K_DELTA_TILES, K_DELTA_FINISH,
   K_SPARSIFY_CALL,      // not a kernel: the whole sparsify call on the caller's stream, fork to join
@@ -226,8 +248,12 @@ int plan_slots(double max_per_tile);
 hipError_t launch_fill_u32(uint32_t* p, int64_t n, uint32_t value, hipStream_t s);
 hipError_t launch_small(int cls, int nseg, const SegDesc* segs, const int32_t* list, const float* grad,
                         float* res, float lr, int32_t* out_idx, float* out_val, hipStream_t s, Prof* prof);
-// chain: also enqueue the multi-pass kernels (rejected guesses then use them instead of the
-// one-workgroup rescue); always true for plans with has_dense.
+// The large layers' pipeline in two parts, same arguments to both: the threshold guesses
+// (k_prep), then everything that follows them.  chain: also enqueue the multi-pass kernels
+// (rejected guesses then use them instead of the one-workgroup rescue); always true for plans
+// with has_dense.
+hipError_t launch_large_prep(const LargePlan& pl, const Scratch& sc, const SegDesc* segs, const float* grad,
+                             const float* res, float lr, bool chain, hipStream_t s, Prof* prof);
 hipError_t launch_large(const LargePlan& pl, const Scratch& sc, const SegDesc* segs, const float* grad,
                         float* res, float lr, int32_t* out_idx, float* out_val, bool chain, hipStream_t s,
                         Prof* prof);

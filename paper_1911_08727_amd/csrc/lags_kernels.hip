@@ -514,81 +514,122 @@ __device__ __forceinline__ bool find_rank(const uint32_t* hist, int nb, uint32_t
   return rank_in_bin != 0u;
 }
 
-// Keys of one batch of the sample: 4 wave rounds (16 keys per thread) of the 256 pieces of
-// 64 * BATCHES consecutive elements each (a wave round covers 64 / (16 * BATCHES) pieces).
-template <int BATCHES>
-__device__ __forceinline__ void sample_batch(int batch, const LargeSeg& ls, int li, const SegDesc& sd,
-                                             const float* __restrict__ g, const float* __restrict__ r, bool vec,
-                                             float lr, int lane, int w, uint32_t (&a)[4][4]) {
-  constexpr int V = 4 * BATCHES;
-  constexpr int PL = kSamplePiece * BATCHES;   // piece length
-  constexpr int LP = PL / 4;                   // lanes per piece
+// Workgroup of the threshold guess: 4 waves; a thread holds V * 4 sample keys, V = 16 for the
+// full sample of kSamplePieces pieces and V = 4 for the short sample of kSamplePiecesSmall.
+// Small workgroups, so that many layers are guessed at once: a CU holds four of them side by
+// side, and what bounds the kernel is then the scattered reads of the samples themselves.
+constexpr int kPrepThreads = 256;
+constexpr int kPrepV = kSampleMax / (kPrepThreads * 4);
+constexpr int kPrepVSmall = kSamplePiecesSmall * kSamplePiece / (kPrepThreads * 4);
+static_assert(kPrepV * kPrepThreads * 4 == kSampleMax, "every sample slot has a thread");
+static_assert(kPrepVSmall * kPrepThreads * 4 == kSamplePiecesSmall * kSamplePiece && kPrepVSmall % 2 == 0,
+              "every slot of the short sample has a thread");
+
+// Keys of the sample: 16 V pieces of kSamplePiece consecutive elements; a wave round of 64
+// lanes x 4 elements covers 4 pieces, wave w owns the pieces [4 V w, 4 V w + 4 V).
+// The loads of half the rounds are issued before any of them is used, from addresses that are
+// valid whether or not the sample slot exists (a slot that does not, or that would cross the
+// layer's end, reads the layer's first elements and is then set to key 0): no branch separates
+// the loads, so their latencies overlap; two halves, so that the registers of the loads in
+// flight and of the keys leave room for four waves per SIMD.  Large layers hold more than 4
+// elements.
+template <int V>
+__device__ __forceinline__ void sample_keys(const LargeSeg& ls, int li, const SegDesc& sd,
+                                            const float* __restrict__ g, const float* __restrict__ r, bool vec,
+                                            float lr, int lane, int w, uint32_t (&a)[V][4]) {
+  constexpr int H = V / 2;
+  constexpr int LP = kSamplePiece / 4;         // lanes per piece
   constexpr int PR = 64 / LP;                  // pieces per wave round
-  static_assert(BATCHES == 1 || BATCHES == 2 || BATCHES == 4, "a piece is a whole number of lanes of one wave round");
 #pragma unroll
-  for (int jj = 0; jj < 4; ++jj) {
-    const int j = batch * 4 + jj;
-    const int piece = w * (V * PR) + j * PR + (lane / LP);
-    a[jj][0] = a[jj][1] = a[jj][2] = a[jj][3] = 0u;
-    if (piece < ls.sample_pieces) {
+  for (int half = 0; half < 2; ++half) {
+    int e[H];
+    bool have[H];
+#pragma unroll
+    for (int jj = 0; jj < H; ++jj) {
+      const int j = half * H + jj;
+      const int piece = w * (V * PR) + j * PR + (lane / LP);
       int start = piece * ls.sample_stride;
-      if (ls.sample_stride > PL)
-        start += (int)(mix32((uint32_t)piece * 0x9E3779B9u + (uint32_t)li) % (uint32_t)(ls.sample_stride - PL + 1));
+      if (ls.sample_stride > kSamplePiece)
+        start += (int)(mix32((uint32_t)piece * 0x9E3779B9u + (uint32_t)li) %
+                       (uint32_t)(ls.sample_stride - kSamplePiece + 1));
       start &= ~3;
-      const int e = start + (lane % LP) * 4;
-      if (vec && e + 3 < sd.d) {
-        const float4 gv = *reinterpret_cast<const float4*>(g + e);
-        const float4 rv = *reinterpret_cast<const float4*>(r + e);
-        a[jj][0] = acc_bits(gv.x, rv.x, lr);
-        a[jj][1] = acc_bits(gv.y, rv.y, lr);
-        a[jj][2] = acc_bits(gv.z, rv.z, lr);
-        a[jj][3] = acc_bits(gv.w, rv.w, lr);
-      } else {
+      e[jj] = start + (lane % LP) * 4;
+      have[jj] = piece < ls.sample_pieces && e[jj] >= 0 && e[jj] + 3 < sd.d;
+      if (!have[jj]) e[jj] = 0;
+    }
+    if (vec) {
+      float4 gv[H], rv[H];
 #pragma unroll
-        for (int c = 0; c < 4; ++c)
-          if (e + c < sd.d) a[jj][c] = acc_bits(g[e + c], r[e + c], lr);
+      for (int jj = 0; jj < H; ++jj) {
+        gv[jj] = *reinterpret_cast<const float4*>(g + e[jj]);
+        rv[jj] = *reinterpret_cast<const float4*>(r + e[jj]);
+      }
+#pragma unroll
+      for (int jj = 0; jj < H; ++jj) {
+        const int j = half * H + jj;
+        a[j][0] = acc_bits(gv[jj].x, rv[jj].x, lr);
+        a[j][1] = acc_bits(gv[jj].y, rv[jj].y, lr);
+        a[j][2] = acc_bits(gv[jj].z, rv[jj].z, lr);
+        a[j][3] = acc_bits(gv[jj].w, rv[jj].w, lr);
+      }
+    } else {
+#pragma unroll
+      for (int jj = 0; jj < H; ++jj) {
+        const int j = half * H + jj;
+        float gs[4], rs[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          gs[c] = g[e[jj] + c];
+          rs[c] = r[e[jj] + c];
+        }
+#pragma unroll
+        for (int c = 0; c < 4; ++c) a[j][c] = acc_bits(gs[c], rs[c], lr);
       }
     }
 #pragma unroll
-    for (int c = 0; c < 4; ++c) a[jj][c] &= 0x7FFFFFFFu;
+    for (int jj = 0; jj < H; ++jj) {
+      const int j = half * H + jj;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) a[j][c] = have[jj] ? (a[j][c] & 0x7FFFFFFFu) : 0u;
+    }
   }
 }
 
-// Threshold guess for one large layer: form acc on up to 256 pieces of 64 * BATCHES
-// consecutive elements spread over the layer (with a hashed offset inside each stride);
-// tau is a key that at least `sample_rank` sample keys reach (and few more), t_est one
-// that at least `sample_rank_hi` reach: the sample's estimate of the layer's k-th largest key.
-// Any value would be correct (the guess is verified by counting); a good one keeps the
-// candidates few.  Missing sample slots count as key 0.
+// Threshold guess for one large layer: form acc on up to 16 V pieces of 64 consecutive elements
+// spread over the layer (with a hashed offset inside each stride); tau is a key that at least
+// `sample_rank` sample keys reach (and few more), t_est one that at least `sample_rank_hi`
+// reach: the sample's estimate of the layer's k-th largest key.  Any value would be correct
+// (the guess is verified by counting); a good one keeps the candidates few.  Missing sample
+// slots count as key 0.
 //
-// The two keys come from two histograms over 1024 linear bins, which spread the top of the
+// The two keys come from two histograms over NT linear bins, which spread the top of the
 // sample evenly (bins of exponent bits would put it all into a handful of LDS words):
 // first the per-thread maxima over the 2^26 key steps below the largest sample key M, which
 // gives a floor F that at least `sample_rank` thread maxima reach; then the sample entries at
 // or above F over [F, M].  The lower edge of the bin that holds a rank is returned; where that
 // bin holds clearly more entries than the rank needs, the rank is resolved inside it.  Ranks
-// above 1024 (very dense layers) and samples whose top spans more than 2^26 key steps take an
-// exact radix select over the first batch instead, with the ranks scaled to it.
-template <int BATCHES>
+// above NT (dense layers) and samples whose top spans more than 2^26 key steps take an exact
+// radix select instead.
+template <int V>
 __device__ __forceinline__ void sample_layer(const LargeSeg& ls, int li, const SegDesc& sd,
                                              const float* __restrict__ grad, const float* __restrict__ res,
                                              float lr, uint32_t* s_hist, uint32_t* s_wt, uint32_t* s_sel,
                                              uint32_t* s_out, uint32_t& tau, uint32_t& t_est) {
-  constexpr int NT = 1024;  // 16 waves
+  constexpr int NT = kPrepThreads;
+  constexpr int LOG = 8;                      // log2(NT): key bits resolved per histogram
+  static_assert((1 << LOG) == NT, "one bin per thread");
   const int tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
   const float* g = grad + sd.offset;
   const float* r = res + sd.offset;
   const bool vec = aligned16(g, r);
   const uint32_t rank = (uint32_t)ls.sample_rank, rank_hi = (uint32_t)ls.sample_rank_hi;
-  uint32_t a[4][4];
+  uint32_t a[V][4];
+  sample_keys<V>(ls, li, sd, g, r, vec, lr, lane, w, a);
   uint32_t mx = 0u;
-  for (int batch = BATCHES - 1; batch >= 0; --batch) {  // batch 0 last: it stays in the registers
-    sample_batch<BATCHES>(batch, ls, li, sd, g, r, vec, lr, lane, w, a);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+  for (int j = 0; j < V; ++j) {
 #pragma unroll
-      for (int c = 0; c < 4; ++c) mx = a[j][c] > mx ? a[j][c] : mx;
-    }
+    for (int c = 0; c < 4; ++c) mx = a[j][c] > mx ? a[j][c] : mx;
   }
   const uint32_t M = block_max<NT>(mx, s_wt);
   bool fast = rank <= (uint32_t)NT;  // uniform over the workgroup
@@ -597,26 +638,23 @@ __device__ __forceinline__ void sample_layer(const LargeSeg& ls, int li, const S
     const uint32_t L1 = M > 0x03FFFFFFu ? M - 0x03FFFFFFu : 0u;
     s_hist[tid] = 0u;
     __syncthreads();
-    if (mx >= L1) atomicAdd(&s_hist[(mx - L1) >> 16], 1u);
+    if (mx >= L1) atomicAdd(&s_hist[(mx - L1) >> (26 - LOG)], 1u);
     __syncthreads();
     find_two_ranks<NT>(s_hist[tid], rank, rank, s_wt, s_out);
     fast = s_out[1] != 0u;
-    F = L1 + (s_out[0] << 16);
+    F = L1 + (s_out[0] << (26 - LOG));
   }
   if (fast) {
     int s2 = 0;
-    while (((M - F) >> s2) >= 1024u) ++s2;
+    while (((M - F) >> s2) >= (uint32_t)NT) ++s2;
     __syncthreads();
     s_hist[tid] = 0u;
     __syncthreads();
-    for (int batch = 0; batch < BATCHES; ++batch) {
-      if (batch > 0) sample_batch<BATCHES>(batch, ls, li, sd, g, r, vec, lr, lane, w, a);
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < V; ++j) {
 #pragma unroll
-        for (int c = 0; c < 4; ++c)
-          if (a[j][c] >= F) atomicAdd(&s_hist[(a[j][c] - F) >> s2], 1u);
-      }
+      for (int c = 0; c < 4; ++c)
+        if (a[j][c] >= F) atomicAdd(&s_hist[(a[j][c] - F) >> s2], 1u);
     }
     __syncthreads();
     // at least `rank` entries reach F, so both ranks are found
@@ -625,23 +663,20 @@ __device__ __forceinline__ void sample_layer(const LargeSeg& ls, int li, const S
     t_est = F + (s_out[3] << s2);
     // If the bin of tau holds clearly more sample entries than the rank needs (keys that lie
     // closer together than the bins are wide: quantised or narrow data), its lower edge would
-    // admit them all: resolve the rank inside the bin, 1024 finer bins at a time.
+    // admit them all: resolve the rank inside the bin, NT finer bins at a time.
     uint32_t rib = s_out[1];
     uint32_t extra = rib != 0u ? s_out[2] - rib : 0u;
     while (s2 > 0 && extra > 4u) {  // uniform over the workgroup
       const uint32_t lo = tau, width = 1u << s2;
-      s2 = s2 > 10 ? s2 - 10 : 0;
+      s2 = s2 > LOG ? s2 - LOG : 0;
       __syncthreads();
       s_hist[tid] = 0u;
       __syncthreads();
-      for (int batch = 0; batch < BATCHES; ++batch) {
-        if (BATCHES > 1) sample_batch<BATCHES>(batch, ls, li, sd, g, r, vec, lr, lane, w, a);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+      for (int j = 0; j < V; ++j) {
 #pragma unroll
-          for (int c = 0; c < 4; ++c)
-            if (a[j][c] >= lo && a[j][c] - lo < width) atomicAdd(&s_hist[(a[j][c] - lo) >> s2], 1u);
-        }
+        for (int c = 0; c < 4; ++c)
+          if (a[j][c] >= lo && a[j][c] - lo < width) atomicAdd(&s_hist[(a[j][c] - lo) >> s2], 1u);
       }
       __syncthreads();
       find_two_ranks<NT>(s_hist[tid], rib, rib, s_wt, s_out);
@@ -651,11 +686,9 @@ __device__ __forceinline__ void sample_layer(const LargeSeg& ls, int li, const S
       extra = s_out[2] - rib;
     }
   } else {
-    if (BATCHES > 1) sample_batch<BATCHES>(0, ls, li, sd, g, r, vec, lr, lane, w, a);
     uint32_t rtake;
-    const uint32_t r1 = rank / BATCHES > 0 ? rank / BATCHES : 1u, r2 = rank_hi / BATCHES > 0 ? rank_hi / BATCHES : 1u;
-    block_radix_select<NT, 4>(a, 4 * 256, lane, r1, s_hist, s_wt, s_sel, tau, rtake);
-    block_radix_select<NT, 4>(a, 4 * 256, lane, r2, s_hist, s_wt, s_sel, t_est, rtake);
+    block_radix_select<NT, V>(a, V * 256, lane, rank, s_hist, s_wt, s_sel, tau, rtake);
+    block_radix_select<NT, V>(a, V * 256, lane, rank_hi, s_hist, s_wt, s_sel, t_est, rtake);
   }
   if (t_est < tau) t_est = tau;
 }
@@ -663,12 +696,12 @@ __device__ __forceinline__ void sample_layer(const LargeSeg& ls, int li, const S
 // One workgroup per large layer: resets the layer's per-call state (and, when the multi-pass
 // kernels will run, their histograms and work counter) and guesses the threshold of a sampled
 // layer.
-__global__ __launch_bounds__(1024) void k_prep(const SegDesc* __restrict__ segs,
-                                               const LargeSeg* __restrict__ lsegs,
-                                               const float* __restrict__ grad,
-                                               const float* __restrict__ res, float lr,
-                                               LState* __restrict__ lstate, uint32_t* __restrict__ ghist,
-                                               uint32_t* __restrict__ counters, int chain) {
+__global__ __launch_bounds__(kPrepThreads) __attribute__((amdgpu_waves_per_eu(4, 8))) void k_prep(const SegDesc* __restrict__ segs,
+                                                       const LargeSeg* __restrict__ lsegs,
+                                                       const float* __restrict__ grad,
+                                                       const float* __restrict__ res, float lr,
+                                                       LState* __restrict__ lstate, uint32_t* __restrict__ ghist,
+                                                       uint32_t* __restrict__ counters, int chain) {
   __shared__ uint32_t s_hist[kBins0];
   __shared__ uint32_t s_wt[16];
   __shared__ uint32_t s_sel[2];
@@ -676,8 +709,9 @@ __global__ __launch_bounds__(1024) void k_prep(const SegDesc* __restrict__ segs,
   const int li = blockIdx.x, tid = threadIdx.x;
   const LargeSeg ls = lsegs[li];
   if (chain) {
-    static_assert(kHistStride == 4096, "one 16-byte store per thread clears a layer's histograms");
-    reinterpret_cast<uint4*>(ghist + (int64_t)li * kHistStride)[tid] = make_uint4(0u, 0u, 0u, 0u);
+    static_assert(kHistStride % (4 * kPrepThreads) == 0, "16-byte stores clear a layer's histograms");
+    for (int i = tid; i < kHistStride / 4; i += kPrepThreads)
+      reinterpret_cast<uint4*>(ghist + (int64_t)li * kHistStride)[i] = make_uint4(0u, 0u, 0u, 0u);
     if (li == 0 && tid < 16) counters[tid] = 0u;
   }
   if (!ls.sampled) {  // uniform over the workgroup
@@ -691,7 +725,10 @@ __global__ __launch_bounds__(1024) void k_prep(const SegDesc* __restrict__ segs,
   }
   const SegDesc sd = segs[ls.seg];
   uint32_t tau, t_est;
-  sample_layer<kSampleBatches>(ls, li, sd, grad, res, lr, s_hist, s_wt, s_sel, s_out, tau, t_est);
+  if (ls.sample_pieces <= kSamplePiecesSmall)  // uniform over the workgroup
+    sample_layer<kPrepVSmall>(ls, li, sd, grad, res, lr, s_hist, s_wt, s_sel, s_out, tau, t_est);
+  else
+    sample_layer<kPrepV>(ls, li, sd, grad, res, lr, s_hist, s_wt, s_sel, s_out, tau, t_est);
   if (tid == 0) {
     // bucket width: the distance from tau to the estimate of the k-th largest key spans 512 to
     // 1023 buckets, so the 4096 buckets reach four to eight times that distance above tau
@@ -947,40 +984,119 @@ __device__ __forceinline__ void wc_for_each(const WaveChunk& wc, const uint2* __
   }
 }
 
-// Bucket counts of one wave chunk into the LDS histogram s_fine; returns the number of
-// candidates at or above tau_top (wave-uniform).
+// Up to kWaveChunks wave chunks of one wave, walked together.  The first 128 entries of every
+// chunk are loaded once, all loads in flight together, and stay in registers for the three
+// passes (a chunk of a layer that keeps 0.1 % holds one to two hundred entries); what a chunk
+// holds beyond that is read again in every pass.  Chunks without entries cost nothing.
+constexpr int kWaveChunks = 4;
+struct WaveEntries {
+  uint2 e0[kWaveChunks], e1[kWaveChunks];  // entries lane and 64 + lane of each chunk
+};
+
+__device__ __forceinline__ void wc_load4(const WaveChunk (&wc)[kWaveChunks], const uint2* __restrict__ slots,
+                                         int nslot, int lane, WaveEntries& we) {
+#pragma unroll
+  for (int i = 0; i < kWaveChunks; ++i) {
+    const uint32_t n = wc[i].total;  // wave-uniform
+    we.e0[i] = make_uint2(0u, 0u);
+    we.e1[i] = make_uint2(0u, 0u);
+    if (n > 0u) we.e0[i] = wc_entry(wc[i], (uint32_t)lane < n ? (uint32_t)lane : n - 1u, slots, nslot);
+    if (n > 64u) we.e1[i] = wc_entry(wc[i], 64u + lane < n ? 64u + lane : n - 1u, slots, nslot);
+  }
+}
+
+// Calls f(i, entry, live) chunk by chunk in index order, all lanes taking part.
+template <typename F>
+__device__ __forceinline__ void wc_for_each4(const WaveChunk (&wc)[kWaveChunks], const WaveEntries& we,
+                                             const uint2* __restrict__ slots, int nslot, int lane, F f) {
+#pragma unroll
+  for (int i = 0; i < kWaveChunks; ++i) {
+    const uint32_t n = wc[i].total;
+    if (n > 0u) f(i, we.e0[i], (uint32_t)lane < n);
+    if (n > 64u) f(i, we.e1[i], 64u + lane < n);
+    for (uint32_t base = 128; base < n; base += 128) {  // wave-uniform trip count
+      const bool two = base + 64 < n;
+      const bool live0 = base + lane < n, live1 = base + 64 + lane < n;
+      const uint2 x0 = wc_entry(wc[i], live0 ? base + lane : n - 1u, slots, nslot);
+      uint2 x1 = make_uint2(0u, 0u);
+      if (two) x1 = wc_entry(wc[i], live1 ? base + 64 + lane : n - 1u, slots, nslot);
+      f(i, x0, live0);
+      if (two) f(i, x1, live1);
+    }
+  }
+}
+
+// What the three passes over the candidates do with one entry (all lanes of the wave call them
+// together; live = the lane holds an entry).
+// Counting pass: the entry's bucket in the LDS histogram s_fine; n_top counts the candidates
+// at or above tau_top (wave-uniform).
+__device__ __forceinline__ void entry_count(uint2 en, bool live, uint32_t tau, uint32_t tau_top, uint32_t shift,
+                                            uint32_t* s_fine, uint32_t& n_top) {
+  const uint32_t key = en.y & 0x7FFFFFFFu;
+  const bool top = key >= tau_top;
+  n_top += (uint32_t)__popcll(__ballot(live && top));
+  if (live && !top) {
+    // slots hold keys in [tau, tau_top) here; the clamps only keep a corrupted entry inside the array
+    const uint32_t b = key >= tau ? (key - tau) >> shift : 0u;
+    atomicAdd(&s_fine[b < (uint32_t)kFineBins ? b : (uint32_t)kFineBins - 1u], 1u);
+  }
+}
+
+// Phase A: n_gt counts the candidates above bucket b* (wave-uniform); the entries of bucket b*
+// are appended to band[0 .. cap) through the LDS counter *s_nband.
+__device__ __forceinline__ void entry_phase_a(uint2 en, bool live, uint32_t tau, uint32_t tau_top, uint32_t shift,
+                                              uint32_t bstar, uint2* band, uint32_t cap, uint32_t* s_nband,
+                                              uint32_t& n_gt) {
+  const uint32_t key = en.y & 0x7FFFFFFFu;
+  const bool top = key >= tau_top;
+  const uint32_t b = (key - tau) >> shift;
+  n_gt += (uint32_t)__popcll(__ballot(live && (top || b > bstar)));
+  if (live && !top && b == bstar) {
+    const uint32_t pos = atomicAdd(s_nband, 1u);
+    if (pos < cap) band[pos] = en;
+  }
+}
+
+// Phase B: the kept entries go to out[pos0 ...] in index order (pos0 advances).  The streaming
+// pass wrote zero for the entries with key >= t_zero and acc for the others, so the residual is
+// written only where that differs from the outcome: zero for kept entries below t_zero, acc
+// for dropped entries at or above it.  Positions are checked against k so that no state can
+// write out of bounds.
+__device__ __forceinline__ void entry_phase_b(uint2 en, bool live, uint32_t T, uint32_t I, uint32_t t_zero,
+                                              uint32_t& pos0, uint32_t k, int32_t d, int32_t* __restrict__ oi,
+                                              float* __restrict__ ov, float* __restrict__ rl) {
+  const uint32_t key = en.y & 0x7FFFFFFFu;
+  const bool keep = live && (key > T || (key == T && en.x <= I));
+  const bool zeroed = key >= t_zero;  // what the streaming pass assumed
+  const uint64_t mk = __ballot(keep);
+  const uint32_t pos = pos0 + mbcnt64(mk);
+  if (live && en.x < (uint32_t)d) {
+    if (keep && pos < k) {
+      oi[pos] = (int32_t)en.x;
+      ov[pos] = __uint_as_float(en.y);
+    }
+    if (keep && !zeroed) rl[en.x] = 0.0f;
+    if (!keep && zeroed) rl[en.x] = __uint_as_float(en.y);
+  }
+  pos0 += (uint32_t)__popcll(mk);
+}
+
+// The passes over one wave chunk.
 __device__ __forceinline__ uint32_t wc_count(const WaveChunk& wc, const uint2* __restrict__ slots, int nslot,
                                              uint32_t tau, uint32_t tau_top, uint32_t shift, uint32_t* s_fine,
                                              int lane) {
   uint32_t n_top = 0;
-  wc_for_each(wc, slots, nslot, lane, [&](uint2 en, bool live) {
-    const uint32_t key = en.y & 0x7FFFFFFFu;
-    const bool top = key >= tau_top;
-    n_top += (uint32_t)__popcll(__ballot(live && top));
-    if (live && !top) {
-      // slots hold keys in [tau, tau_top) here; the clamps only keep a corrupted entry inside the array
-      const uint32_t b = key >= tau ? (key - tau) >> shift : 0u;
-      atomicAdd(&s_fine[b < (uint32_t)kFineBins ? b : (uint32_t)kFineBins - 1u], 1u);
-    }
-  });
+  wc_for_each(wc, slots, nslot, lane,
+              [&](uint2 en, bool live) { entry_count(en, live, tau, tau_top, shift, s_fine, n_top); });
   return n_top;
 }
 
-// Phase A over one wave chunk: returns the number of candidates above bucket b* (wave-uniform)
-// and appends the entries of bucket b* to band[0 .. cap) through the LDS counter *s_nband.
 __device__ __forceinline__ uint32_t wc_phase_a(const WaveChunk& wc, const uint2* __restrict__ slots, int nslot,
                                                uint32_t tau, uint32_t tau_top, uint32_t shift, uint32_t bstar,
                                                uint2* band, uint32_t cap, uint32_t* s_nband, int lane) {
   uint32_t n_gt = 0;
   wc_for_each(wc, slots, nslot, lane, [&](uint2 en, bool live) {
-    const uint32_t key = en.y & 0x7FFFFFFFu;
-    const bool top = key >= tau_top;
-    const uint32_t b = (key - tau) >> shift;
-    n_gt += (uint32_t)__popcll(__ballot(live && (top || b > bstar)));
-    if (live && !top && b == bstar) {
-      const uint32_t pos = atomicAdd(s_nband, 1u);
-      if (pos < cap) band[pos] = en;
-    }
+    entry_phase_a(en, live, tau, tau_top, shift, bstar, band, cap, s_nband, n_gt);
   });
   return n_gt;
 }
@@ -1064,31 +1180,12 @@ __device__ __forceinline__ uint32_t band_kept_before(const uint2* s_band, uint32
   return wave_sum(c);
 }
 
-// Phase B over one wave chunk: the kept entries go to out[pos0 ...] in index order.  The
-// streaming pass wrote zero for the entries with key >= t_zero and acc for the others, so the
-// residual is written only where that differs from the outcome: zero for kept entries below
-// t_zero, acc for dropped entries at or above it.  Positions are checked against k so that no
-// state can write out of bounds.
 __device__ __forceinline__ void wc_phase_b(const WaveChunk& wc, const uint2* __restrict__ slots, int nslot,
                                            uint32_t T, uint32_t I, uint32_t t_zero, uint32_t pos0, uint32_t k,
                                            int32_t d, int32_t* __restrict__ oi, float* __restrict__ ov,
                                            float* __restrict__ rl, int lane) {
-  wc_for_each(wc, slots, nslot, lane, [&](uint2 en, bool live) {
-    const uint32_t key = en.y & 0x7FFFFFFFu;
-    const bool keep = live && (key > T || (key == T && en.x <= I));
-    const bool zeroed = key >= t_zero;  // what the streaming pass assumed
-    const uint64_t mk = __ballot(keep);
-    const uint32_t pos = pos0 + mbcnt64(mk);
-    if (live && en.x < (uint32_t)d) {
-      if (keep && pos < k) {
-        oi[pos] = (int32_t)en.x;
-        ov[pos] = __uint_as_float(en.y);
-      }
-      if (keep && !zeroed) rl[en.x] = 0.0f;
-      if (!keep && zeroed) rl[en.x] = __uint_as_float(en.y);
-    }
-    pos0 += (uint32_t)__popcll(mk);
-  });
+  wc_for_each(wc, slots, nslot, lane,
+              [&](uint2 en, bool live) { entry_phase_b(en, live, T, I, t_zero, pos0, k, d, oi, ov, rl); });
 }
 
 // Gives the entries that the streaming pass zeroed (slotted, key >= t_zero) their acc back:
@@ -1271,7 +1368,12 @@ __device__ __forceinline__ bool wave_find_rank64(uint32_t c, uint32_t rank, int 
 // One workgroup per large layer.  Layers that are not sampled hand their tiles to the
 // multi-pass kernels.  Sampled layers get their verdict and decisive bucket; those of at most
 // kFusedTiles tiles are finished here, the others by k_group_a and k_group_b.
-__global__ __launch_bounds__(1024) void k_finish(const SegDesc* __restrict__ segs,
+// Two launches share the layers: workgroups of 256 threads take the sampled layers of at most
+// kFinishSmallTiles tiles, workgroups of 1024 threads all others.  What a layer of a few wave
+// chunks costs is the workgroup-wide scans and searches, which every wave executes; a quarter
+// of the waves issues a quarter of those instructions.
+template <int NT>
+__global__ __launch_bounds__(NT) void k_finish(const SegDesc* __restrict__ segs,
                                                  const LargeSeg* __restrict__ lsegs,
                                                  LState* __restrict__ lstate,
                                                  const uint32_t* __restrict__ chunk_cnt,
@@ -1283,10 +1385,16 @@ __global__ __launch_bounds__(1024) void k_finish(const SegDesc* __restrict__ seg
                                                  float* __restrict__ out_val, uint32_t* __restrict__ counter,
                                                  int32_t* __restrict__ items, int chain,
                                                  uint32_t* __restrict__ fail_flag) {
-  constexpr int NT = 1024, NW = 16;
+  constexpr int NW = NT / 64;
   constexpr int kMaxWc = kFusedTiles / kWaveTiles;
   static_assert(kMaxWc <= NT, "one thread per wave chunk in the scan of their counts");
-  __shared__ uint2 s_band[kBandCap];
+  static_assert(NT == 256 || NT == 1024, "the two launches");
+  static_assert(kFinishSmallTiles <= 256 / 64 * kWaveChunks * kWaveTiles &&
+                    kFusedTiles <= 1024 / 64 * kWaveChunks * kWaveTiles,
+                "a wave walks at most kWaveChunks wave chunks");
+  // the small workgroups keep a shorter band: with 24 KB of LDS a CU holds six of them
+  constexpr int BAND = NT == 256 ? kBandCapSmall : kBandCap;
+  __shared__ uint2 s_band[BAND];
   __shared__ uint32_t s_fine[kFineBins];   // bucket counts; the rescue's histograms reuse it
   __shared__ uint32_t s_wt[2 * NW];
   __shared__ uint32_t s_sel[2];
@@ -1296,6 +1404,7 @@ __global__ __launch_bounds__(1024) void k_finish(const SegDesc* __restrict__ seg
   static_assert(kFineBins >= kBins0, "the rescue's histogram fits");
   const int li = blockIdx.x, tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
   const LargeSeg ls = lsegs[li];
+  if (finish_small(ls) != (NT == 256)) return;  // the other launch's layer
   const SegDesc sd = segs[ls.seg];
   if (!ls.sampled) {  // uniform over the workgroup
     append_tiles<NT>(ls, counter, items, s_sel);
@@ -1307,6 +1416,8 @@ __global__ __launch_bounds__(1024) void k_finish(const SegDesc* __restrict__ seg
   uint32_t n = 0, ntop = 0, bstar = 0, k_rem = 0, n_band = 0;
   int over = 0;
   bool ok;  // uniform over the workgroup
+  WaveChunk wcs[kWaveChunks];  // wave w walks the wave chunks w, w + NW, ... of a layer finished here
+  WaveEntries we;
   if (ls.fused) {
     // totals of the tiles (candidates, overflowed tiles) and bucket counts of the own slots
     for (int c = ls.chunk_begin + tid; c < ls.chunk_end; c += NT) {  // at most kFusedTiles <= NT tiles
@@ -1314,12 +1425,15 @@ __global__ __launch_bounds__(1024) void k_finish(const SegDesc* __restrict__ seg
       over |= v > (uint32_t)nslot;
       n += v;
     }
-    reinterpret_cast<uint4*>(s_fine)[tid] = make_uint4(0u, 0u, 0u, 0u);
+    for (int i = tid; i < kFineBins / 4; i += NT) reinterpret_cast<uint4*>(s_fine)[i] = make_uint4(0u, 0u, 0u, 0u);
     __syncthreads();
-    for (int q = w; q < nwc; q += NW) {
-      const WaveChunk wc = wc_open(ls.chunk_begin + q * kWaveTiles, ls.chunk_end, chunk_cnt, nslot, lane);
-      ntop += wc_count(wc, slots, nslot, st.tau, st.tau_top, st.shift, s_fine, lane);
-    }
+#pragma unroll
+    for (int i = 0; i < kWaveChunks; ++i)  // a chunk that starts at or after chunk_end is empty
+      wcs[i] = wc_open(ls.chunk_begin + (w + i * NW) * kWaveTiles, ls.chunk_end, chunk_cnt, nslot, lane);
+    wc_load4(wcs, slots, nslot, lane, we);
+    wc_for_each4(wcs, we, slots, nslot, lane, [&](int, uint2 en, bool live) {
+      entry_count(en, live, st.tau, st.tau_top, st.shift, s_fine, ntop);
+    });
     ntop = lane == 0 ? ntop : 0u;  // the count is wave-uniform: one lane carries it into the sum
     block_sum2<NT>(n, ntop, s_wt);
     over = __syncthreads_or(over);
@@ -1379,7 +1493,7 @@ __global__ __launch_bounds__(1024) void k_finish(const SegDesc* __restrict__ seg
       }
     }
   }
-  ok = ok && n_band <= (uint32_t)kBandCap;
+  ok = ok && n_band <= (uint32_t)BAND;
   if (!ok) {
     reject_layer<NT>(li, ls, sd, st.t_zero, chunk_cnt, slots, nslot, chain, lstate, fail_flag, counter, items, res,
                      out_idx, out_val, s_fine, s_wt, s_sel);
@@ -1397,14 +1511,17 @@ __global__ __launch_bounds__(1024) void k_finish(const SegDesc* __restrict__ seg
   // one workgroup finishes the layer: a wave takes every 16th wave chunk
   if (tid == 0) s_nband = 0u;
   __syncthreads();
-  for (int q = w; q < nwc; q += NW) {
-    const WaveChunk wc = wc_open(ls.chunk_begin + q * kWaveTiles, ls.chunk_end, chunk_cnt, nslot, lane);
-    const uint32_t n_gt =
-        wc_phase_a(wc, slots, nslot, st.tau, st.tau_top, st.shift, bstar, s_band, kBandCap, &s_nband, lane);
-    if (lane == 0) s_wgt[q] = n_gt;
+  {
+    uint32_t n_gt[kWaveChunks] = {0u, 0u, 0u, 0u};
+    wc_for_each4(wcs, we, slots, nslot, lane, [&](int i, uint2 en, bool live) {
+      entry_phase_a(en, live, st.tau, st.tau_top, st.shift, bstar, s_band, BAND, &s_nband, n_gt[i]);
+    });
+#pragma unroll
+    for (int i = 0; i < kWaveChunks; ++i)
+      if (lane == 0 && w + i * NW < nwc) s_wgt[w + i * NW] = n_gt[i];
   }
   __syncthreads();
-  const uint32_t m = s_nband < (uint32_t)kBandCap ? s_nband : (uint32_t)kBandCap;  // equals n_band
+  const uint32_t m = s_nband < (uint32_t)BAND ? s_nband : (uint32_t)BAND;  // equals n_band
   if (tid == 0) { s_ti[0] = 0xFFFFFFFFu; s_ti[1] = 0u; }
   // exclusive scan of the wave chunks' counts (in place)
   {
@@ -1419,11 +1536,19 @@ __global__ __launch_bounds__(1024) void k_finish(const SegDesc* __restrict__ seg
   int32_t* oi = out_idx + sd.out_offset;
   float* ov = out_val + sd.out_offset;
   float* rl = res + sd.offset;
-  for (int q = w; q < nwc; q += NW) {
-    const uint32_t pos0 =
-        s_wgt[q] + band_kept_before(s_band, m, T, I, (uint32_t)q * (uint32_t)(kWaveTiles * kTile), lane);
-    const WaveChunk wc = wc_open(ls.chunk_begin + q * kWaveTiles, ls.chunk_end, chunk_cnt, nslot, lane);
-    wc_phase_b(wc, slots, nslot, T, I, st.t_zero, pos0, k, sd.d, oi, ov, rl, lane);
+  {
+    // a chunk's first output position: the candidates above b* and the kept band entries before it
+    uint32_t pos[kWaveChunks];
+#pragma unroll
+    for (int i = 0; i < kWaveChunks; ++i) {
+      const int q = w + i * NW;
+      pos[i] = 0u;
+      if (q < nwc)  // wave-uniform
+        pos[i] = s_wgt[q] + band_kept_before(s_band, m, T, I, (uint32_t)q * (uint32_t)(kWaveTiles * kTile), lane);
+    }
+    wc_for_each4(wcs, we, slots, nslot, lane, [&](int i, uint2 en, bool live) {
+      entry_phase_b(en, live, T, I, st.t_zero, pos[i], k, sd.d, oi, ov, rl);
+    });
   }
   if (tid == 0) {
     lstate[li].mode = MODE_SPARSE;
@@ -2125,7 +2250,7 @@ __global__ __launch_bounds__(256) void k_delta_finish(const SegDesc* __restrict_
 // ------------------------------------------------------------------ launch ---
 const char* kernel_name(int id) {
   static const char* names[K_NUM] = {
-      "k_prep", "k_small<4,1>", "k_small<4,8>", "k_small<16,10>", "k_stream", "k_group_h", "k_finish", "k_group_a",
+      "k_prep", "k_small<4,1>", "k_small<4,8>", "k_stream", "k_group_h", "k_finish", "k_group_a",
       "k_group_p", "k_group_b",
       "k_hist", "k_count", "k_scan", "k_emit", "k_merge_bounds", "k_merge", "k_merge<apply>", "k_delta_tiles",
       "k_delta_finish", "sparsify_call"};
@@ -2152,11 +2277,19 @@ hipError_t launch_small(int cls, int nseg, const SegDesc* segs, const int32_t* l
   ProfScope ps(prof, K_SMALL0 + cls, s);
   if (cls == 0)
     hipLaunchKernelGGL((k_small<4, 1>), dim3(nseg), dim3(256), 0, s, segs, list, grad, res, lr, out_idx, out_val);
-  else if (cls == 1)
-    hipLaunchKernelGGL((k_small<4, 8>), dim3(nseg), dim3(256), 0, s, segs, list, grad, res, lr, out_idx, out_val);
   else
-    hipLaunchKernelGGL((k_small<16, 10>), dim3(nseg), dim3(1024), 0, s, segs, list, grad, res, lr, out_idx,
-                       out_val);
+    hipLaunchKernelGGL((k_small<4, 8>), dim3(nseg), dim3(256), 0, s, segs, list, grad, res, lr, out_idx, out_val);
+  return hipGetLastError();
+}
+
+hipError_t launch_large_prep(const LargePlan& pl, const Scratch& sc, const SegDesc* segs, const float* grad,
+                             const float* res, float lr, bool chain, hipStream_t s, Prof* prof) {
+  if (pl.n_large <= 0) return hipSuccess;
+  if (pl.has_dense) chain = true;
+  uint32_t* counters = sc.ghist + (int64_t)pl.n_large * kHistStride;
+  ProfScope ps(prof, K_PREP, s);
+  hipLaunchKernelGGL(k_prep, dim3(pl.n_large), dim3(kPrepThreads), 0, s, segs, pl.lsegs, grad, res, lr, sc.lstate, sc.ghist,
+                     counters, chain ? 1 : 0);
   return hipGetLastError();
 }
 
@@ -2167,11 +2300,6 @@ hipError_t launch_large(const LargePlan& pl, const Scratch& sc, const SegDesc* s
   if (pl.has_dense) chain = true;
   uint32_t* counters = sc.ghist + (int64_t)pl.n_large * kHistStride;
   const int ch = chain ? 1 : 0;
-  {
-    ProfScope ps(prof, K_PREP, s);
-    hipLaunchKernelGGL(k_prep, dim3(pl.n_large), dim3(1024), 0, s, segs, pl.lsegs, grad, res, lr, sc.lstate, sc.ghist,
-                       counters, ch);
-  }
   {
     const int nl = (pl.n_tiles + kStreamLaunchTiles - 1) / kStreamLaunchTiles;
     ProfScope ps(prof, K_STREAM, s, nl);
@@ -2188,9 +2316,15 @@ hipError_t launch_large(const LargePlan& pl, const Scratch& sc, const SegDesc* s
   }
   {
     ProfScope ps(prof, K_FINISH, s);
-    hipLaunchKernelGGL(k_finish, dim3(pl.n_large), dim3(1024), 0, s, segs, pl.lsegs, sc.lstate, sc.chunk_cnt,
-                       sc.slots, pl.slot, sc.bh_part, sc.coarse_part, sc.part_info, res, out_idx, out_val, counters,
-                       sc.items, ch, sc.fail_flag);
+    // every workgroup of either launch looks at its layer's class and leaves the other launch's alone
+    if (pl.n_finish_small > 0)
+      hipLaunchKernelGGL(k_finish<256>, dim3(pl.n_large), dim3(256), 0, s, segs, pl.lsegs, sc.lstate, sc.chunk_cnt,
+                         sc.slots, pl.slot, sc.bh_part, sc.coarse_part, sc.part_info, res, out_idx, out_val, counters,
+                         sc.items, ch, sc.fail_flag);
+    if (pl.n_finish_small < pl.n_large)
+      hipLaunchKernelGGL(k_finish<1024>, dim3(pl.n_large), dim3(1024), 0, s, segs, pl.lsegs, sc.lstate, sc.chunk_cnt,
+                         sc.slots, pl.slot, sc.bh_part, sc.coarse_part, sc.part_info, res, out_idx, out_val, counters,
+                         sc.items, ch, sc.fail_flag);
   }
   if (pl.n_groups > 0) {
     {

@@ -169,9 +169,9 @@ int lags_sparsify_layer_noalloc(int device, const float* grad, float* residual, 
   OneLayer p = {};
   p.d = (int32_t)d;
   p.k = (int32_t)k;
-  const int cls = d <= kSmall0 ? 0 : (d <= kSmall1 ? 1 : (d <= kSmall2 ? 2 : 3));
+  const int cls = d <= kSmall0 ? 0 : (d <= kSmall1 ? 1 : kSmallClasses);
   LargePlan pl;
-  if (cls == 3) {
+  if (cls == kSmallClasses) {
     const int64_t nt = (d + kTile - 1) / kTile;
     double per_tile = 0.0;
     LargeSeg& ls = p.ls;
@@ -205,6 +205,7 @@ int lags_sparsify_layer_noalloc(int device, const float* grad, float* residual, 
     } else {
       pl.has_dense = true;
     }
+    pl.n_finish_small = finish_small(ls) ? 1 : 0;
     p.n_tiles = pl.n_tiles;
     p.n_groups = pl.n_groups;
     p.n_hparts = pl.n_hparts;
@@ -221,7 +222,7 @@ int lags_sparsify_layer_noalloc(int device, const float* grad, float* residual, 
     if (hipGetLastError() != hipSuccess) return LAGS_EHIP;
   }
   const SegDesc* segs = reinterpret_cast<const SegDesc*>(base + kLayout.segs);
-  if (cls < 3) {
+  if (cls < kSmallClasses) {
     if (launch_small(cls, 1, segs, reinterpret_cast<const int32_t*>(base + kLayout.list), grad, residual, lr, out_idx,
                      out_val, s, nullptr) != hipSuccess)
       return LAGS_EHIP;
@@ -249,6 +250,7 @@ int lags_sparsify_layer_noalloc(int device, const float* grad, float* residual, 
   sc.items = reinterpret_cast<int32_t*>(base + kLayout.items);
   sc.fail_flag = reinterpret_cast<uint32_t*>(base + kLayout.fail);   // nobody reads it: a rejected guess is
                                                                       // always served inside the same launches
+  if (launch_large_prep(pl, sc, segs, grad, residual, lr, /*chain=*/false, s, nullptr) != hipSuccess) return LAGS_EHIP;
   if (launch_large(pl, sc, segs, grad, residual, lr, out_idx, out_val, /*chain=*/false, s, nullptr) != hipSuccess)
     return LAGS_EHIP;
   return LAGS_OK;

@@ -350,7 +350,7 @@ def test_scratch_poison_does_not_change_results(gpu, oracle):
     do the merge, the apply and the delta metric."""
     torch = gpu.torch
     rng = np.random.default_rng(92)
-    sizes = [(700, 0.01), (250_000, 0.002), (2_600_000, 0.003), (60_000, 0.6), (180_000, 0.001), (30_000, 0.004)]
+    sizes = [(700, 0.01), (250_000, 0.002), (2_600_000, 0.003), (60_000, 0.6), (180_000, 0.001), (7_000, 0.004)]
     layers, total = _one_table_case(rng, sizes)
     P = 3
     table = gpu.ctx.table(layers)

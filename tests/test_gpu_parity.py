@@ -278,7 +278,7 @@ def test_fallback_after_early_zeros(gpu, oracle):
 def test_mixed_routes_in_one_table(gpu, oracle):
     """One table whose layers take all four routes at once, over several iterations."""
     rng = np.random.default_rng(53)
-    sizes = [(100, 0.01), (200_000, 0.002), (60_000, 0.6), (150_000, 0.001), (9000, 0.001), (1_200_000, 0.003)]
+    sizes = [(100, 0.01), (200_000, 0.002), (60_000, 0.6), (150_000, 0.001), (6000, 0.001), (1_200_000, 0.003)]
     layers, off = [], 0
     for d, rho in sizes:
         layers.append((off, d, rho))
