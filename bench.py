@@ -30,15 +30,19 @@ N_ITERS = 3             # pre-generated gradient iterations that the steps cycle
 
 def committed_traffic(kernel, workload, workers):
     """HBM bytes per launch of `kernel` for this workload from a committed rocprofv3 counter
-    summary (profiles/*.txt, line 'TRAFFIC_BYTES_PER_LAUNCH <kernel> <workload> P=<workers>: <bytes>'),
-    with the file it came from, or (None, None) if no summary covers it."""
+    summary (profiles/*.txt, lines 'FETCH_BYTES_PER_LAUNCH <kernel> <workload> P=<workers>: <bytes>'
+    and 'WRITE_BYTES_PER_LAUNCH ...'): (read bytes, written bytes, file), each None where no
+    summary holds it."""
     import glob
-    key = "TRAFFIC_BYTES_PER_LAUNCH %s %s P=%d:" % (kernel, workload, workers)
+    found = {"FETCH": None, "WRITE": None}
+    src = None
     for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*.txt"))):
         for line in open(path):
-            if line.startswith(key):
-                return float(line.split(":")[1]), os.path.relpath(path, ROOT)
-    return None, None
+            for what in found:
+                if line.startswith("%s_BYTES_PER_LAUNCH %s %s P=%d:" % (what, kernel, workload, workers)):
+                    found[what] = float(line.split(":")[1])
+                    src = os.path.relpath(path, ROOT)
+    return found["FETCH"], found["WRITE"], src
 
 
 def cpu_baseline(wl, grad0_host, threads):
@@ -214,6 +218,7 @@ def main():
                     help="one lags_sparsify_model call per worker (L layers each) instead of one batched call")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-configs", action="store_true", help="skip the block of the other configurations")
+    ap.add_argument("--progress", action="store_true", help="name every stage on stderr as it starts")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain device copy of 1 GiB (for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -222,6 +227,11 @@ def main():
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
         sys.exit(2)
 
+    def stage(name):
+        if args.progress:
+            print("bench.py: " + name, file=sys.stderr, flush=True)
+
+    stage("import torch")
     import numpy as np
     import torch
     from paper_1911_08727_amd import hbmcal, lags, workloads
@@ -247,16 +257,19 @@ def main():
     grad_pool = torch.empty(N_ITERS * pool_elems, dtype=torch.float32, device=dev)
     res_pool = torch.empty(pool_elems, dtype=torch.float32, device=dev)
 
+    stage("tables and synthetic gradients")
     ctx = lags.Context(0)
     job = Job(torch, lags, workloads, ctx, wl, P, grad_pool, res_pool, dev)
     total, K, layers = job.total, job.K, job.layers
     grad0_host = None if args.no_cpu_baseline else job.grads[0][:total].cpu().numpy()
 
+    stage("warm-up steps")
     for _ in range(args.warmup):
         job.step(args.per_worker)
     torch.cuda.synchronize()
     # an untimed pass with every kernel bracketed by events: the per-kernel table, and which
     # kernel dominates
+    stage("per-kernel pass")
     ctx.lags_profile_reset()
     ctx.lags_profile_enable(True)
     n_table = max(2, min(5, args.steps))
@@ -270,6 +283,7 @@ def main():
     dom = max(prof_all, key=lambda k: prof_all[k][0])
     # the timed region: exactly K steps; only the dominant kernel is bracketed by HIP events
     # (on the stream it is launched on), so the measurement adds two events per step
+    stage("timed steps")
     ctx.lags_profile_enable_kernel(dom)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -281,11 +295,13 @@ def main():
     prof = ctx.lags_profile_read()
     ctx.lags_profile_reset()
     # the two calls of a step apart, two events each (no per-kernel events)
+    stage("steps with one event pair per call")
     sp_ms, mg_ms, st_ms = job.timed_steps(max(3, min(10, args.steps)), args.per_worker)
     headline = job.summary(sp_ms, mg_ms, st_ms)
 
     # the rows next to the hot path, measured apart from the timed steps: the in-place sparse
     # parameter step (Algorithm 1 line 9) and the delta metric of Section 6.2
+    stage("sparse apply and delta metric")
     param = torch.zeros(total, dtype=torch.float32, device=dev)
     delta = torch.empty(3 * len(layers), dtype=torch.float64, device=dev)
     reps = 5
@@ -304,6 +320,7 @@ def main():
     apply_ms = statistics.median(ev[2 * i].elapsed_time(ev[2 * i + 1]) for i in range(reps))
     delta_ms = statistics.median(ev[2 * i + 1].elapsed_time(ev[2 * i + 2]) for i in range(reps))
     delta_host = delta.cpu().numpy().reshape(-1, 3)
+    stage("routes")
     route_elems = job.routes()
 
     # Eq. 9 (Section 5) on a SYNTHETIC timing table: backpropagation time proportional to the layer
@@ -336,12 +353,16 @@ def main():
     # algorithmic bytes of the elements the kernel covers in one step / its time in one step
     # (= bytes per launch / average launch duration when every launch covers an equal share)
     achieved = bpe * kel.get(dom, elements) / (dom_ms_per_step * 1e-3) / 1e9
-    traffic, traffic_file = (None, None) if args.per_worker else committed_traffic(dom, wl.name, P)
+    # HBM bytes per launch from the committed counter summary; `traffic` needs both counters
+    t_fetch, t_write, traffic_file = (None, None, None) if args.per_worker else committed_traffic(dom, wl.name, P)
+    traffic = None if t_fetch is None or t_write is None else t_fetch + t_write
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": None if traffic is None else traffic / launches_per_step,
-                "traffic_source": None if traffic is None else
-                "%s (rocprofv3 --pmc run committed with the tree, not measured in this run)" % traffic_file,
+                "traffic": traffic,
+                "traffic_fetch": t_fetch, "traffic_write": t_write,
+                "traffic_source": None if traffic_file is None else
+                "%s (rocprofv3 --pmc runs committed with the tree, not measured in this run; "
+                "a counter that is null there was not collected)" % traffic_file,
                 "avg_kernel_ms": round(dom_ms, 4), "launches_per_step": launches_per_step,
                 "bytes_per_element": round(bpe, 4),
                 "elements_per_launch": kel.get(dom, elements) / launches_per_step}
@@ -351,6 +372,7 @@ def main():
     # the practical ceiling beside the data sheet's peak: plain kernels of the streaming pass's
     # shape (libhbmcal.so) on an array the size of the largest layer and on one as large as all
     # workers' arrays; with and without the streaming pass's occupancy cap
+    stage("plain streaming kernels")
     sink = torch.zeros(64, dtype=torch.float32, device=dev)
     big_n = (pool_elems // 4096) * 4096
     small_n = min(big_n, (102760448 // 4096) * 4096)
@@ -386,8 +408,11 @@ def main():
         "hbm": {"peak_gbs": HBM_PEAK_GBS, "plain_kernels": cal,
                 "dominant_kernel_algorithmic_gbs": roofline["achieved"],
                 "dominant_kernel_frac_of_plain_triad": round(roofline["achieved"] / triad, 4),
-                "dominant_kernel_counter_gbs_from_committed_profile":
-                    None if traffic is None else round(roofline["traffic"] / (dom_ms * 1e-3) / 1e9, 1)},
+                "dominant_kernel_read_counter_gbs_from_committed_profile":
+                    None if t_fetch is None else round(t_fetch / (dom_ms * 1e-3) / 1e9, 1),
+                "dominant_kernel_read_counter_over_algorithmic_read":
+                    None if t_fetch is None or dom != "k_stream" else
+                    round(t_fetch / (8.0 * kel.get(dom, elements) / launches_per_step), 4)},
         "kernels": kernels,
         "elements_by_route": route_elems,
         "roofline": roofline,
@@ -405,6 +430,7 @@ def main():
     idx_host, val_host = job.idx.cpu().numpy(), job.val.cpu().numpy()
 
     if not args.no_configs:
+        stage("other call shapes and configurations")
         # the call shapes a single worker would issue, on the headline workload
         configs = {}
         sp, mg, st = job.timed_steps(5, per_worker=True)
@@ -427,6 +453,7 @@ def main():
         job.close()
 
     if not args.no_cpu_baseline:
+        stage("oracle on the host cores")
         threads = min(16, os.cpu_count() or 1)
         v, dt = cpu_baseline(wl, grad0_host, threads)
         extras = cpu_baseline_extras(wl, grad0_host, idx_host, val_host, P, K)

@@ -71,7 +71,12 @@ int64_t lags_topk_count(int64_t d, double rho);
 
 /* Create / destroy a context on HIP device `device`.  Scratch grows when a table is
  * created and is released by lags_destroy (which waits for the device first).  If an allocation
- * for a larger table fails, the context and the tables created before stay usable. */
+ * for a larger table fails, the context and the tables created before stay usable.
+ * A context owns one side stream on which lags_sparsify_model runs the kernels of the small
+ * layers beside those of the large ones (forked from and joined to the caller's stream with
+ * events, so the caller sees one ordered call).  With LAGS_SIDE_STREAM=0 in the environment when
+ * the context is created, every kernel stays on the caller's stream: meant for tools that
+ * serialise the dispatches of all queues, such as counter collection. */
 int lags_create(lags_ctx **out, int device);
 int lags_destroy(lags_ctx *ctx);
 

@@ -6,6 +6,7 @@
 
 #include <algorithm>
 #include <cmath>
+#include <cstdlib>
 #include <map>
 #include <new>
 #include <utility>
@@ -476,7 +477,11 @@ int lags_create(lags_ctx** out, int device) {
   c->device = device;
   {
     DeviceGuard g(device);
-    if (g.ok && hipStreamCreateWithFlags(&c->aux, hipStreamNonBlocking) == hipSuccess) {
+    // LAGS_SIDE_STREAM=0 keeps every kernel on the caller's stream (for tools that serialise
+    // the dispatches of all queues, such as counter collection)
+    const char* side = std::getenv("LAGS_SIDE_STREAM");
+    const bool want_side = !(side && side[0] == '0' && side[1] == '\0');
+    if (g.ok && want_side && hipStreamCreateWithFlags(&c->aux, hipStreamNonBlocking) == hipSuccess) {
       if (hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) != hipSuccess ||
           hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming) != hipSuccess) {
         if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
