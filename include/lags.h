@@ -109,8 +109,10 @@ int lags_sparsify_layer(lags_ctx *ctx, const float *grad, float *residual, int64
  * ends), and the call performs no allocation of any kind: it enqueues kernels on `hip_stream`
  * of HIP device `device` and returns.
  *   d <= lags_noalloc_max_elements() (16,777,216), and tiles of 4096 elements x candidate slots
- *   per tile <= 2^19: a layer that keeps up to 0.16 % of its entries uses 128 slots per tile
- *   (16.7 M elements fit), one that keeps up to 0.4 % uses 256 (8.3 M elements fit), and so on.
+ *   per tile <= 2^19.  The slots per tile follow from k/d (a power of two, at least eight times
+ *   the expected candidates of a tile): above 2^20 elements a layer that keeps up to 0.16 % of
+ *   its entries uses 128 slots per tile (16.7 M elements fit), one that keeps up to 0.4 % uses
+ *   256 (8.3 M elements fit), and so on; layers of up to 2^20 elements always fit.
  *   Larger requests return LAGS_ECAPACITY and enqueue nothing.
  * All calls on one GPU share the array: calls that overlap in time on one GPU (two streams, two
  * threads) race and give undefined results; calls ordered on one stream are fine, and nothing

@@ -274,6 +274,40 @@ def test_two_contexts_on_two_streams(gpu, oracle):
     ctxs[1].destroy()
 
 
+def test_context_without_side_stream(gpu, oracle, monkeypatch):
+    """LAGS_SIDE_STREAM=0 at lags_create keeps every kernel on the caller's stream: a table with
+    small and large layers gives the oracle's results over several iterations."""
+    from paper_1911_08727_amd import lags
+    torch = gpu.torch
+    monkeypatch.setenv("LAGS_SIDE_STREAM", "0")
+    ctx = lags.Context(0)
+    monkeypatch.delenv("LAGS_SIDE_STREAM")
+    rng = np.random.default_rng(79)
+    sizes = [(900, 0.01), (6_000, 0.004), (300_000, 0.002), (30_000, 0.001), (2_300_000, 0.001), (70_000, 0.4)]
+    layers, off = [], 0
+    for d, rho in sizes:
+        layers.append((off, d, rho))
+        off += d + 1
+    table = ctx.table(layers)
+    K = table.total_k
+    res = torch.zeros(off, dtype=torch.float32, device=gpu.dev)
+    idx = torch.empty(K, dtype=torch.int32, device=gpu.dev)
+    val = torch.empty(K, dtype=torch.float32, device=gpu.dev)
+    rc = np.zeros(off, np.float32)
+    stream = torch.cuda.current_stream()
+    for it in range(3):
+        note("one-stream context, iteration %d" % it)
+        g = rng.standard_normal(off).astype(np.float32)
+        wi, wv = oracle_model_parallel(oracle, layers, g, rc, 0.2)
+        ctx.lags_sparsify_model(table, gpu.to_dev(g), res, 0.2, idx, val, stream)
+        torch.cuda.synchronize()
+        assert_same("idx", idx.cpu().numpy(), wi)
+        assert_same("val", val.cpu().numpy(), wv)
+        assert_same("res", res.cpu().numpy(), rc)
+    table.destroy()
+    ctx.destroy()
+
+
 def _one_table_case(rng, sizes):
     layers, off = [], 0
     for d, rho in sizes:
