@@ -1978,61 +1978,99 @@ __global__ __launch_bounds__(256) void k_merge_bounds(const BChunk* __restrict__
 
 // Accumulation shared by the merge-type kernels: the workgroup that owns one tile of the
 // dense layout loads the entries of all workers that fall into the tile (found through the
-// bounds, no searching) and adds them into the LDS tile s_acc in worker order (one barrier per
-// worker; inside one worker the indices are distinct).  T = float: binary32 adds, the sum the
-// method defines.  T = double: exact-order double sums for the delta metric.
-// Returns the number of entries that fell into the tile.
-template <typename T>
-__device__ __forceinline__ uint32_t merge_accumulate(T* s_acc, uint32_t* s_start, int32_t* s_lo, uint32_t* s_wt,
-                                                     const TileDesc& td, const SegDesc& sd, int slot,
-                                                     const int32_t* __restrict__ idx,
-                                                     const float* __restrict__ val, int P, int64_t stride_k,
-                                                     int nb, const int32_t* __restrict__ bounds) {
+// bounds, no searching) and adds them into the LDS tile s_acc in worker order.
+// T = float: binary32 adds, the sum the method defines.  T = double: exact-order double sums for
+// the delta metric.
+//
+// Order only matters for an element that three or more workers selected: 0 + a + b is the same
+// binary32 value in either order (0 + x is x, or +0 for x = -0, and the sum of two values is
+// commutative).  So the float accumulation first adds all entries at once (compare-and-swap on
+// the element's bits with a correctly rounded add), while two bitmaps record which elements were
+// hit once and twice; only if some element is hit a third time (about one tile in 200 when the
+// workers together keep 1.6 % of the tile) is the tile redone in worker order, one barrier per
+// worker (inside one worker the indices are distinct).  Tiles with more than kMergeUnorderedMax
+// entries, where third hits are likely, and calls with more than 256 workers go straight to the
+// ordered pass.  s_multi: 2 * kMergeTile / 32 + 1 words (float only).
+// merge_accumulate returns the number of entries that fell into the tile.
+constexpr int kMergeUnorderedMax = 256;
+
+// Entry table of one batch of up to 256 workers for one tile: s_start[q] = number of entries of
+// the workers before q that fall into the tile, s_start[256] = their total (returned), s_lo[q] =
+// where worker q's entries start in its list.  Ends with a barrier.
+__device__ __forceinline__ uint32_t merge_table(uint32_t* s_start, int32_t* s_lo, uint32_t* s_wt, int32_t k,
+                                                int slot, int p0, int np, int P,
+                                                const int32_t* __restrict__ bounds) {
   const int tid = threadIdx.x;
-  uint32_t entries = 0;
-  for (int i = tid; i < kMergeTile; i += 256) s_acc[i] = (T)0;
-  for (int p0 = 0; p0 < P; p0 += 256) {
-    const int np = P - p0 < 256 ? P - p0 : 256;
-    int lo = 0;
-    uint32_t cnt = 0;
-    if (tid < np) {
-      const int32_t* b = bounds + (int64_t)slot * P + (p0 + tid);  // slot-major: adjacent workers, adjacent words
-      int hi = b[P];
-      lo = b[0];
-      lo = lo < 0 ? 0 : (lo > sd.k ? sd.k : lo);
-      hi = hi < 0 ? 0 : (hi > sd.k ? sd.k : hi);
-      cnt = hi > lo ? (uint32_t)(hi - lo) : 0u;
+  int lo = 0;
+  uint32_t cnt = 0;
+  if (tid < np) {
+    const int32_t* b = bounds + (int64_t)slot * P + (p0 + tid);  // slot-major: adjacent workers, adjacent words
+    int hi = b[P];
+    lo = b[0];
+    lo = lo < 0 ? 0 : (lo > k ? k : lo);
+    hi = hi < 0 ? 0 : (hi > k ? k : hi);
+    cnt = hi > lo ? (uint32_t)(hi - lo) : 0u;
+  }
+  uint32_t total;
+  const uint32_t incl = block_incl_scan<256>(cnt, s_wt, total);
+  s_start[tid] = incl - cnt;
+  s_lo[tid] = lo;
+  if (tid == 0) s_start[256] = total;
+  __syncthreads();
+  return total;
+}
+
+// Adds the `total` entries of the batch's table into s_acc.  Ends with a barrier.
+template <typename T, bool ORDERED>
+__device__ __forceinline__ void merge_entries(T* s_acc, const uint32_t* s_start, const int32_t* s_lo,
+                                              uint32_t* s_multi, uint32_t total, const TileDesc& td,
+                                              const SegDesc& sd, int p0, int np, const int32_t* __restrict__ idx,
+                                              const float* __restrict__ val, int64_t stride_k) {
+  const int tid = threadIdx.x;
+  for (uint32_t base = 0; base < total; base += 1024) {
+    int pe[4];
+    uint32_t off[4];
+    float v[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const uint32_t e = base + (uint32_t)(r * 256 + tid);
+      pe[r] = -1;
+      off[r] = 0xFFFFFFFFu;
+      v[r] = 0.f;
+      if (e < total) {
+        int a = 0, z = np;  // last worker q with s_start[q] <= e (skips workers without entries here)
+        while (a < z) {
+          const int mid = (a + z) >> 1;
+          if (s_start[mid] <= e) a = mid + 1; else z = mid;
+        }
+        const int q = a - 1;
+        const int64_t gi = (int64_t)(p0 + q) * stride_k + sd.out_offset + s_lo[q] + (int)(e - s_start[q]);
+        off[r] = (uint32_t)(idx[gi] - td.local0);
+        v[r] = val[gi];
+        pe[r] = q;
+      }
     }
-    uint32_t total;
-    const uint32_t incl = block_incl_scan<256>(cnt, s_wt, total);
-    s_start[tid] = incl - cnt;
-    s_lo[tid] = lo;
-    if (tid == 0) s_start[256] = total;
-    __syncthreads();
-    entries += total;
-    for (uint32_t base = 0; base < total; base += 1024) {
-      int pe[4];
-      uint32_t off[4];
-      float v[4];
+    if constexpr (!ORDERED) {
+      static_assert(sizeof(T) == 4, "the unordered pass is for binary32 sums");
+      uint32_t* once = s_multi;
+      uint32_t* twice = s_multi + kMergeTile / 32;
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        const uint32_t e = base + (uint32_t)(r * 256 + tid);
-        pe[r] = -1;
-        off[r] = 0xFFFFFFFFu;
-        v[r] = 0.f;
-        if (e < total) {
-          int a = 0, z = np;  // last worker q with s_start[q] <= e (skips workers without entries here)
-          while (a < z) {
-            const int mid = (a + z) >> 1;
-            if (s_start[mid] <= e) a = mid + 1; else z = mid;
+        if (pe[r] >= 0 && off[r] < (uint32_t)td.n) {
+          const uint32_t bit = 1u << (off[r] & 31u), wd = off[r] >> 5;
+          if (atomicOr(&once[wd], bit) & bit)
+            if (atomicOr(&twice[wd], bit) & bit) s_multi[2 * (kMergeTile / 32)] = 1u;  // a third hit
+          uint32_t* cell = reinterpret_cast<uint32_t*>(&s_acc[off[r]]);
+          uint32_t seen = *cell;
+          for (;;) {  // ends: a failed swap means another entry's swap succeeded
+            const uint32_t want = __float_as_uint(__fadd_rn(__uint_as_float(seen), v[r]));
+            const uint32_t got = atomicCAS(cell, seen, want);
+            if (got == seen) break;
+            seen = got;
           }
-          const int q = a - 1;
-          const int64_t gi = (int64_t)(p0 + q) * stride_k + sd.out_offset + s_lo[q] + (int)(e - s_start[q]);
-          off[r] = (uint32_t)(idx[gi] - td.local0);
-          v[r] = val[gi];
-          pe[r] = q;
         }
       }
+    } else {
       // workers present in this pass (uniform over the workgroup)
       int qf, ql;
       {
@@ -2055,7 +2093,40 @@ __device__ __forceinline__ uint32_t merge_accumulate(T* s_acc, uint32_t* s_start
         __syncthreads();
       }
     }
-    __syncthreads();
+  }
+  __syncthreads();
+}
+
+template <typename T>
+__device__ __forceinline__ uint32_t merge_accumulate(T* s_acc, uint32_t* s_start, int32_t* s_lo, uint32_t* s_wt,
+                                                     uint32_t* s_multi, const TileDesc& td, const SegDesc& sd,
+                                                     int slot, const int32_t* __restrict__ idx,
+                                                     const float* __restrict__ val, int P, int64_t stride_k,
+                                                     const int32_t* __restrict__ bounds) {
+  const int tid = threadIdx.x;
+  for (int i = tid; i < kMergeTile; i += 256) s_acc[i] = (T)0;
+  if constexpr (sizeof(T) == 4) {
+    if (P <= 256) {  // one batch of workers: its table shows the tile's whole entry count
+      for (int i = tid; i < 2 * (kMergeTile / 32) + 1; i += 256) s_multi[i] = 0u;
+      const uint32_t total = merge_table(s_start, s_lo, s_wt, sd.k, slot, 0, P, P, bounds);
+      if (total <= (uint32_t)kMergeUnorderedMax) {  // uniform over the workgroup
+        merge_entries<T, false>(s_acc, s_start, s_lo, s_multi, total, td, sd, 0, P, idx, val, stride_k);
+        if (s_multi[2 * (kMergeTile / 32)] == 0u) return total;
+        __syncthreads();
+        for (int i = tid; i < kMergeTile; i += 256) s_acc[i] = (T)0;
+        __syncthreads();
+      }
+      merge_entries<T, true>(s_acc, s_start, s_lo, s_multi, total, td, sd, 0, P, idx, val, stride_k);
+      return total;
+    }
+  }
+  __syncthreads();
+  uint32_t entries = 0;
+  for (int p0 = 0; p0 < P; p0 += 256) {
+    const int np = P - p0 < 256 ? P - p0 : 256;
+    const uint32_t total = merge_table(s_start, s_lo, s_wt, sd.k, slot, p0, np, P, bounds);
+    entries += total;
+    merge_entries<T, true>(s_acc, s_start, s_lo, s_multi, total, td, sd, p0, np, idx, val, stride_k);
   }
   return entries;
 }
@@ -2076,6 +2147,7 @@ __global__ __launch_bounds__(256) void k_merge(const MTile* __restrict__ mtiles,
   __shared__ int32_t s_lo[256];
   __shared__ uint32_t s_wt[4];
   __shared__ uint32_t s_claim[APPLY ? kMergeTile / 32 : 1];
+  __shared__ uint32_t s_multi[2 * (kMergeTile / 32) + 1];
   const MTile mt = mtiles[blockIdx.x];  // one read: the tile and what the kernel needs of its layer
   TileDesc td;
   td.start = mt.start; td.n = mt.n; td.seg = mt.seg; td.local0 = mt.local0; td.ctile = -1;
@@ -2085,7 +2157,7 @@ __global__ __launch_bounds__(256) void k_merge(const MTile* __restrict__ mtiles,
   const int slot = (int)blockIdx.x + td.seg;  // every earlier layer owns one extra (end) slot
   if (APPLY) s_claim[tid] = 0u;  // kMergeTile / 32 = 256 words; the accumulation's barriers order this
   const uint32_t entries =
-      merge_accumulate<float>(s_acc, s_start, s_lo, s_wt, td, sd, slot, idx, val, P, stride_k, nb, bounds);
+      merge_accumulate<float>(s_acc, s_start, s_lo, s_wt, s_multi, td, sd, slot, idx, val, P, stride_k, bounds);
   // sum / P: for P a power of two the product with 1/P is the same binary32 value as the
   // quotient (an exact scaling, rounded identically when the result is subnormal), and it is
   // much cheaper than a correctly rounded division
@@ -2174,7 +2246,7 @@ __global__ __launch_bounds__(256) void k_delta_tiles(const MTile* __restrict__ m
   sd.offset = 0; sd.out_offset = mt.out_offset; sd.d = 0; sd.k = mt.k;
   const int tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
   const int slot = (int)blockIdx.x + td.seg;
-  (void)merge_accumulate<double>(s_acc, s_start, s_lo, s_wt, td, sd, slot, idx, val, P, stride_k, nb, bounds);
+  (void)merge_accumulate<double>(s_acc, s_start, s_lo, s_wt, nullptr, td, sd, slot, idx, val, P, stride_k, bounds);
   double num = 0.0, sq = 0.0;
   const float* rt = res + td.start;
   const bool vec = aligned16(rt, rt) && (res_stride & 3) == 0;

@@ -406,7 +406,7 @@ def test_merge_closed_forms(gpu, oracle):
     layers = [(0, 20000, 0.01), (20004, 9, 0.5), (20013, 70000, 0.002)]
     total = 20013 + 70000
     K = oracle.total_k(layers)
-    for P in (1, 3, 7, 16, 70, 300):
+    for P in (1, 2, 3, 7, 16, 70, 300):
         idx = np.empty(P * K, np.int32)
         val = (rng.standard_normal(P * K) * 10.0 ** rng.integers(-8, 8, P * K)).astype(np.float32)
         for p in range(P):
@@ -442,6 +442,7 @@ def test_merge_subnormal_results(gpu, oracle):
         idx = np.tile(np.sort(rng.choice(5000, K, replace=False)).astype(np.int32), P)
         val = (rng.integers(-40, 41, P * K).astype(np.float64) * 2.0 ** -149).astype(np.float32)
         val[::7] = np.float32(1.1754944e-38) * rng.standard_normal(len(val[::7])).astype(np.float32)
+        val[::11] = -0.0          # 0 + (-0) is +0 whichever worker comes first
         note("merge subnormal P=%d" % P)
         want = np.empty(5000, np.float32)
         oracle.merge_sparse(layers, idx, val, P, K, want)

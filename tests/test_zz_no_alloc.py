@@ -17,7 +17,8 @@ def test_noalloc_matches_sparsify_layer():
     dev = torch.device("cuda:0")
     ctx = lags.Context(0)
     gen = torch.Generator(device=dev).manual_seed(77)
-    # (d, rho): multi-workgroup finish, one-workgroup finish, the three small classes, a layer
+    # (d, rho): multi-workgroup finish, one-workgroup finish (large and small workgroups, short and
+    # full sample), the two one-workgroup classes, a layer
     # too dense to sample (multi-pass route), an all-zero layer (rejected guess)
     cases = [(3_000_001, 0.001), (700_000, 0.004), (16_000_000, 0.0015), (8_000_000, 0.004), (1 << 20, 0.001), (30_000, 0.01),
              (5_000, 0.002), (600, 0.01), (300_000, 0.5), (250_000, 0.001), (41_000, 0.003), (40, 1.0)]
