@@ -74,7 +74,7 @@ struct lags_ctx {
   // side stream (default priority) on which the small layers' kernels run beside the large
   // layers' pipeline; forked from and joined to the caller's stream with events in every call
   hipStream_t aux = nullptr;
-  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+  hipEvent_t ev_fork = nullptr, ev_join = nullptr, ev_side = nullptr;
   std::vector<void*>* retire_list() { return captured ? &retired : nullptr; }
   Scratch scratch() const {
     Scratch sc;
@@ -445,12 +445,19 @@ int run_sparsify(lags_ctx* ctx, const lags_table* t, const float* grad, float* r
     if (launch_small(c, t->n_small[c], t->d_segs, t->d_small[c], grad, res, lr, out_idx, out_val, ss, &ctx->prof) != hipSuccess)
       rc = LAGS_EHIP;
   }
-  if (fork && hipEventRecord(ctx->ev_join, ctx->aux) != hipSuccess) rc = LAGS_EHIP;
+  // the layers that one small workgroup finishes need nothing from the kernels of the layers
+  // finished by groups: when the table has both, the side stream takes them after the streaming pass
+  const LargePlan& pl = t->plan;
+  const bool offload = rc == LAGS_OK && ctx->aux && !chain && pl.n_finish_small > 0 && pl.n_finish_small < pl.n_large;
   if (rc == LAGS_OK &&
-      launch_large(t->plan, ctx->scratch(), t->d_segs, grad, res, lr, out_idx, out_val, chain, s, &ctx->prof) != hipSuccess)
+      launch_large(pl, ctx->scratch(), t->d_segs, grad, res, lr, out_idx, out_val, chain, s, &ctx->prof,
+                   offload ? ctx->aux : nullptr, ctx->ev_side) != hipSuccess)
     rc = LAGS_EHIP;
   // always join what was forked, also on an error path, so the caller's stream stays ordered
-  if (fork && hipStreamWaitEvent(s, ctx->ev_join, 0) != hipSuccess) rc = LAGS_EHIP;
+  if (fork || offload) {
+    if (hipEventRecord(ctx->ev_join, ctx->aux) != hipSuccess || hipStreamWaitEvent(s, ctx->ev_join, 0) != hipSuccess)
+      rc = LAGS_EHIP;
+  }
   return rc;
 }
 
@@ -483,12 +490,14 @@ int lags_create(lags_ctx** out, int device) {
     const bool want_side = !(side && side[0] == '0' && side[1] == '\0');
     if (g.ok && want_side && hipStreamCreateWithFlags(&c->aux, hipStreamNonBlocking) == hipSuccess) {
       if (hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) != hipSuccess ||
-          hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming) != hipSuccess) {
+          hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming) != hipSuccess ||
+          hipEventCreateWithFlags(&c->ev_side, hipEventDisableTiming) != hipSuccess) {
         if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
         if (c->ev_join) (void)hipEventDestroy(c->ev_join);
+        if (c->ev_side) (void)hipEventDestroy(c->ev_side);
         (void)hipStreamDestroy(c->aux);
         c->aux = nullptr;   // everything then runs on the caller's stream
-        c->ev_fork = c->ev_join = nullptr;
+        c->ev_fork = c->ev_join = c->ev_side = nullptr;
       }
     } else {
       c->aux = nullptr;
@@ -503,6 +512,7 @@ int lags_create(lags_ctx** out, int device) {
         (void)hipStreamDestroy(c->aux);
         (void)hipEventDestroy(c->ev_fork);
         (void)hipEventDestroy(c->ev_join);
+        (void)hipEventDestroy(c->ev_side);
       }
       delete c;
       return g.ok ? LAGS_ENOMEM : LAGS_EHIP;
@@ -524,6 +534,7 @@ int lags_destroy(lags_ctx* ctx) {
     (void)hipStreamDestroy(ctx->aux);
     (void)hipEventDestroy(ctx->ev_fork);
     (void)hipEventDestroy(ctx->ev_join);
+    (void)hipEventDestroy(ctx->ev_side);
   }
   for (auto& kv : ctx->layer_tables) {
     free_table_device(kv.second);

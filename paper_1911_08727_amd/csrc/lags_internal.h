@@ -251,12 +251,14 @@ hipError_t launch_small(int cls, int nseg, const SegDesc* segs, const int32_t* l
 // The large layers' pipeline in two parts, same arguments to both: the threshold guesses
 // (k_prep), then everything that follows them.  chain: also enqueue the multi-pass kernels
 // (rejected guesses then use them instead of the one-workgroup rescue); always true for plans
-// with has_dense.
+// with has_dense.  side (may be null): a second stream on which launch_large may enqueue work
+// that depends only on the streaming pass, after an event `side_ev` that it records on `s`; the
+// caller joins `side` to `s` afterwards.
 hipError_t launch_large_prep(const LargePlan& pl, const Scratch& sc, const SegDesc* segs, const float* grad,
                              const float* res, float lr, bool chain, hipStream_t s, Prof* prof);
 hipError_t launch_large(const LargePlan& pl, const Scratch& sc, const SegDesc* segs, const float* grad,
                         float* res, float lr, int32_t* out_idx, float* out_val, bool chain, hipStream_t s,
-                        Prof* prof);
+                        Prof* prof, hipStream_t side = nullptr, hipEvent_t side_ev = nullptr);
 enum { MERGE_UPDATE = 0, MERGE_APPLY = 1, MERGE_DELTA = 2 };
 
 struct MergePlan {      // device pointers + counts of the merge-type launches

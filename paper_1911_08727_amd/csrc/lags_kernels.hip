@@ -2367,7 +2367,7 @@ hipError_t launch_large_prep(const LargePlan& pl, const Scratch& sc, const SegDe
 
 hipError_t launch_large(const LargePlan& pl, const Scratch& sc, const SegDesc* segs, const float* grad,
                         float* res, float lr, int32_t* out_idx, float* out_val, bool chain, hipStream_t s,
-                        Prof* prof) {
+                        Prof* prof, hipStream_t side, hipEvent_t side_ev) {
   if (pl.n_large <= 0) return hipSuccess;
   if (pl.has_dense) chain = true;
   uint32_t* counters = sc.ghist + (int64_t)pl.n_large * kHistStride;
@@ -2381,22 +2381,32 @@ hipError_t launch_large(const LargePlan& pl, const Scratch& sc, const SegDesc* s
                          pl.tiles + t0, grad, res, lr, sc.lstate, sc.chunk_cnt, sc.slots, pl.slot, sc.ghist);
     }
   }
+  // Two launches share the layers (every workgroup looks at its layer's class and leaves the
+  // other launch's alone).  The small workgroups' layers are finished by that launch alone, so
+  // it can run on the side stream beside the kernels of the layers finished by groups; not when
+  // the multi-pass kernels follow, which read what it appends to their work list.
+  if (pl.n_finish_small > 0) {
+    hipStream_t fs = s;
+    if (side && !chain && pl.n_finish_small < pl.n_large) {
+      if (hipEventRecord(side_ev, s) != hipSuccess || hipStreamWaitEvent(side, side_ev, 0) != hipSuccess)
+        return hipErrorUnknown;
+      fs = side;
+    }
+    ProfScope ps(prof, K_FINISH, fs);
+    hipLaunchKernelGGL(k_finish<256>, dim3(pl.n_large), dim3(256), 0, fs, segs, pl.lsegs, sc.lstate, sc.chunk_cnt,
+                       sc.slots, pl.slot, sc.bh_part, sc.coarse_part, sc.part_info, res, out_idx, out_val, counters,
+                       sc.items, ch, sc.fail_flag);
+  }
   if (pl.n_hparts > 0) {
     ProfScope ps(prof, K_GROUP_H, s);
     hipLaunchKernelGGL(k_group_h, dim3(pl.n_hparts), dim3(1024), 0, s, pl.hparts, pl.lsegs, sc.lstate, sc.chunk_cnt,
                        sc.slots, pl.slot, sc.bh_part, sc.coarse_part, sc.part_info);
   }
-  {
+  if (pl.n_finish_small < pl.n_large) {
     ProfScope ps(prof, K_FINISH, s);
-    // every workgroup of either launch looks at its layer's class and leaves the other launch's alone
-    if (pl.n_finish_small > 0)
-      hipLaunchKernelGGL(k_finish<256>, dim3(pl.n_large), dim3(256), 0, s, segs, pl.lsegs, sc.lstate, sc.chunk_cnt,
-                         sc.slots, pl.slot, sc.bh_part, sc.coarse_part, sc.part_info, res, out_idx, out_val, counters,
-                         sc.items, ch, sc.fail_flag);
-    if (pl.n_finish_small < pl.n_large)
-      hipLaunchKernelGGL(k_finish<1024>, dim3(pl.n_large), dim3(1024), 0, s, segs, pl.lsegs, sc.lstate, sc.chunk_cnt,
-                         sc.slots, pl.slot, sc.bh_part, sc.coarse_part, sc.part_info, res, out_idx, out_val, counters,
-                         sc.items, ch, sc.fail_flag);
+    hipLaunchKernelGGL(k_finish<1024>, dim3(pl.n_large), dim3(1024), 0, s, segs, pl.lsegs, sc.lstate, sc.chunk_cnt,
+                       sc.slots, pl.slot, sc.bh_part, sc.coarse_part, sc.part_info, res, out_idx, out_val, counters,
+                       sc.items, ch, sc.fail_flag);
   }
   if (pl.n_groups > 0) {
     {
