@@ -917,7 +917,9 @@ __global__ __launch_bounds__(NW * 64) void k_stream(const TileDesc* __restrict__
 //   phase B   writes the kept pairs in index order (position = kept entries of the earlier wave
 //             chunks + kept band entries with a smaller index + rank inside the wave chunk) and
 //             zeroes their residual.
-// Layers of up to kFusedTiles tiles do all of it in one workgroup (k_finish).  Larger ones take
+// Layers of up to kFusedTiles tiles (kFusedTilesShared in tables that hold larger layers
+// anyway) do all of it in one workgroup (k_finish; 256 threads up to kFinishSmallTiles tiles,
+// 1024 above).  Larger ones take
 // one launch per step: k_group_h (partial bucket counts per 256 tiles), k_finish (decides),
 // k_group_a over groups of 64 tiles, k_group_p (one workgroup per layer: selects, turns the
 // counts into output positions), k_group_b over the groups again.  Work that every group would
