@@ -1980,21 +1980,26 @@ __global__ __launch_bounds__(256) void k_merge_bounds(const BChunk* __restrict__
 
 // Accumulation shared by the merge-type kernels: the workgroup that owns one tile of the
 // dense layout loads the entries of all workers that fall into the tile (found through the
-// bounds, no searching) and adds them into the LDS tile s_acc in worker order.
+// bounds, no searching) and adds them into the LDS tile s_acc so that every element holds the
+// sum of its entries in worker order.
 // T = float: binary32 adds, the sum the method defines.  T = double: exact-order double sums for
 // the delta metric.
 //
 // Order only matters for an element that three or more workers selected: 0 + a + b is the same
 // binary32 value in either order (0 + x is x, or +0 for x = -0, and the sum of two values is
-// commutative).  So the float accumulation first adds all entries at once (compare-and-swap on
-// the element's bits with a correctly rounded add), while two bitmaps record which elements were
-// hit once and twice; only if some element is hit a third time (about one tile in 200 when the
-// workers together keep 1.6 % of the tile) is the tile redone in worker order, one barrier per
-// worker (inside one worker the indices are distinct).  Tiles with more than kMergeUnorderedMax
-// entries, where third hits are likely, and calls with more than 256 workers go straight to the
-// ordered pass.  s_multi: 2 * kMergeTile / 32 + 1 words (float only).
-// merge_accumulate returns the number of entries that fell into the tile.
-constexpr int kMergeUnorderedMax = 256;
+// commutative).  So the float accumulation adds all entries at once (compare-and-swap on the
+// element's bits with a correctly rounded add), while three bitmaps record which elements were
+// hit once, twice and three times.  The elements hit three times or more (none in most tiles
+// when the workers together keep about 1 % of the layer, a handful when they keep 10 %) are
+// repaired afterwards: their entries are collected in a short LDS list and one thread per such
+// element adds them again in worker order.  Tiles with more than 1024 entries (the entries no
+// longer fit the registers of one pass), a list that overflows, and more than 256 workers take
+// the plain way: one barrier per worker (inside one worker the indices are distinct).
+// s_multi: kMergeMultiWords words (float only).  merge_accumulate returns the number of entries
+// that fell into the tile.
+constexpr int kMergeBitWords = kMergeTile / 32;          // words of one bitmap
+constexpr int kMergeRepairCap = kMergeBitWords;          // list entries: they reuse the first two bitmaps (8 bytes each)
+constexpr int kMergeMultiWords = 3 * kMergeBitWords + 2; // once, twice, thrice, [flag], [list count]
 
 // Entry table of one batch of up to 256 workers for one tile: s_start[q] = number of entries of
 // the workers before q that fall into the tile, s_start[256] = their total (returned), s_lo[q] =
@@ -2022,81 +2027,155 @@ __device__ __forceinline__ uint32_t merge_table(uint32_t* s_start, int32_t* s_lo
   return total;
 }
 
-// Adds the `total` entries of the batch's table into s_acc.  Ends with a barrier.
-template <typename T, bool ORDERED>
-__device__ __forceinline__ void merge_entries(T* s_acc, const uint32_t* s_start, const int32_t* s_lo,
-                                              uint32_t* s_multi, uint32_t total, const TileDesc& td,
-                                              const SegDesc& sd, int p0, int np, const int32_t* __restrict__ idx,
-                                              const float* __restrict__ val, int64_t stride_k) {
+// Entry e of the batch's table: its worker q (-1 if e >= total), offset inside the tile and value.
+__device__ __forceinline__ void merge_entry(uint32_t e, uint32_t total, const uint32_t* s_start, const int32_t* s_lo,
+                                            const TileDesc& td, const SegDesc& sd, int p0, int np,
+                                            const int32_t* __restrict__ idx, const float* __restrict__ val,
+                                            int64_t stride_k, int& q, uint32_t& off, float& v) {
+  q = -1;
+  off = 0xFFFFFFFFu;
+  v = 0.f;
+  if (e < total) {
+    int a = 0, z = np;  // last worker q with s_start[q] <= e (skips workers without entries here)
+    while (a < z) {
+      const int mid = (a + z) >> 1;
+      if (s_start[mid] <= e) a = mid + 1; else z = mid;
+    }
+    q = a - 1;
+    const int64_t gi = (int64_t)(p0 + q) * stride_k + sd.out_offset + s_lo[q] + (int)(e - s_start[q]);
+    off = (uint32_t)(idx[gi] - td.local0);
+    v = val[gi];
+  }
+}
+
+// Adds the `total` entries of the batch's table into s_acc in worker order, one barrier per
+// worker.  Ends with a barrier.
+template <typename T>
+__device__ __forceinline__ void merge_entries_ordered(T* s_acc, const uint32_t* s_start, const int32_t* s_lo,
+                                                      uint32_t total, const TileDesc& td, const SegDesc& sd, int p0,
+                                                      int np, const int32_t* __restrict__ idx,
+                                                      const float* __restrict__ val, int64_t stride_k) {
   const int tid = threadIdx.x;
   for (uint32_t base = 0; base < total; base += 1024) {
     int pe[4];
     uint32_t off[4];
     float v[4];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const uint32_t e = base + (uint32_t)(r * 256 + tid);
-      pe[r] = -1;
-      off[r] = 0xFFFFFFFFu;
-      v[r] = 0.f;
-      if (e < total) {
-        int a = 0, z = np;  // last worker q with s_start[q] <= e (skips workers without entries here)
-        while (a < z) {
-          const int mid = (a + z) >> 1;
-          if (s_start[mid] <= e) a = mid + 1; else z = mid;
-        }
-        const int q = a - 1;
-        const int64_t gi = (int64_t)(p0 + q) * stride_k + sd.out_offset + s_lo[q] + (int)(e - s_start[q]);
-        off[r] = (uint32_t)(idx[gi] - td.local0);
-        v[r] = val[gi];
-        pe[r] = q;
-      }
+    for (int r = 0; r < 4; ++r)
+      merge_entry(base + (uint32_t)(r * 256 + tid), total, s_start, s_lo, td, sd, p0, np, idx, val, stride_k, pe[r],
+                  off[r], v[r]);
+    // workers present in this pass (uniform over the workgroup)
+    int qf, ql;
+    {
+      const uint32_t e0 = base, e1 = (base + 1024 < total ? base + 1024 : total) - 1;
+      int a = 0, z = np;
+      while (a < z) { const int mid = (a + z) >> 1; if (s_start[mid] <= e0) a = mid + 1; else z = mid; }
+      qf = a - 1;
+      a = 0; z = np;
+      while (a < z) { const int mid = (a + z) >> 1; if (s_start[mid] <= e1) a = mid + 1; else z = mid; }
+      ql = a - 1;
     }
-    if constexpr (!ORDERED) {
-      static_assert(sizeof(T) == 4, "the unordered pass is for binary32 sums");
-      uint32_t* once = s_multi;
-      uint32_t* twice = s_multi + kMergeTile / 32;
+    for (int q = qf; q <= ql; ++q) {
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        if (pe[r] >= 0 && off[r] < (uint32_t)td.n) {
-          const uint32_t bit = 1u << (off[r] & 31u), wd = off[r] >> 5;
-          if (atomicOr(&once[wd], bit) & bit)
-            if (atomicOr(&twice[wd], bit) & bit) s_multi[2 * (kMergeTile / 32)] = 1u;  // a third hit
-          uint32_t* cell = reinterpret_cast<uint32_t*>(&s_acc[off[r]]);
-          uint32_t seen = *cell;
-          for (;;) {  // ends: a failed swap means another entry's swap succeeded
-            const uint32_t want = __float_as_uint(__fadd_rn(__uint_as_float(seen), v[r]));
-            const uint32_t got = atomicCAS(cell, seen, want);
-            if (got == seen) break;
-            seen = got;
-          }
+        if (pe[r] == q && off[r] < (uint32_t)td.n) {
+          if (sizeof(T) == 4) s_acc[off[r]] = (T)__fadd_rn((float)s_acc[off[r]], v[r]);
+          else s_acc[off[r]] = s_acc[off[r]] + (T)v[r];
         }
       }
-    } else {
-      // workers present in this pass (uniform over the workgroup)
-      int qf, ql;
-      {
-        const uint32_t e0 = base, e1 = (base + 1024 < total ? base + 1024 : total) - 1;
-        int a = 0, z = np;
-        while (a < z) { const int mid = (a + z) >> 1; if (s_start[mid] <= e0) a = mid + 1; else z = mid; }
-        qf = a - 1;
-        a = 0; z = np;
-        while (a < z) { const int mid = (a + z) >> 1; if (s_start[mid] <= e1) a = mid + 1; else z = mid; }
-        ql = a - 1;
-      }
-      for (int q = qf; q <= ql; ++q) {
+      __syncthreads();
+    }
+  }
+  __syncthreads();
+}
+
+// The unordered accumulation of a tile with at most 1024 entries (four per thread, which stay
+// in registers for the repair).  All entries are added at once; then the elements whose bit is
+// set in `thrice` get the sum of their entries in worker order: their entries are collected
+// (key = offset | worker << 16, value) in the space of the first two bitmaps, and the thread that
+// holds an element's first entry adds the element's entries by increasing worker.  Returns false
+// (uniform; s_acc is then to be cleared and filled the ordered way) if there are more than
+// kMergeRepairCap such entries.  Ends with a barrier.
+__device__ __forceinline__ bool merge_entries_unordered(float* s_acc, const uint32_t* s_start, const int32_t* s_lo,
+                                                        uint32_t* s_multi, uint32_t total, const TileDesc& td,
+                                                        const SegDesc& sd, int np, const int32_t* __restrict__ idx,
+                                                        const float* __restrict__ val, int64_t stride_k) {
+  static_assert(kMergeTile <= 65536 && 2 * kMergeBitWords >= 2 * kMergeRepairCap, "key packing; the list fits");
+  const int tid = threadIdx.x;
+  uint32_t* once = s_multi;
+  uint32_t* twice = s_multi + kMergeBitWords;
+  uint32_t* thrice = s_multi + 2 * kMergeBitWords;
+  uint32_t* flag = s_multi + 3 * kMergeBitWords;
+  uint32_t* count = flag + 1;
+  int pe[4];
+  uint32_t off[4];
+  float v[4];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          if (pe[r] == q && off[r] < (uint32_t)td.n) {
-            if (sizeof(T) == 4) s_acc[off[r]] = (T)__fadd_rn((float)s_acc[off[r]], v[r]);
-            else s_acc[off[r]] = s_acc[off[r]] + (T)v[r];
-          }
+  for (int r = 0; r < 4; ++r)
+    merge_entry((uint32_t)(r * 256 + tid), total, s_start, s_lo, td, sd, 0, np, idx, val, stride_k, pe[r], off[r],
+                v[r]);
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    if (pe[r] >= 0 && off[r] < (uint32_t)td.n) {
+      const uint32_t bit = 1u << (off[r] & 31u), wd = off[r] >> 5;
+      if (atomicOr(&once[wd], bit) & bit)
+        if (atomicOr(&twice[wd], bit) & bit) {
+          atomicOr(&thrice[wd], bit);
+          *flag = 1u;  // some element needs the repair
         }
-        __syncthreads();
+      uint32_t* cell = reinterpret_cast<uint32_t*>(&s_acc[off[r]]);
+      uint32_t seen = *cell;
+      for (;;) {  // ends: a failed swap means another entry's swap succeeded
+        const uint32_t want = __float_as_uint(__fadd_rn(__uint_as_float(seen), v[r]));
+        const uint32_t got = atomicCAS(cell, seen, want);
+        if (got == seen) break;
+        seen = got;
       }
     }
   }
   __syncthreads();
+  if (*flag == 0u) return true;  // uniform
+  bool listed[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r)
+    listed[r] = pe[r] >= 0 && off[r] < (uint32_t)td.n && ((thrice[off[r] >> 5] >> (off[r] & 31u)) & 1u);
+  __syncthreads();  // everybody has read `thrice` and the other bitmaps are dead: their space becomes the list
+  uint32_t* lkey = s_multi;                                              // kMergeRepairCap words
+  float* lval = reinterpret_cast<float*>(s_multi + kMergeRepairCap);     // kMergeRepairCap words
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    if (listed[r]) {
+      const uint32_t at = atomicAdd(count, 1u);
+      if (at < (uint32_t)kMergeRepairCap) {
+        lkey[at] = off[r] | ((uint32_t)pe[r] << 16);
+        lval[at] = v[r];
+      }
+    }
+  }
+  __syncthreads();
+  const uint32_t n = *count;
+  if (n > (uint32_t)kMergeRepairCap) return false;
+  for (uint32_t i = tid; i < n; i += 256) {
+    const uint32_t mine = lkey[i], o = mine & 0xFFFFu;
+    bool first = true;
+    for (uint32_t j = 0; j < n; ++j) first = first && !((lkey[j] & 0xFFFFu) == o && lkey[j] < mine);
+    if (!first) continue;
+    float sum = 0.0f;
+    uint32_t last = 0u;  // keys of this element taken so far are below `last`
+    for (;;) {
+      uint32_t best = 0xFFFFFFFFu, bj = 0u;
+      for (uint32_t j = 0; j < n; ++j) {
+        const uint32_t kj = lkey[j];
+        if ((kj & 0xFFFFu) == o && kj >= last && kj < best) { best = kj; bj = j; }
+      }
+      if (best == 0xFFFFFFFFu) break;
+      sum = __fadd_rn(sum, lval[bj]);
+      last = best + 0x10000u;  // the next worker's key at the earliest (worker numbers are below 256)
+    }
+    s_acc[o] = sum;
+  }
+  __syncthreads();
+  return true;
 }
 
 template <typename T>
@@ -2108,17 +2187,15 @@ __device__ __forceinline__ uint32_t merge_accumulate(T* s_acc, uint32_t* s_start
   const int tid = threadIdx.x;
   for (int i = tid; i < kMergeTile; i += 256) s_acc[i] = (T)0;
   if constexpr (sizeof(T) == 4) {
-    if (P <= 256) {  // one batch of workers: its table shows the tile's whole entry count
-      for (int i = tid; i < 2 * (kMergeTile / 32) + 1; i += 256) s_multi[i] = 0u;
+    if (P <= 256) {  // one batch of workers
+      for (int i = tid; i < kMergeMultiWords; i += 256) s_multi[i] = 0u;
       const uint32_t total = merge_table(s_start, s_lo, s_wt, sd.k, slot, 0, P, P, bounds);
-      if (total <= (uint32_t)kMergeUnorderedMax) {  // uniform over the workgroup
-        merge_entries<T, false>(s_acc, s_start, s_lo, s_multi, total, td, sd, 0, P, idx, val, stride_k);
-        if (s_multi[2 * (kMergeTile / 32)] == 0u) return total;
-        __syncthreads();
+      if (total <= 1024u) {  // uniform over the workgroup
+        if (merge_entries_unordered(s_acc, s_start, s_lo, s_multi, total, td, sd, P, idx, val, stride_k)) return total;
         for (int i = tid; i < kMergeTile; i += 256) s_acc[i] = (T)0;
         __syncthreads();
       }
-      merge_entries<T, true>(s_acc, s_start, s_lo, s_multi, total, td, sd, 0, P, idx, val, stride_k);
+      merge_entries_ordered<T>(s_acc, s_start, s_lo, total, td, sd, 0, P, idx, val, stride_k);
       return total;
     }
   }
@@ -2128,7 +2205,7 @@ __device__ __forceinline__ uint32_t merge_accumulate(T* s_acc, uint32_t* s_start
     const int np = P - p0 < 256 ? P - p0 : 256;
     const uint32_t total = merge_table(s_start, s_lo, s_wt, sd.k, slot, p0, np, P, bounds);
     entries += total;
-    merge_entries<T, true>(s_acc, s_start, s_lo, s_multi, total, td, sd, p0, np, idx, val, stride_k);
+    merge_entries_ordered<T>(s_acc, s_start, s_lo, total, td, sd, p0, np, idx, val, stride_k);
   }
   return entries;
 }
@@ -2149,7 +2226,7 @@ __global__ __launch_bounds__(256) void k_merge(const MTile* __restrict__ mtiles,
   __shared__ int32_t s_lo[256];
   __shared__ uint32_t s_wt[4];
   __shared__ uint32_t s_claim[APPLY ? kMergeTile / 32 : 1];
-  __shared__ uint32_t s_multi[2 * (kMergeTile / 32) + 1];
+  __shared__ uint32_t s_multi[kMergeMultiWords];
   const MTile mt = mtiles[blockIdx.x];  // one read: the tile and what the kernel needs of its layer
   TileDesc td;
   td.start = mt.start; td.n = mt.n; td.seg = mt.seg; td.local0 = mt.local0; td.ctile = -1;
