@@ -206,6 +206,41 @@ def layer_sweep(torch, lags, job, reps=10):
             "median_us": round(statistics.median(us for _, us in rows), 1)}
 
 
+def graph_step_ms(torch, lags, workloads, w, grad_pool, res_pool, dev, reps=50):
+    """One step (batched sparsify + merge) of a small table recorded into a HIP graph, in a context
+    of its own after warm-up calls have sized its scratch, and replayed back to back: milliseconds
+    per replay.  The recorded step reads the first gradient iteration every time; the residuals evolve."""
+    ctx = lags.Context(0)
+    j = Job(torch, lags, workloads, ctx, w, w.P, grad_pool, res_pool, dev)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        j.stream = side
+        j.step()
+        j.step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        j.stream = torch.cuda.current_stream()
+        j.n_steps = 0
+        j.step()
+    torch.cuda.synchronize()
+    for _ in range(3):
+        graph.replay()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        graph.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    del graph
+    j.close()
+    ctx.destroy()
+    return ms
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -448,6 +483,10 @@ def main():
                         "sum_k_per_worker": j.K, "elements_by_route": j.routes()})
             configs["%s (config densities)" % w.name] = row
             j.close()
+            if row["ms_per_step"] < 0.3:
+                # a step this short is a handful of launches: what it costs without the host's launch calls
+                row["graph_replay_ms_per_step"] = round(graph_step_ms(torch, lags, workloads, w, grad_pool,
+                                                                      res_pool, dev), 4)
         out["configs"] = configs
     else:
         job.close()
