@@ -114,6 +114,8 @@ struct lags_table {
   GroupDesc* d_groups = nullptr;
   GroupDesc* d_hparts = nullptr;
   int32_t* d_multi = nullptr;
+  int32_t* d_fin_small = nullptr;
+  int32_t* d_fin_other = nullptr;
   MTile* d_mtiles = nullptr;
   BChunk* d_bchunks = nullptr;
   int32_t* d_seg_mtile0 = nullptr;
@@ -215,6 +217,8 @@ void free_table_device(lags_table* t) {
   if (t->d_groups) (void)hipFree(t->d_groups);
   if (t->d_hparts) (void)hipFree(t->d_hparts);
   if (t->d_multi) (void)hipFree(t->d_multi);
+  if (t->d_fin_small) (void)hipFree(t->d_fin_small);
+  if (t->d_fin_other) (void)hipFree(t->d_fin_other);
   if (t->d_mtiles) (void)hipFree(t->d_mtiles);
   if (t->d_bchunks) (void)hipFree(t->d_bchunks);
   if (t->d_seg_mtile0) (void)hipFree(t->d_seg_mtile0);
@@ -354,10 +358,13 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
   pl.n_groups = (int)groups.size();
   pl.n_multi = (int)multi.size();
   pl.n_hparts = (int)hparts.size();
-  for (const LargeSeg& ls : t->lsegs) {
+  std::vector<int32_t> fin_small, fin_other;
+  for (size_t li = 0; li < t->lsegs.size(); ++li) {
+    const LargeSeg& ls = t->lsegs[li];
     pl.n_sampled += ls.sampled;
-    pl.n_finish_small += finish_small(ls) ? 1 : 0;
+    (finish_small(ls) ? fin_small : fin_other).push_back((int32_t)li);
   }
+  pl.n_finish_small = (int)fin_small.size();
   // candidates cluster (e.g. the few non-zero rows of an embedding gradient), so a tile may
   // hold several times the layer's average: the slots leave a factor 8 where they can
   pl.slot = plan_slots(max_per_tile);
@@ -369,6 +376,8 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
   if (rc == LAGS_OK) rc = upload(&t->d_groups, groups);
   if (rc == LAGS_OK) rc = upload(&t->d_hparts, hparts);
   if (rc == LAGS_OK) rc = upload(&t->d_multi, multi);
+  if (rc == LAGS_OK) rc = upload(&t->d_fin_small, fin_small);
+  if (rc == LAGS_OK) rc = upload(&t->d_fin_other, fin_other);
   if (rc == LAGS_OK) rc = upload(&t->d_mtiles, mtiles);
   if (rc == LAGS_OK) rc = upload(&t->d_bchunks, bchunks);
   if (rc == LAGS_OK) rc = upload(&t->d_seg_mtile0, seg_mtile0);
@@ -380,6 +389,8 @@ int build_table(lags_ctx* ctx, const std::vector<int64_t>& off, const std::vecto
   pl.groups = t->d_groups;
   pl.hparts = t->d_hparts;
   pl.multi = t->d_multi;
+  pl.fin_small = t->d_fin_small;
+  pl.fin_other = t->d_fin_other;
   if (pl.n_large > 0) {
     std::vector<void*>* rl = ctx->retire_list();
     const size_t nl = (size_t)pl.n_large;

@@ -184,6 +184,8 @@ struct LargePlan {      // everything launch_large needs (device pointers + coun
   const GroupDesc* groups = nullptr;    // groups of the layers with fused == 0
   const GroupDesc* hparts = nullptr;    // parts of their bucket counts
   const int32_t* multi = nullptr;       // large-layer indices of those layers
+  const int32_t* fin_small = nullptr;   // large-layer indices that k_finish<256> takes (n_finish_small)
+  const int32_t* fin_other = nullptr;   // ... and the others (n_large - n_finish_small), for k_finish<1024>
 };
 
 struct Scratch {        // context-owned device memory, contents meaningless between calls

@@ -1370,12 +1370,13 @@ __device__ __forceinline__ bool wave_find_rank64(uint32_t c, uint32_t rank, int 
 // One workgroup per large layer.  Layers that are not sampled hand their tiles to the
 // multi-pass kernels.  Sampled layers get their verdict and decisive bucket; those of at most
 // kFusedTiles tiles are finished here, the others by k_group_a and k_group_b.
-// Two launches share the layers: workgroups of 256 threads take the sampled layers of at most
-// kFinishSmallTiles tiles, workgroups of 1024 threads all others.  What a layer of a few wave
-// chunks costs is the workgroup-wide scans and searches, which every wave executes; a quarter
-// of the waves issues a quarter of those instructions.
+// Two launches share the layers (`list` holds the launch's large-layer indices): workgroups of
+// 256 threads take the sampled layers of at most kFinishSmallTiles tiles that one workgroup
+// finishes, workgroups of 1024 threads all others.  A CU holds six of the small workgroups side
+// by side, against two of the large ones.
 template <int NT>
-__global__ __launch_bounds__(NT) void k_finish(const SegDesc* __restrict__ segs,
+__global__ __launch_bounds__(NT) void k_finish(const int32_t* __restrict__ list,
+                                               const SegDesc* __restrict__ segs,
                                                  const LargeSeg* __restrict__ lsegs,
                                                  LState* __restrict__ lstate,
                                                  const uint32_t* __restrict__ chunk_cnt,
@@ -1404,9 +1405,9 @@ __global__ __launch_bounds__(NT) void k_finish(const SegDesc* __restrict__ segs,
   __shared__ uint32_t s_nband;
   __shared__ uint32_t s_wgt[kMaxWc];
   static_assert(kFineBins >= kBins0, "the rescue's histogram fits");
-  const int li = blockIdx.x, tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
+  const int li = list[blockIdx.x], tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
   const LargeSeg ls = lsegs[li];
-  if (finish_small(ls) != (NT == 256)) return;  // the other launch's layer
+  if (finish_small(ls) != (NT == 256)) return;  // never: the host's lists follow the same rule
   const SegDesc sd = segs[ls.seg];
   if (!ls.sampled) {  // uniform over the workgroup
     append_tiles<NT>(ls, counter, items, s_sel);
@@ -2460,10 +2461,10 @@ hipError_t launch_large(const LargePlan& pl, const Scratch& sc, const SegDesc* s
                          pl.tiles + t0, grad, res, lr, sc.lstate, sc.chunk_cnt, sc.slots, pl.slot, sc.ghist);
     }
   }
-  // Two launches share the layers (every workgroup looks at its layer's class and leaves the
-  // other launch's alone).  The small workgroups' layers are finished by that launch alone, so
-  // it can run on the side stream beside the kernels of the layers finished by groups; not when
-  // the multi-pass kernels follow, which read what it appends to their work list.
+  // Two launches share the layers (a list of layer indices each).  The small workgroups' layers
+  // are finished by that launch alone, so it can run on the side stream beside the kernels of the
+  // layers finished by groups; not when the multi-pass kernels follow, which read what it
+  // appends to their work list.
   if (pl.n_finish_small > 0) {
     hipStream_t fs = s;
     if (side && !chain && pl.n_finish_small < pl.n_large) {
@@ -2472,7 +2473,7 @@ hipError_t launch_large(const LargePlan& pl, const Scratch& sc, const SegDesc* s
       fs = side;
     }
     ProfScope ps(prof, K_FINISH, fs);
-    hipLaunchKernelGGL(k_finish<256>, dim3(pl.n_large), dim3(256), 0, fs, segs, pl.lsegs, sc.lstate, sc.chunk_cnt,
+    hipLaunchKernelGGL(k_finish<256>, dim3(pl.n_finish_small), dim3(256), 0, fs, pl.fin_small, segs, pl.lsegs, sc.lstate, sc.chunk_cnt,
                        sc.slots, pl.slot, sc.bh_part, sc.coarse_part, sc.part_info, res, out_idx, out_val, counters,
                        sc.items, ch, sc.fail_flag);
   }
@@ -2483,7 +2484,7 @@ hipError_t launch_large(const LargePlan& pl, const Scratch& sc, const SegDesc* s
   }
   if (pl.n_finish_small < pl.n_large) {
     ProfScope ps(prof, K_FINISH, s);
-    hipLaunchKernelGGL(k_finish<1024>, dim3(pl.n_large), dim3(1024), 0, s, segs, pl.lsegs, sc.lstate, sc.chunk_cnt,
+    hipLaunchKernelGGL(k_finish<1024>, dim3(pl.n_large - pl.n_finish_small), dim3(1024), 0, s, pl.fin_other, segs, pl.lsegs, sc.lstate, sc.chunk_cnt,
                        sc.slots, pl.slot, sc.bh_part, sc.coarse_part, sc.part_info, res, out_idx, out_val, counters,
                        sc.items, ch, sc.fail_flag);
   }

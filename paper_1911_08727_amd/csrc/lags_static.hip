@@ -233,6 +233,8 @@ int lags_sparsify_layer_noalloc(int device, const float* grad, float* residual, 
   pl.groups = reinterpret_cast<const GroupDesc*>(base + kLayout.groups);
   pl.hparts = reinterpret_cast<const GroupDesc*>(base + kLayout.hparts);
   pl.multi = reinterpret_cast<const int32_t*>(base + kLayout.multi);
+  pl.fin_small = pl.multi;  // the one large layer, index 0, is in one of the two lists
+  pl.fin_other = pl.multi;
   Scratch sc;
   sc.lstate = reinterpret_cast<LState*>(base + kLayout.lstate);
   sc.chunk_cnt = reinterpret_cast<uint32_t*>(base + kLayout.chunk_cnt);
