@@ -5,10 +5,9 @@
 //   emit (index, acc) ascending; residual = acc with kept entries zeroed;
 //   merge: update = (sum_p kept_p) / P.
 //
-// Selection is an exact radix select on key = bits(acc) & 0x7fffffff, digits of
-// 11 + 10 + 10 bits from the top, with LDS histograms.  The k-th largest key T and the
-// number r of entries equal to T that are still to be taken define the kept set:
-// key > T, or key == T and fewer than r equal keys precede it in index order.
+// The order is that of key = bits(acc) & 0x7fffffff.  The k-th entry in the order (key
+// descending, index ascending) fixes the kept set: key above its key T, or key == T and an index
+// up to its index (equivalently: the first r entries equal to T in index order).
 //
 // Work layout: a wave owns a contiguous chunk of V*256 elements and walks it in V
 // rounds; in a round lane i holds the 4 consecutive elements (round*256 + 4*i ..+3),
@@ -17,17 +16,18 @@
 // (and over tiles for multi-block layers) and a wave prefix scan per round.
 //
 // Three routes, chosen per layer by size:
-//   small  (d <= 40960): one workgroup, acc stays in registers between the single read of
-//          grad/residual and the single write of the residual.
-//   large, sampled: a sample of 16384 (65536) elements gives a threshold tau that, with high
-//          probability, admits slightly more than k entries.  One streaming pass writes acc
-//          into the residual buffer, collects every entry with key >= tau (in index order)
-//          into per-tile slots and counts them in buckets of the key range just above tau.
-//          If at least k were collected and no tile overflowed, the exact top k are among
+//   small  (d <= 8192): one workgroup, acc stays in registers between the single read of
+//          grad/residual and the single write of the residual; exact select over linear bins
+//          (k <= 256) or an exact radix select, digits of 11 + 10 + 10 key bits, LDS histograms.
+//   large, sampled: a sample of 4096 or 16384 elements gives a threshold tau that, with high
+//          probability, admits somewhat more than k entries.  One streaming pass writes acc
+//          into the residual buffer and collects every entry with key >= tau (in index order)
+//          into per-tile slots.  The finish counts them in buckets of the key range just above
+//          tau.  If at least k were collected and no tile overflowed, the exact top k are among
 //          them: the bucket counts name the bucket that holds the k-th largest key, its few
 //          entries are ranked exactly, and one more pass over the slots emits the kept pairs.
 //          The guess never changes the result: it is verified by the counts.
-//   large, multi-pass: radix select over the acc values in the residual buffer, multi-block
+//   large, multi-pass: the radix select over the acc values in the residual buffer, multi-block
 //          (layers too dense to sample; rejected guesses).
 #include "lags_internal.h"
 
